@@ -1,0 +1,203 @@
+"""Python binding of libsilenzio_pbs (batched TFHE PBS + LWE keyswitch on MI355X / gfx950).
+
+Argument marshalling only: every step runs in the HIP kernels of the shared library.  PyTorch is
+used for device memory and streams.  The functions mirror the C ABI in include/silenzio_pbs.h
+one to one.  There is no CPU fallback: if the library is missing and cannot be built, importing
+a function raises.
+"""
+from __future__ import annotations
+
+import ctypes
+import os
+
+import numpy as np
+
+_HERE = os.path.dirname(os.path.abspath(__file__))
+LIB_PATH = os.path.join(_HERE, "libsilenzio_pbs.so")
+
+SLZ_OPT_FORCE_GENERIC = 1
+
+
+class SlzParams(ctypes.Structure):
+    _fields_ = [(f, ctypes.c_uint32) for f in
+                ("n", "k", "N", "pbs_base_log", "pbs_level", "ks_base_log", "ks_level", "msg_bits")]
+
+
+class SlzError(RuntimeError):
+    def __init__(self, code: int, where: str):
+        self.code = code
+        super().__init__("%s failed: %s (%d)" % (where, lib().slz_strerror(code).decode(), code))
+
+
+_lib = None
+
+EXPORTS = ("slz_ctx_create", "slz_ctx_destroy", "slz_ctx_set_option", "slz_lut_encode", "slz_bsk_prepare",
+           "slz_pbs_batch", "slz_blind_rotate_batch", "slz_keyswitch_batch", "slz_lwe_lincomb_batch",
+           "slz_pbs_path", "slz_strerror")
+
+
+def lib():
+    """Loads the built library (building it first only if no built library exists)."""
+    global _lib
+    if _lib is None:
+        if not os.path.exists(LIB_PATH):
+            from . import build as _build
+            _build.build()
+        L = ctypes.CDLL(LIB_PATH)
+        vp, u32, sz = ctypes.c_void_p, ctypes.c_uint32, ctypes.c_size_t
+        L.slz_ctx_create.argtypes = [ctypes.POINTER(SlzParams), u32, ctypes.POINTER(vp)]
+        L.slz_ctx_destroy.argtypes = [vp]
+        L.slz_ctx_set_option.argtypes = [vp, ctypes.c_int, ctypes.c_int]
+        L.slz_lut_encode.argtypes = [ctypes.POINTER(SlzParams), vp, u32, vp]
+        L.slz_bsk_prepare.argtypes = [vp, vp, vp, ctypes.POINTER(sz), vp]
+        L.slz_pbs_batch.argtypes = [vp, vp, vp, vp, u32, vp, vp, u32, vp]
+        L.slz_blind_rotate_batch.argtypes = [vp, vp, vp, vp, u32, vp, u32, vp, u32, vp]
+        L.slz_keyswitch_batch.argtypes = [vp, vp, vp, vp, u32, vp]
+        L.slz_lwe_lincomb_batch.argtypes = [vp, vp, vp, vp, u32, u32, u32, vp]
+        L.slz_pbs_path.argtypes = [vp]
+        L.slz_pbs_path.restype = ctypes.c_char_p
+        L.slz_strerror.argtypes = [ctypes.c_int]
+        L.slz_strerror.restype = ctypes.c_char_p
+        for name in EXPORTS:
+            if name not in ("slz_pbs_path", "slz_strerror"):
+                getattr(L, name).restype = ctypes.c_int
+        _lib = L
+    return _lib
+
+
+def make_params(p) -> SlzParams:
+    """From any object with the fields n, k, N, pbs_base_log, pbs_level, ks_base_log, ks_level, msg_bits."""
+    return SlzParams(p.n, p.k, p.N, p.pbs_base_log, p.pbs_level, p.ks_base_log, p.ks_level, p.msg_bits)
+
+
+def _check(rc: int, where: str):
+    if rc != 0:
+        raise SlzError(rc, where)
+
+
+def _stream() -> int:
+    import torch
+    return torch.cuda.current_stream().cuda_stream
+
+
+def _dev_u64(t, what: str) -> int:
+    """Device address of a contiguous int64/uint64 CUDA tensor (the bits are the u64 words)."""
+    import torch
+    if not t.is_cuda or not t.is_contiguous() or t.dtype not in (torch.int64, torch.uint64, torch.float64):
+        raise TypeError("%s: need a contiguous 64-bit CUDA tensor" % what)
+    return t.data_ptr()
+
+
+def to_device_u64(a: np.ndarray):
+    """numpy uint64 array -> CUDA int64 tensor with the same bits."""
+    import torch
+    return torch.from_numpy(np.ascontiguousarray(a, dtype=np.uint64).view(np.int64)).cuda()
+
+
+def to_host_u64(t) -> np.ndarray:
+    return t.cpu().numpy().view(np.uint64)
+
+
+def lut_encode(p, tables: np.ndarray) -> np.ndarray:
+    """slz_lut_encode: tables u64 [n_tables][t] (host) -> LUT polynomials u64 [n_tables][N] (host)."""
+    cp = make_params(p)
+    tables = np.ascontiguousarray(tables, dtype=np.uint64).reshape(-1, 1 << p.msg_bits)
+    out = np.empty((tables.shape[0], p.N), dtype=np.uint64)
+    _check(lib().slz_lut_encode(ctypes.byref(cp), tables.ctypes.data, tables.shape[0], out.ctypes.data), "slz_lut_encode")
+    return out
+
+
+class Context:
+    """slz_ctx wrapper.  Owns the context handle; tensors passed in stay owned by the caller."""
+
+    def __init__(self, p, max_batch: int):
+        self.p = p
+        self.cp = make_params(p)
+        self.max_batch = int(max_batch)
+        self._h = ctypes.c_void_p()
+        _check(lib().slz_ctx_create(ctypes.byref(self.cp), self.max_batch, ctypes.byref(self._h)), "slz_ctx_create")
+
+    def close(self):
+        if self._h:
+            lib().slz_ctx_destroy(self._h)
+            self._h = ctypes.c_void_p()
+
+    def __del__(self):
+        try:
+            self.close()
+        except Exception:
+            pass
+
+    @property
+    def path(self) -> str:
+        return lib().slz_pbs_path(self._h).decode()
+
+    def set_option(self, option: int, value: int):
+        _check(lib().slz_ctx_set_option(self._h, option, value), "slz_ctx_set_option")
+
+    def bsk_prepared_bytes(self) -> int:
+        need = ctypes.c_size_t(0)
+        _check(lib().slz_bsk_prepare(self._h, None, None, ctypes.byref(need), None), "slz_bsk_prepare(size)")
+        return need.value
+
+    def bsk_prepare(self, bsk_dev):
+        """Standard-domain BSK (CUDA tensor, u64 bits) -> prepared key (CUDA float64 tensor, library-private layout)."""
+        import torch
+        need = self.bsk_prepared_bytes()
+        dst = torch.empty(need // 8, dtype=torch.float64, device=bsk_dev.device)
+        nb = ctypes.c_size_t(need)
+        _check(lib().slz_bsk_prepare(self._h, _dev_u64(bsk_dev, "bsk"), dst.data_ptr(), ctypes.byref(nb), _stream()),
+               "slz_bsk_prepare")
+        return dst
+
+    def _lut_args(self, luts_dev, lut_idx_dev):
+        import torch
+        n_luts = luts_dev.numel() // self.p.N
+        idx_ptr = None
+        if lut_idx_dev is not None:
+            if lut_idx_dev.dtype != torch.int32 or not lut_idx_dev.is_cuda or not lut_idx_dev.is_contiguous():
+                raise TypeError("lut_idx: need a contiguous int32 CUDA tensor")
+            idx_ptr = lut_idx_dev.data_ptr()
+        return n_luts, idx_ptr
+
+    def pbs_batch(self, lwe_in, luts, lut_idx, bsk_prepared, out=None):
+        import torch
+        batch = lwe_in.shape[0]
+        if out is None:
+            out = torch.empty((batch, self.p.k * self.p.N + 1), dtype=torch.int64, device=lwe_in.device)
+        n_luts, idx_ptr = self._lut_args(luts, lut_idx)
+        _check(lib().slz_pbs_batch(self._h, _dev_u64(lwe_in, "lwe_in"), _dev_u64(luts, "luts"), idx_ptr, n_luts,
+                                   bsk_prepared.data_ptr(), _dev_u64(out, "out"), batch, _stream()), "slz_pbs_batch")
+        return out
+
+    def blind_rotate_batch(self, lwe_in, luts, lut_idx, bsk_prepared, n_steps: int, out=None):
+        import torch
+        batch = lwe_in.shape[0]
+        if out is None:
+            out = torch.empty((batch, self.p.k + 1, self.p.N), dtype=torch.int64, device=lwe_in.device)
+        n_luts, idx_ptr = self._lut_args(luts, lut_idx)
+        _check(lib().slz_blind_rotate_batch(self._h, _dev_u64(lwe_in, "lwe_in"), _dev_u64(luts, "luts"), idx_ptr, n_luts,
+                                            bsk_prepared.data_ptr(), int(n_steps), _dev_u64(out, "out"), batch, _stream()),
+               "slz_blind_rotate_batch")
+        return out
+
+    def keyswitch_batch(self, lwe_in, ksk, out=None):
+        import torch
+        batch = lwe_in.shape[0]
+        if out is None:
+            out = torch.empty((batch, self.p.n + 1), dtype=torch.int64, device=lwe_in.device)
+        _check(lib().slz_keyswitch_batch(self._h, _dev_u64(lwe_in, "lwe_in"), _dev_u64(ksk, "ksk"), _dev_u64(out, "out"),
+                                         batch, _stream()), "slz_keyswitch_batch")
+        return out
+
+    def lwe_lincomb_batch(self, cts, w, out=None):
+        import torch
+        G, J, width = cts.shape
+        O = w.shape[1]
+        if w.dtype != torch.int32 or not w.is_cuda or not w.is_contiguous():
+            raise TypeError("w: need a contiguous int32 CUDA tensor")
+        if out is None:
+            out = torch.empty((G, O, width), dtype=torch.int64, device=cts.device)
+        _check(lib().slz_lwe_lincomb_batch(self._h, _dev_u64(cts, "cts"), w.data_ptr(), _dev_u64(out, "out"), G, J, O,
+                                           _stream()), "slz_lwe_lincomb_batch")
+        return out

@@ -1,0 +1,187 @@
+// C-ABI entry points of libsilenzio_pbs: argument checks, path selection, scratch ownership.
+#include "slz_internal.h"
+#include <new>
+#include <cstring>
+
+static bool is_pow2(uint32_t v) { return v && !(v & (v - 1)); }
+
+static int check_params(const slz_params *p) {
+    if (!p) return SLZ_E_INVALID_ARG;
+    if (p->n == 0 || p->k == 0 || !is_pow2(p->N) || p->N < 2) return SLZ_E_INVALID_ARG;
+    if (p->pbs_base_log == 0 || p->pbs_level == 0 || p->pbs_base_log * p->pbs_level > 64) return SLZ_E_INVALID_ARG;
+    if (p->ks_base_log == 0 || p->ks_level == 0 || p->ks_base_log * p->ks_level > 64) return SLZ_E_INVALID_ARG;
+    if (p->msg_bits == 0 || p->msg_bits > 62) return SLZ_E_INVALID_ARG;
+    return SLZ_OK;
+}
+
+static bool misaligned(const void *p) { return ((uintptr_t)p & 15u) != 0; }
+
+extern "C" int slz_ctx_create(const slz_params *params, uint32_t max_batch, slz_ctx **out) {
+    if (!out) return SLZ_E_INVALID_ARG;
+    *out = nullptr;
+    int rc = check_params(params);
+    if (rc != SLZ_OK) return rc;
+    if (max_batch == 0) return SLZ_E_INVALID_ARG;
+    uint32_t logN = 0;
+    while ((1u << logN) < params->N) logN++;
+    if (logN > SLZ_MAX_LOGN) return SLZ_E_UNSUPPORTED;
+    if (params->pbs_base_log > 30) return SLZ_E_UNSUPPORTED;
+    // Exactness: the integer sum of (k+1) l N products digit * key word is below
+    // (k+1) l N 2^(beta-1) 2^63; it must stay below p1 p2 / 4 (about 2^97.99) for the CRT lift.
+    {
+        long double bound = (long double)(params->k + 1) * params->pbs_level * params->N;
+        bound *= (long double)(1ull << (params->pbs_base_log - 1));
+        bound *= 9223372036854775808.0L;                          // 2^63
+        long double M = (long double)SLZ_P1 * (long double)SLZ_P2;
+        if (4.0L * bound > M) return SLZ_E_UNSUPPORTED;
+    }
+    slz_ctx *ctx = new (std::nothrow) slz_ctx;
+    if (!ctx) return SLZ_E_NOMEM;
+    std::memset(ctx, 0, sizeof(*ctx));
+    ctx->prm = *params;
+    ctx->max_batch = max_batch;
+    ctx->logN = logN;
+    if (hipGetDevice(&ctx->device) != hipSuccess) { delete ctx; return SLZ_E_HIP; }
+    rc = slz_build_tables(ctx);
+    if (rc == SLZ_OK && slz_fused_supported(params)) {
+        rc = slz_fused_init(ctx);
+        ctx->has_fused = (rc == SLZ_OK);
+    }
+    if (rc != SLZ_OK) { slz_ctx_destroy(ctx); return rc; }
+    *out = ctx;
+    return SLZ_OK;
+}
+
+extern "C" int slz_ctx_destroy(slz_ctx *ctx) {
+    if (!ctx) return SLZ_E_INVALID_ARG;
+    slz_fused_destroy(ctx);
+    slz_free_tables(ctx);
+    if (ctx->acc) (void)hipFree(ctx->acc);
+    if (ctx->dig) (void)hipFree(ctx->dig);
+    if (ctx->xhat) (void)hipFree(ctx->xhat);
+    if (ctx->outhat) (void)hipFree(ctx->outhat);
+    delete ctx;
+    return SLZ_OK;
+}
+
+extern "C" int slz_ctx_set_option(slz_ctx *ctx, int option, int value) {
+    if (!ctx) return SLZ_E_INVALID_ARG;
+    if (option == SLZ_OPT_FORCE_GENERIC) { ctx->force_generic = value != 0; return SLZ_OK; }
+    return SLZ_E_INVALID_ARG;
+}
+
+extern "C" const char *slz_pbs_path(const slz_ctx *ctx) {
+    if (!ctx) return "none";
+    return (ctx->has_fused && !ctx->force_generic) ? "fused_n2048" : "generic";
+}
+
+extern "C" int slz_lut_encode(const slz_params *p, const uint64_t *table, uint32_t n_tables, uint64_t *lut_out) {
+    int rc = check_params(p);
+    if (rc != SLZ_OK) return rc;
+    if (!table || !lut_out || n_tables == 0) return SLZ_E_INVALID_ARG;
+    if (p->msg_bits >= 31) return SLZ_E_INVALID_ARG;
+    const uint64_t t = 1ull << p->msg_bits;
+    if ((uint64_t)p->N < 2 * t) return SLZ_E_INVALID_ARG;
+    const uint64_t delta = 1ull << (63 - p->msg_bits);
+    const uint32_t box = (uint32_t)(p->N / t), half = box / 2;
+    for (uint32_t q = 0; q < n_tables; q++) {
+        const uint64_t *f = table + (size_t)q * t;
+        for (uint64_t m = 0; m < t; m++) if (f[m] >= t) return SLZ_E_INVALID_ARG;
+        uint64_t *V = lut_out + (size_t)q * p->N;
+        // box m covers coefficients [m*box - half, (m+1)*box - half); the part of box 0 below zero wraps
+        // negacyclically to the top of the polynomial with its sign flipped.
+        for (uint64_t m = 0; m < t; m++) {
+            uint64_t val = delta * f[m];
+            int64_t lo = (int64_t)(m * box) - (int64_t)half, hi = (int64_t)((m + 1) * box) - (int64_t)half;
+            for (int64_t j = lo; j < hi; j++) {
+                if (j >= 0) V[j] = val;
+                else V[j + (int64_t)p->N] = (uint64_t)0 - val;
+            }
+        }
+    }
+    return SLZ_OK;
+}
+
+static size_t prepared_bytes(const slz_params &p) {
+    return (size_t)p.n * 2 * (p.k + 1) * p.pbs_level * (p.k + 1) * p.N * sizeof(double);
+}
+
+extern "C" int slz_bsk_prepare(slz_ctx *ctx, const uint64_t *bsk_dev, void *dst_dev, size_t *dst_bytes, void *hip_stream) {
+    if (!ctx || !dst_bytes) return SLZ_E_INVALID_ARG;
+    const size_t need = prepared_bytes(ctx->prm);
+    if (!dst_dev) { *dst_bytes = need; return SLZ_OK; }
+    if (!bsk_dev || *dst_bytes < need || misaligned(bsk_dev) || misaligned(dst_dev)) return SLZ_E_INVALID_ARG;
+    return slz_generic_bsk_prepare(ctx, bsk_dev, (double *)dst_dev, (hipStream_t)hip_stream);
+}
+
+static int ensure_generic_scratch(slz_ctx *ctx) {
+    if (ctx->dig) return SLZ_OK;
+    const slz_params &p = ctx->prm;
+    const size_t R = (size_t)(p.k + 1) * p.pbs_level, C = p.k + 1, B = ctx->max_batch, N = p.N;
+    if (hipMalloc((void **)&ctx->acc, B * C * N * 8) != hipSuccess) return SLZ_E_NOMEM;
+    if (hipMalloc((void **)&ctx->dig, B * R * N * 8) != hipSuccess) return SLZ_E_NOMEM;
+    if (hipMalloc((void **)&ctx->xhat, B * 2 * R * N * 8) != hipSuccess) return SLZ_E_NOMEM;
+    if (hipMalloc((void **)&ctx->outhat, B * 2 * C * N * 8) != hipSuccess) return SLZ_E_NOMEM;
+    return SLZ_OK;
+}
+
+static int blind_rotate_common(slz_ctx *ctx, const uint64_t *lwe_in, const uint64_t *luts, const uint32_t *lut_idx,
+                               uint32_t n_luts, const void *bskp, uint32_t n_steps, uint64_t *acc_out, uint64_t *lwe_out,
+                               uint32_t batch, void *hip_stream) {
+    if (!ctx || !lwe_in || !luts || !bskp || n_luts == 0 || batch == 0) return SLZ_E_INVALID_ARG;
+    if (!acc_out && !lwe_out) return SLZ_E_INVALID_ARG;
+    if (batch > ctx->max_batch) return SLZ_E_TOO_LARGE;
+    if (n_steps > ctx->prm.n) return SLZ_E_INVALID_ARG;
+    if (misaligned(lwe_in) || misaligned(luts) || misaligned(bskp) || misaligned(acc_out) || misaligned(lwe_out) ||
+        ((uintptr_t)lut_idx & 3u))
+        return SLZ_E_INVALID_ARG;
+    hipStream_t s = (hipStream_t)hip_stream;
+    if (ctx->has_fused && !ctx->force_generic)
+        return slz_fused_blind_rotate(ctx, lwe_in, luts, lut_idx, (const double *)bskp, n_steps, acc_out, lwe_out, batch, s);
+    int rc = ensure_generic_scratch(ctx);
+    if (rc != SLZ_OK) return rc;
+    return slz_generic_blind_rotate(ctx, lwe_in, luts, lut_idx, (const double *)bskp, n_steps, acc_out, lwe_out, batch, s);
+}
+
+extern "C" int slz_pbs_batch(slz_ctx *ctx, const uint64_t *lwe_in_dev, const uint64_t *luts_dev, const uint32_t *lut_idx_dev,
+                             uint32_t n_luts, const void *bsk_prepared_dev, uint64_t *lwe_out_dev, uint32_t batch,
+                             void *hip_stream) {
+    if (!lwe_out_dev) return SLZ_E_INVALID_ARG;
+    return blind_rotate_common(ctx, lwe_in_dev, luts_dev, lut_idx_dev, n_luts, bsk_prepared_dev, ctx ? ctx->prm.n : 0, nullptr,
+                               lwe_out_dev, batch, hip_stream);
+}
+
+extern "C" int slz_blind_rotate_batch(slz_ctx *ctx, const uint64_t *lwe_in_dev, const uint64_t *luts_dev,
+                                      const uint32_t *lut_idx_dev, uint32_t n_luts, const void *bsk_prepared_dev, uint32_t n_steps,
+                                      uint64_t *acc_out_dev, uint32_t batch, void *hip_stream) {
+    if (!acc_out_dev) return SLZ_E_INVALID_ARG;
+    return blind_rotate_common(ctx, lwe_in_dev, luts_dev, lut_idx_dev, n_luts, bsk_prepared_dev, n_steps, acc_out_dev, nullptr,
+                               batch, hip_stream);
+}
+
+extern "C" int slz_keyswitch_batch(slz_ctx *ctx, const uint64_t *lwe_in_dev, const uint64_t *ksk_dev, uint64_t *lwe_out_dev,
+                                   uint32_t batch, void *hip_stream) {
+    if (!ctx || !lwe_in_dev || !ksk_dev || !lwe_out_dev || batch == 0) return SLZ_E_INVALID_ARG;
+    if (misaligned(lwe_in_dev) || misaligned(ksk_dev) || misaligned(lwe_out_dev)) return SLZ_E_INVALID_ARG;
+    return slz_keyswitch_launch(ctx, lwe_in_dev, ksk_dev, lwe_out_dev, batch, (hipStream_t)hip_stream);
+}
+
+extern "C" int slz_lwe_lincomb_batch(slz_ctx *ctx, const uint64_t *cts_dev, const int32_t *w_dev, uint64_t *out_dev, uint32_t G,
+                                     uint32_t J, uint32_t O, void *hip_stream) {
+    if (!ctx || !cts_dev || !w_dev || !out_dev || G == 0 || J == 0 || O == 0) return SLZ_E_INVALID_ARG;
+    if (G > 65535) return SLZ_E_UNSUPPORTED;
+    if (misaligned(cts_dev) || misaligned(out_dev) || ((uintptr_t)w_dev & 3u)) return SLZ_E_INVALID_ARG;
+    return slz_lincomb_launch(ctx, cts_dev, w_dev, out_dev, G, J, O, (hipStream_t)hip_stream);
+}
+
+extern "C" const char *slz_strerror(int code) {
+    switch (code) {
+        case SLZ_OK: return "success";
+        case SLZ_E_INVALID_ARG: return "invalid argument";
+        case SLZ_E_UNSUPPORTED: return "parameter set not supported by this build";
+        case SLZ_E_HIP: return "HIP runtime error";
+        case SLZ_E_NOMEM: return "out of device memory";
+        case SLZ_E_TOO_LARGE: return "batch larger than the context's max_batch";
+        default: return "unknown error code";
+    }
+}

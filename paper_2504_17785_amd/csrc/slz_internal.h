@@ -1,0 +1,84 @@
+// Internal declarations shared by the translation units of libsilenzio_pbs (not installed).
+#pragma once
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+#include <stddef.h>
+#include "../../include/silenzio_pbs.h"
+
+// ---- exact transform arithmetic -------------------------------------------------------------
+// Negacyclic products mod 2^64 are computed exactly through two number-theoretic transforms over
+// primes just below 2^50 (both = 1 mod 2^18, so N up to 2^17 has a primitive 2N-th root) and a CRT
+// lift.  Residues are held in doubles: on gfx950 an FP64 FMA issues at the full VALU rate and carries
+// a 53-bit product, which makes a 50-bit modular multiply 6 instructions (see slz_modarith.h).
+#define SLZ_P1 1125899902124033.0   /* 0x3ffffffb80001 */
+#define SLZ_P2 1125899886395393.0   /* 0x3fffffec80001 */
+#define SLZ_P1_U64 1125899902124033ull
+#define SLZ_P2_U64 1125899886395393ull
+#define SLZ_MAX_LOGN 17
+
+struct slz_mod {          // one transform prime, passed to kernels by value
+    double p;             // the prime
+    double pinv;          // nearest double to 1/p
+};
+
+// Position of transform-domain coefficient `idx` (index in the bit-reversed output order of the
+// forward transform) inside a prepared polynomial.  The fused kernels hold 32 consecutive outputs per
+// lane, so the prepared key is stored register-major / lane-minor to make their loads coalesced.
+__host__ __device__ static inline uint32_t slz_prep_pos(uint32_t idx, uint32_t N) {
+    uint32_t E = N < 32 ? N : 32;
+    return (idx % E) * (N / E) + idx / E;
+}
+
+struct slz_tables {       // device tables of one prime (all doubles, centred residues)
+    double *fwd;          // [N]  fwd[m+i] = psi^bitrev(m+i): merged negacyclic forward twiddles
+    double *inv;          // [N]  inv[t+j] = psi^(-(N/t) j), j < t: cyclic inverse twiddles of half-size t
+    double *post;         // [N]  post[j] = psi^(-j) / N
+};
+
+struct slz_ctx {
+    slz_params prm;
+    uint32_t max_batch;
+    int device;
+    int force_generic;
+    int has_fused;
+    uint32_t logN;
+    slz_mod mod[2];
+    double two32[2];          // 2^32 mod p_i (centred)
+    double p1inv_mod_p2;      // p1^{-1} mod p2 (centred)
+    slz_tables tab[2];
+    double *fused_tab;        // tables re-laid-out for the fused kernel (or null)
+    // scratch for the generic path, sized for max_batch
+    uint64_t *acc;            // [max_batch][k+1][N]
+    double *dig;              // [max_batch][(k+1)l][N]
+    double *xhat;             // [max_batch][2][(k+1)l][N]
+    double *outhat;           // [max_batch][2][k+1][N]
+    uint32_t fwd_reduce_mask; // bit s: fully reduce all values before forward stage s (0-based)
+    uint32_t inv_reduce_mask; // same for the inverse stages
+    double fwd_out_bound;     // bound (in units of p) of forward outputs
+};
+
+#define SLZ_HIP(x) do { hipError_t e_ = (x); if (e_ != hipSuccess) return SLZ_E_HIP; } while (0)
+
+// host side (slz_tables.cpp)
+int slz_build_tables(slz_ctx *ctx);
+void slz_free_tables(slz_ctx *ctx);
+// bound bookkeeping shared by host checks
+double slz_mulmod_bound(double in_bound);
+
+// generic path (slz_generic.hip)
+int slz_generic_bsk_prepare(slz_ctx *ctx, const uint64_t *bsk, double *dst, hipStream_t s);
+int slz_generic_blind_rotate(slz_ctx *ctx, const uint64_t *lwe_in, const uint64_t *luts, const uint32_t *lut_idx,
+                             const double *bskp, uint32_t n_steps, uint64_t *acc_out, uint64_t *lwe_out,
+                             uint32_t batch, hipStream_t s);
+// fused path (slz_fused.hip)
+int slz_fused_supported(const slz_params *p);
+int slz_fused_init(slz_ctx *ctx);
+void slz_fused_destroy(slz_ctx *ctx);
+int slz_fused_blind_rotate(slz_ctx *ctx, const uint64_t *lwe_in, const uint64_t *luts, const uint32_t *lut_idx,
+                           const double *bskp, uint32_t n_steps, uint64_t *acc_out, uint64_t *lwe_out,
+                           uint32_t batch, hipStream_t s);
+// keyswitch / lincomb (slz_keyswitch.hip)
+int slz_keyswitch_launch(slz_ctx *ctx, const uint64_t *lwe_in, const uint64_t *ksk, uint64_t *lwe_out,
+                         uint32_t batch, hipStream_t s);
+int slz_lincomb_launch(slz_ctx *ctx, const uint64_t *cts, const int32_t *w, uint64_t *out, uint32_t G, uint32_t J,
+                       uint32_t O, hipStream_t s);

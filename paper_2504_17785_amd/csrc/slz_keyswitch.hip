@@ -1,0 +1,124 @@
+// LWE key switching and the clear-weight linear combination of LWE ciphertexts.
+// Both are wrapping u64 integer contractions streamed from HBM; the order of summation is free.
+#include "slz_internal.h"
+#include "slz_modarith.h"
+
+#define KS_THREADS 256
+#define KS_TB 8            // ciphertexts per workgroup (each key word is reused KS_TB times from a register)
+#define KS_IC 32           // mask words decomposed per LDS refill
+#define KS_MAX_L 16
+
+__global__ void __launch_bounds__(KS_THREADS)
+k_ks_init(const uint64_t *__restrict__ lwe_in, uint64_t *__restrict__ out, uint32_t kN, uint32_t n, uint32_t batch) {
+    size_t gid = (size_t)blockIdx.x * KS_THREADS + threadIdx.x;
+    if (gid >= (size_t)batch * (n + 1)) return;
+    uint32_t x = (uint32_t)(gid % (n + 1));
+    size_t c = gid / (n + 1);
+    out[gid] = (x == n) ? lwe_in[c * (kN + 1) + kN] : 0ull;
+}
+
+// out[c][x] -= sum_{i in segment} sum_j d_j(a'_{c,i}) * KSK[i][j][x]
+// grid: (x tiles, ciphertext tiles, segments of the mask index)
+__global__ void __launch_bounds__(KS_THREADS)
+k_keyswitch(const uint64_t *__restrict__ lwe_in, const uint64_t *__restrict__ ksk, uint64_t *__restrict__ out, uint32_t kN,
+            uint32_t n, uint32_t beta, uint32_t l, uint32_t batch, uint32_t seg_len) {
+    __shared__ int32_t dig[KS_IC * KS_MAX_L * KS_TB];      // [ii][j][c]
+    const uint32_t x = blockIdx.x * KS_THREADS + threadIdx.x;
+    const uint32_t c0 = blockIdx.y * KS_TB;
+    const uint32_t i_begin = blockIdx.z * seg_len;
+    const uint32_t i_end = min(kN, i_begin + seg_len);
+    const bool active = x <= n;
+    uint64_t acc[KS_TB];
+#pragma unroll
+    for (int c = 0; c < KS_TB; c++) acc[c] = 0;
+    for (uint32_t ib = i_begin; ib < i_end; ib += KS_IC) {
+        __syncthreads();
+        // decompose KS_TB x KS_IC mask words (one per thread)
+        {
+            uint32_t c = threadIdx.x / KS_IC, ii = threadIdx.x % KS_IC;      // KS_THREADS == KS_TB*KS_IC
+            uint32_t i = ib + ii;
+            uint64_t v = 0;
+            if (c0 + c < batch && i < i_end) v = slz_round_top_bits(lwe_in[(size_t)(c0 + c) * (kN + 1) + i], beta * l);
+            for (int j = (int)l - 1; j >= 0; j--) {
+                uint64_t B = 1ull << beta, d = v & (B - 1);
+                v >>= beta;
+                int64_t sd = (int64_t)d;
+                if (d >= (B >> 1)) { sd -= (int64_t)B; v += 1; }
+                dig[(ii * l + j) * KS_TB + c] = (int32_t)sd;
+            }
+        }
+        __syncthreads();
+        if (active) {
+            uint32_t cnt = min((uint32_t)KS_IC, i_end - ib);
+            for (uint32_t ii = 0; ii < cnt; ii++) {
+                const uint64_t *row = ksk + ((size_t)(ib + ii) * l) * (n + 1) + x;
+                for (uint32_t j = 0; j < l; j++) {
+                    uint64_t w = row[(size_t)j * (n + 1)];
+                    const int32_t *d = &dig[(ii * l + j) * KS_TB];
+#pragma unroll
+                    for (int c = 0; c < KS_TB; c++) acc[c] -= (uint64_t)(int64_t)d[c] * w;
+                }
+            }
+        }
+    }
+    if (active) {
+#pragma unroll
+        for (int c = 0; c < KS_TB; c++)
+            if (c0 + c < batch) atomicAdd((unsigned long long *)&out[(size_t)(c0 + c) * (n + 1) + x], (unsigned long long)acc[c]);
+    }
+}
+
+int slz_keyswitch_launch(slz_ctx *ctx, const uint64_t *lwe_in, const uint64_t *ksk, uint64_t *lwe_out, uint32_t batch,
+                         hipStream_t s) {
+    const slz_params &p = ctx->prm;
+    const uint32_t kN = p.k * p.N, n = p.n;
+    if (p.ks_level > KS_MAX_L || p.ks_base_log > 31) return SLZ_E_UNSUPPORTED;
+    static_assert(KS_THREADS == KS_TB * KS_IC, "one mask word per thread in the decomposition step");
+    size_t total = (size_t)batch * (n + 1);
+    hipLaunchKernelGGL(k_ks_init, dim3((unsigned)((total + KS_THREADS - 1) / KS_THREADS)), dim3(KS_THREADS), 0, s, lwe_in, lwe_out,
+                       kN, n, batch);
+    uint32_t xt = (n + 1 + KS_THREADS - 1) / KS_THREADS, ct = (batch + KS_TB - 1) / KS_TB;
+    // enough segments of the mask index to give the 256 CUs several workgroups each
+    uint32_t segs = 1;
+    while ((size_t)xt * ct * segs < 2048 && segs < kN / (4 * KS_IC)) segs *= 2;
+    uint32_t seg_len = ((kN + segs - 1) / segs + KS_IC - 1) / KS_IC * KS_IC;
+    segs = (kN + seg_len - 1) / seg_len;
+    hipLaunchKernelGGL(k_keyswitch, dim3(xt, ct, segs), dim3(KS_THREADS), 0, s, lwe_in, ksk, lwe_out, kN, n, p.ks_base_log,
+                       p.ks_level, batch, seg_len);
+    SLZ_HIP(hipGetLastError());
+    return SLZ_OK;
+}
+
+// ---- out[g][o][x] = sum_j w[j][o] * ct[g][j][x] ----------------------------------------------
+#define LC_OT 16
+__global__ void __launch_bounds__(KS_THREADS)
+k_lincomb(const uint64_t *__restrict__ cts, const int32_t *__restrict__ w, uint64_t *__restrict__ out, uint32_t J, uint32_t O,
+          uint32_t width) {
+    const uint32_t x = blockIdx.x * KS_THREADS + threadIdx.x;
+    const uint32_t o0 = blockIdx.y * LC_OT;
+    const uint32_t g = blockIdx.z;
+    if (x >= width) return;
+    uint64_t acc[LC_OT];
+#pragma unroll
+    for (int o = 0; o < LC_OT; o++) acc[o] = 0;
+    const uint64_t *src = cts + (size_t)g * J * width + x;
+    for (uint32_t j = 0; j < J; j++) {
+        uint64_t c = src[(size_t)j * width];
+        const int32_t *wr = w + (size_t)j * O + o0;
+#pragma unroll
+        for (int o = 0; o < LC_OT; o++)
+            if (o0 + o < O) acc[o] += (uint64_t)(int64_t)wr[o] * c;
+    }
+#pragma unroll
+    for (int o = 0; o < LC_OT; o++)
+        if (o0 + o < O) out[((size_t)g * O + o0 + o) * width + x] = acc[o];
+}
+
+int slz_lincomb_launch(slz_ctx *ctx, const uint64_t *cts, const int32_t *w, uint64_t *out, uint32_t G, uint32_t J, uint32_t O,
+                       hipStream_t s) {
+    const uint32_t width = ctx->prm.n + 1;
+    hipLaunchKernelGGL(k_lincomb, dim3((width + KS_THREADS - 1) / KS_THREADS, (O + LC_OT - 1) / LC_OT, G), dim3(KS_THREADS), 0, s,
+                       cts, w, out, J, O, width);
+    SLZ_HIP(hipGetLastError());
+    return SLZ_OK;
+}

@@ -1,0 +1,71 @@
+"""Host-only checks of the C-ABI library (no GPU): it loads, exports every symbol the header declares,
+its pure host function slz_lut_encode agrees with the oracle, and argument errors are reported."""
+import ctypes
+import os
+import re
+
+import numpy as np
+import pytest
+
+import synth
+import paper_2504_17785_amd as slz
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+
+
+def test_library_loads_and_exports_header_symbols():
+    L = slz.lib()
+    header = open(os.path.join(ROOT, "include", "silenzio_pbs.h")).read()
+    declared = set(re.findall(r"\b(slz_[a-z_0-9]+)\s*\(", header))
+    declared -= {"slz_params", "slz_ctx"}
+    assert {"slz_pbs_batch", "slz_keyswitch_batch", "slz_lut_encode"} <= declared
+    for name in sorted(declared):
+        assert hasattr(L, name), name
+    assert declared == set(slz.EXPORTS)
+
+
+@pytest.mark.parametrize("cfg", [1, 2, 3, 4, 5])
+def test_lut_encode_matches_oracle(orc, cfg):
+    p = synth.CONFIGS[cfg]
+    tables = synth.config_tables(cfg)
+    assert np.array_equal(slz.lut_encode(p, tables), orc.lut_encode(p, tables))
+
+
+def test_lut_encode_small_shapes_match_oracle(orc):
+    for N, bits in [(8, 1), (8, 2), (64, 5), (32, 3), (1024, 9)]:
+        p = synth.CONFIGS[1].with_(N=N, msg_bits=bits)
+        tables = synth.random_tables(p, 3)
+        assert np.array_equal(slz.lut_encode(p, tables), orc.lut_encode(p, tables))
+
+
+def test_lut_encode_rejects_bad_arguments():
+    L = slz.lib()
+    p = synth.CONFIGS[1]
+    cp = slz.make_params(p)
+    tab = np.zeros(p.t, dtype=np.uint64)
+    out = np.zeros(p.N, dtype=np.uint64)
+    assert L.slz_lut_encode(ctypes.byref(cp), None, 1, out.ctypes.data) == -1
+    assert L.slz_lut_encode(ctypes.byref(cp), tab.ctypes.data, 0, out.ctypes.data) == -1
+    assert L.slz_lut_encode(None, tab.ctypes.data, 1, out.ctypes.data) == -1
+    tab[3] = p.t                                           # entry out of range
+    assert L.slz_lut_encode(ctypes.byref(cp), tab.ctypes.data, 1, out.ctypes.data) == -1
+    small = slz.make_params(p.with_(N=8, msg_bits=3))      # N < 2t
+    assert L.slz_lut_encode(ctypes.byref(small), tab.ctypes.data, 1, out.ctypes.data) == -1
+    bad = slz.make_params(p.with_(N=500))                  # not a power of two
+    assert L.slz_lut_encode(ctypes.byref(bad), tab.ctypes.data, 1, out.ctypes.data) == -1
+    assert L.slz_strerror(-1) == b"invalid argument"
+    assert L.slz_strerror(0) == b"success"
+
+
+def test_null_context_calls_are_errors_not_crashes():
+    L = slz.lib()
+    assert L.slz_ctx_destroy(None) == -1
+    assert L.slz_ctx_set_option(None, 1, 1) == -1
+    assert L.slz_pbs_batch(None, None, None, None, 0, None, None, 0, None) == -1
+    assert L.slz_keyswitch_batch(None, None, None, None, 0, None) == -1
+    assert L.slz_blind_rotate_batch(None, None, None, None, 0, None, 0, None, 0, None) == -1
+    assert L.slz_lwe_lincomb_batch(None, None, None, None, 0, 0, 0, None) == -1
+    need = ctypes.c_size_t(0)
+    assert L.slz_bsk_prepare(None, None, None, ctypes.byref(need), None) == -1
+    out = ctypes.c_void_p()
+    assert L.slz_ctx_create(None, 1, ctypes.byref(out)) == -1

@@ -1,0 +1,179 @@
+"""GPU parity: the HIP library, called through its C ABI, against the CPU oracle, bit for bit, on the
+same seeded keys and inputs.  All integer work: the bar is exact equality of every output word."""
+import ctypes
+
+import numpy as np
+import pytest
+
+import synth
+from synth import Params
+
+pytestmark = pytest.mark.gpu
+
+torch = pytest.importorskip("torch")
+
+
+def tiny(**kw):
+    base = dict(name="tiny", n=10, k=1, N=64, pbs_base_log=8, pbs_level=2, ks_base_log=4, ks_level=3,
+                msg_bits=2, sigma_lwe=2.0 ** -30, sigma_bsk=2.0 ** -50, batch=8, n_luts=2, seed=4242)
+    base.update(kw)
+    return Params(**base)
+
+
+@pytest.fixture(scope="module")
+def slz():
+    if not torch.cuda.is_available():
+        pytest.fail("the gpu tests need a GPU: torch.cuda.is_available() is False")
+    import paper_2504_17785_amd as m
+    m.lib()
+    return m
+
+
+class Case:
+    """Keys, LUTs and input ciphertexts of one parameter set, on host (oracle side) and device."""
+
+    def __init__(self, slz, orc, p, batch, n_tables=2, msgs=None, raw_inputs=False, force_generic=False):
+        self.p, self.batch = p, batch
+        self.keys = orc.Keys(p, synth)
+        self.tables = synth.random_tables(p, n_tables)
+        self.luts = orc.lut_encode(p, self.tables)
+        self.lut_idx = synth.uniform_below(p.seed, "lut_idx", batch, n_tables).astype(np.uint32)
+        if raw_inputs:
+            self.msgs = None
+            self.cts = synth.raw_words(p, "raw_ct", batch * (p.n + 1)).reshape(batch, p.n + 1)
+        else:
+            self.msgs = synth.messages(p, batch) if msgs is None else np.asarray(msgs, dtype=np.uint64)
+            self.cts = orc.encrypt_messages(p, synth, self.keys.lwe_sk, self.msgs)
+        self.ctx = slz.Context(p, batch)
+        if force_generic:
+            self.ctx.set_option(slz.SLZ_OPT_FORCE_GENERIC, 1)
+        self.d_bsk = self.ctx.bsk_prepare(slz.to_device_u64(self.keys.bsk))
+        self.d_ksk = slz.to_device_u64(self.keys.ksk)
+        self.d_luts = slz.to_device_u64(self.luts)
+        self.d_idx = torch.from_numpy(self.lut_idx.astype(np.int32)).cuda()
+        self.d_cts = slz.to_device_u64(self.cts)
+
+
+SHAPES = [
+    dict(n=6, N=8, k=1, pbs_base_log=8, pbs_level=2),
+    dict(n=7, N=16, k=2, pbs_base_log=6, pbs_level=3),
+    dict(n=10, N=64, k=1, pbs_base_log=23, pbs_level=1),
+    dict(n=5, N=256, k=1, pbs_base_log=12, pbs_level=2),
+    dict(n=4, N=1024, k=3, pbs_base_log=15, pbs_level=1),
+    dict(n=3, N=2048, k=1, pbs_base_log=23, pbs_level=1),
+    dict(n=3, N=4096, k=1, pbs_base_log=11, pbs_level=2),     # larger than one LDS chunk: HBM stages
+    dict(n=2, N=8192, k=1, pbs_base_log=15, pbs_level=2),
+]
+
+
+@pytest.mark.parametrize("shape", SHAPES, ids=lambda s: "N%d_k%d_l%d" % (s["N"], s["k"], s["pbs_level"]))
+def test_blind_rotation_states_match_oracle(slz, orc, shape):
+    p = tiny(**shape)
+    batch = 5
+    case = Case(slz, orc, p, batch, raw_inputs=True, force_generic=True)
+    for steps in sorted({0, 1, 2, p.n}):
+        want = orc.blind_rotate_batch(p, case.cts, case.luts, case.lut_idx, case.keys.bsk, steps)
+        got = slz.to_host_u64(case.ctx.blind_rotate_batch(case.d_cts, case.d_luts, case.d_idx, case.d_bsk, steps))
+        assert np.array_equal(got, want), "accumulators differ after %d steps" % steps
+    want = orc.pbs_batch(p, case.cts, case.luts, case.lut_idx, case.keys.bsk)
+    got = slz.to_host_u64(case.ctx.pbs_batch(case.d_cts, case.d_luts, case.d_idx, case.d_bsk))
+    assert np.array_equal(got, want)
+    # lut_idx == NULL: every ciphertext uses LUT 0
+    want0 = orc.pbs_batch(p, case.cts, case.luts, None, case.keys.bsk)
+    got0 = slz.to_host_u64(case.ctx.pbs_batch(case.d_cts, case.d_luts, None, case.d_bsk))
+    assert np.array_equal(got0, want0)
+
+
+def test_worst_case_magnitudes_stay_exact(slz, orc):
+    # key words and accumulator words at the extremes of the signed range, digits at +-B/2: the largest
+    # sums the exactness bound allows for this shape
+    p = tiny(n=3, N=2048, k=1, pbs_base_log=23, pbs_level=1)
+    case = Case(slz, orc, p, 3, raw_inputs=True, force_generic=True)
+    bsk = case.keys.bsk.copy()
+    flat = bsk.reshape(-1)
+    flat[0::3] = np.uint64(1 << 63)                       # -2^63
+    flat[1::3] = np.uint64((1 << 63) - 1)                 # 2^63 - 1
+    luts = case.luts.copy()
+    luts[:, 0::2] = np.uint64((1 << 63) - (1 << 40))      # decomposes to digit +-2^22
+    luts[:, 1::2] = np.uint64(1 << 63)
+    d_bsk = case.ctx.bsk_prepare(slz.to_device_u64(bsk))
+    want = orc.blind_rotate_batch(p, case.cts, luts, case.lut_idx, bsk, p.n)
+    got = slz.to_host_u64(case.ctx.blind_rotate_batch(case.d_cts, slz.to_device_u64(luts), case.d_idx, d_bsk, p.n))
+    assert np.array_equal(got, want)
+
+
+@pytest.mark.parametrize("batch,kN,n,beta,l", [(1, 64, 10, 4, 3), (13, 128, 33, 3, 5), (8, 256, 255, 2, 8),
+                                               (37, 2048, 742, 3, 5), (3, 32, 300, 5, 2)])
+def test_keyswitch_matches_oracle(slz, orc, batch, kN, n, beta, l):
+    p = tiny(n=n, N=kN, k=1, ks_base_log=beta, ks_level=l)
+    ksk = synth.raw_words(p, "raw_ksk", kN * l * (n + 1)).reshape(kN, l, n + 1)
+    cts = synth.raw_words(p, "raw_ct", batch * (kN + 1)).reshape(batch, kN + 1)
+    ctx = slz.Context(p, batch)
+    got = slz.to_host_u64(ctx.keyswitch_batch(slz.to_device_u64(cts), slz.to_device_u64(ksk)))
+    assert np.array_equal(got, orc.keyswitch_batch(p, cts, ksk))
+
+
+def test_lincomb_matches_oracle(slz, orc):
+    p = tiny(n=42)
+    G, J, O = 5, 37, 19
+    cts = synth.raw_words(p, "raw_ct", G * J * (p.n + 1)).reshape(G, J, p.n + 1)
+    w = (synth.uniform_below(p.seed, "weights", J * O, 27).astype(np.int64) - 13).astype(np.int32).reshape(J, O)
+    ctx = slz.Context(p, 1)
+    got = slz.to_host_u64(ctx.lwe_lincomb_batch(slz.to_device_u64(cts), torch.from_numpy(w).cuda()))
+    assert np.array_equal(got, orc.lwe_lincomb_batch(cts, w))
+
+
+def test_config1_full_pipeline_bit_exact_and_decrypts(slz, orc):
+    p = synth.CONFIGS[1]
+    case = Case(slz, orc, p, p.batch, n_tables=1, msgs=synth.config_messages(1))
+    case.tables = synth.config_tables(1)
+    case.luts = orc.lut_encode(p, case.tables)
+    case.d_luts = slz.to_device_u64(slz.lut_encode(p, case.tables))
+    big = case.ctx.pbs_batch(case.d_cts, case.d_luts, None, case.d_bsk)
+    small = case.ctx.keyswitch_batch(big, case.d_ksk)
+    want_big = orc.pbs_batch(p, case.cts, case.luts, None, case.keys.bsk)
+    want_small = orc.keyswitch_batch(p, want_big, case.keys.ksk)
+    assert np.array_equal(slz.to_host_u64(big), want_big)
+    assert np.array_equal(slz.to_host_u64(small), want_small)
+    got, err = orc.decode(orc.lwe_phase(case.keys.lwe_sk, slz.to_host_u64(small)), p.msg_bits)
+    assert np.array_equal(got, case.tables[0][case.msgs.astype(np.int64)])
+    assert np.abs(err).max() < 2.0 ** -6
+
+
+def test_results_do_not_depend_on_batch_composition_or_repetition(slz, orc):
+    p = tiny(n=12, N=512, pbs_base_log=8, pbs_level=2)
+    case = Case(slz, orc, p, 9, raw_inputs=True)
+    full = slz.to_host_u64(case.ctx.pbs_batch(case.d_cts, case.d_luts, case.d_idx, case.d_bsk))
+    again = slz.to_host_u64(case.ctx.pbs_batch(case.d_cts, case.d_luts, case.d_idx, case.d_bsk))
+    assert np.array_equal(full, again)
+    perm = np.array([4, 0, 8, 2, 6, 1, 7, 3, 5])
+    d_cts = slz.to_device_u64(case.cts[perm])
+    d_idx = torch.from_numpy(case.lut_idx[perm].astype(np.int32)).cuda()
+    shuffled = slz.to_host_u64(case.ctx.pbs_batch(d_cts, case.d_luts, d_idx, case.d_bsk))
+    assert np.array_equal(shuffled, full[perm])
+    part = slz.to_host_u64(case.ctx.pbs_batch(case.d_cts[2:5].contiguous(), case.d_luts, case.d_idx[2:5].contiguous(), case.d_bsk))
+    assert np.array_equal(part, full[2:5])
+
+
+def test_error_codes(slz):
+    L = slz.lib()
+    p = tiny()
+    h = ctypes.c_void_p()
+    cp = slz.make_params(p)
+    assert L.slz_ctx_create(ctypes.byref(cp), 0, ctypes.byref(h)) == -1                     # batch 0
+    bad = slz.make_params(p.with_(pbs_base_log=33, pbs_level=2))
+    assert L.slz_ctx_create(ctypes.byref(bad), 4, ctypes.byref(h)) == -1                    # base*level > 64
+    big = slz.make_params(p.with_(N=2048, pbs_base_log=30, pbs_level=2))
+    assert L.slz_ctx_create(ctypes.byref(big), 4, ctypes.byref(h)) == -2                    # exactness bound
+    ctx = slz.Context(p, 4)
+    x = torch.zeros(64, dtype=torch.int64, device="cuda")
+    assert L.slz_pbs_batch(ctx._h, x.data_ptr(), x.data_ptr(), None, 1, x.data_ptr(), x.data_ptr(), 5, None) == -5
+    assert L.slz_pbs_batch(ctx._h, x.data_ptr(), x.data_ptr(), None, 1, x.data_ptr(), x.data_ptr(), 0, None) == -1
+    assert L.slz_pbs_batch(ctx._h, x.data_ptr() + 8, x.data_ptr(), None, 1, x.data_ptr(), x.data_ptr(), 1, None) == -1
+    assert L.slz_blind_rotate_batch(ctx._h, x.data_ptr(), x.data_ptr(), None, 1, x.data_ptr(), p.n + 1, x.data_ptr(), 1, None) == -1
+    need = ctypes.c_size_t(0)
+    assert L.slz_bsk_prepare(ctx._h, None, None, ctypes.byref(need), None) == 0
+    assert need.value == p.n * 2 * 2 * p.pbs_level * 2 * p.N * 8
+    short = ctypes.c_size_t(need.value - 8)
+    assert L.slz_bsk_prepare(ctx._h, x.data_ptr(), x.data_ptr(), ctypes.byref(short), None) == -1
+    torch.cuda.synchronize()
