@@ -1,0 +1,152 @@
+"""Benchmark of the hot path: one step = slz_pbs_batch + slz_keyswitch_batch over one batch of ciphertexts.
+
+Prints ONE JSON line.  Workload: configuration 2 of the baseline (1024 LWE ciphertexts, n=742, k=1, N=2048,
+PBS base 2^23 x 1 level, keyswitch base 2^3 x 5 levels) unless --config says otherwise.  Inputs are seeded
+and synthetic and already resident in HBM when the timed region starts.  Key and ciphertext material for
+the timed run is uniform random u64 words (what TFHE keys and ciphertexts look like; the kernels have no
+data-dependent control flow); LUT polynomials come from slz_lut_encode.  The cpu_baseline leg runs the
+CPU oracle on a bounded sample of the same inputs and also checks that the GPU's outputs for that sample
+are bit-identical.
+"""
+import argparse
+import json
+import os
+import sys
+import time
+
+import numpy as np
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+if ROOT not in sys.path:
+    sys.path.insert(0, ROOT)
+
+PEAK_ALU_TINSTR = 256 * 4 * 16 * 2.4e9 / 1e12      # 256 CUs x 4 SIMD16 x 2.4 GHz: FP64/INT32 lane-instructions per second
+
+
+def alu_model_ops_per_pbs(p) -> float:
+    """Algorithmic VALU lane-instructions of one PBS (the op table is in the design doc):
+    8 per butterfly (6 modular multiply + add + sub), 7 per pointwise multiply-accumulate, 3 per inverse
+    post-scaling beyond the butterflies' share (6-instruction modular multiply per coefficient), 12 per
+    decomposed coefficient (rotate, subtract, round, digit, convert) and 20 per CRT-lifted coefficient."""
+    logN = p.N.bit_length() - 1
+    R, C = (p.k + 1) * p.pbs_level, p.k + 1
+    per_prime = (R + C) * (p.N // 2) * logN * 8 + R * C * p.N * 7 + C * p.N * 6
+    per_cmux = 2 * per_prime + C * p.N * (12 + 4 * (p.pbs_level - 1)) + C * p.N * 20
+    return float(p.n) * per_cmux
+
+
+def main():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=5)
+    ap.add_argument("--warmup", type=int, default=1)
+    ap.add_argument("--config", type=int, default=2)
+    ap.add_argument("--batch", type=int, default=0, help="override the configuration's batch size")
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--generic", action="store_true", help="force the generic multi-kernel path")
+    args = ap.parse_args()
+    if args.gpus != 1:
+        print("bench.py measures one GPU only (this build has no multi-GPU path); run with --gpus 1", file=sys.stderr)
+        sys.exit(2)
+
+    import torch
+    import synth
+    import paper_2504_17785_amd as slz
+
+    p = synth.CONFIGS[args.config]
+    batch = args.batch or p.batch
+    torch.cuda.set_device(0)
+    ctx = slz.Context(p, batch)
+    if args.generic:
+        ctx.set_option(slz.SLZ_OPT_FORCE_GENERIC, 1)
+
+    # ---- synthetic inputs, resident in HBM ----
+    R, C = (p.k + 1) * p.pbs_level, p.k + 1
+    bsk = synth.raw_words(p, "raw_bsk", p.n * R * C * p.N).reshape(p.n, p.k + 1, p.pbs_level, C, p.N)
+    ksk = synth.raw_words(p, "raw_ksk", p.k * p.N * p.ks_level * (p.n + 1)).reshape(p.k * p.N, p.ks_level, p.n + 1)
+    cts = synth.raw_words(p, "raw_ct", batch * (p.n + 1)).reshape(batch, p.n + 1)
+    tables = synth.config_tables(args.config)
+    luts = slz.lut_encode(p, tables)
+    lut_idx = synth.config_lut_idx(args.config, batch)
+    d_bsk_std = slz.to_device_u64(bsk)
+    d_bskp = ctx.bsk_prepare(d_bsk_std)
+    del d_bsk_std
+    d_ksk = slz.to_device_u64(ksk)
+    d_cts = slz.to_device_u64(cts)
+    d_luts = slz.to_device_u64(luts)
+    d_idx = torch.from_numpy(lut_idx.astype(np.int32)).cuda()
+    d_big = torch.empty((batch, p.k * p.N + 1), dtype=torch.int64, device="cuda")
+    d_small = torch.empty((batch, p.n + 1), dtype=torch.int64, device="cuda")
+    torch.cuda.synchronize()
+
+    def step():
+        ctx.pbs_batch(d_cts, d_luts, d_idx, d_bskp, out=d_big)
+        ctx.keyswitch_batch(d_big, d_ksk, out=d_small)
+
+    for _ in range(args.warmup):
+        step()
+    torch.cuda.synchronize()
+
+    # ---- timed region: exactly K steps; per-call HIP events on the launch stream give the kernel split ----
+    ev = [[torch.cuda.Event(enable_timing=True) for _ in range(3)] for _ in range(args.steps)]
+    t0 = time.perf_counter()
+    for k in range(args.steps):
+        ev[k][0].record()
+        ctx.pbs_batch(d_cts, d_luts, d_idx, d_bskp, out=d_big)
+        ev[k][1].record()
+        ctx.keyswitch_batch(d_big, d_ksk, out=d_small)
+        ev[k][2].record()
+    torch.cuda.synchronize()
+    wall = time.perf_counter() - t0
+    pbs_ms = float(np.mean([e[0].elapsed_time(e[1]) for e in ev]))
+    ks_ms = float(np.mean([e[1].elapsed_time(e[2]) for e in ev]))
+    ms_per_step = wall * 1e3 / args.steps
+
+    model_ops = alu_model_ops_per_pbs(p) * batch
+    achieved = model_ops / (pbs_ms * 1e-3) / 1e12
+    prepared_bytes = ctx.bsk_prepared_bytes()
+    result = {
+        "metric": "pbs_plus_keyswitch_per_s",
+        "value": batch / (ms_per_step * 1e-3),
+        "unit": "PBS+KS/s",
+        "n_gpus": 1, "steps": args.steps, "warmup": args.warmup, "ms_per_step": ms_per_step,
+        "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
+        "dtype": "u64 (exact; transforms in f64-held 50-bit residues)", "data": "synthetic",
+        "config": {"workload": "%s: batch %d, n=%d, k=%d, N=%d, PBS 2^%d x %d, KS 2^%d x %d" % (
+            p.name, batch, p.n, p.k, p.N, p.pbs_base_log, p.pbs_level, p.ks_base_log, p.ks_level),
+            "path": ctx.path},
+        "pbs_per_s": batch / (pbs_ms * 1e-3), "keyswitch_per_s": batch / (ks_ms * 1e-3),
+        "pbs_ms": pbs_ms, "keyswitch_ms": ks_ms,
+        "bsk_prepared_bytes": prepared_bytes,
+        "bsk_stream_GBps_min": prepared_bytes / (pbs_ms * 1e-3) / 1e9,
+        "roofline": {"bound": "alu", "kernel": "blind rotation (slz_pbs_batch)", "achieved": achieved,
+                     "peak": PEAK_ALU_TINSTR, "unit": "Tinstr/s", "frac": achieved / PEAK_ALU_TINSTR, "traffic": None},
+    }
+
+    # ---- CPU baseline: the oracle on a bounded sample of the same inputs (also a parity check) ----
+    if not args.no_cpu_baseline:
+        import oracle
+        threads = oracle.num_threads()
+        budget_macs = 2.5e9 * 20.0 * threads * 0.35            # about 20 s at ~0.9 GMAC/s/core schoolbook
+        macs_per_pbs = p.n * (p.k + 1) ** 2 * p.pbs_level * float(p.N) ** 2
+        sample = int(max(1, min(batch, threads * max(1, int(budget_macs / threads / macs_per_pbs)))))
+        idx = np.linspace(0, batch - 1, sample).astype(np.int64)
+        t1 = time.perf_counter()
+        o_big = oracle.pbs_batch(p, cts[idx], luts, lut_idx[idx], bsk)
+        t2 = time.perf_counter()
+        o_small = oracle.keyswitch_batch(p, o_big, ksk)
+        t3 = time.perf_counter()
+        g_big = slz.to_host_u64(d_big)[idx]
+        g_small = slz.to_host_u64(d_small)[idx]
+        result["cpu_baseline"] = {
+            "value": sample / (t3 - t1), "unit": "PBS+KS/s", "cores": min(threads, sample), "kind": "oracle",
+            "sample": "%d of the %d ciphertexts (evenly spaced), full PBS + keyswitch each" % (sample, batch),
+            "pbs_s_per_ct_per_core": (t2 - t1) * min(threads, sample) / sample,
+            "keyswitch_s_per_ct_per_core": (t3 - t2) * min(threads, sample) / sample,
+            "gpu_bit_exact_on_sample": bool(np.array_equal(g_big, o_big) and np.array_equal(g_small, o_small)),
+        }
+    print(json.dumps(result))
+
+
+if __name__ == "__main__":
+    main()

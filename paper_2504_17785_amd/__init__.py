@@ -40,6 +40,10 @@ def lib():
     """Loads the built library (building it first only if no built library exists)."""
     global _lib
     if _lib is None:
+        # PyTorch must be loaded first: its wheel bundles the HIP runtime under the same soname the library
+        # links against, and a process must hold exactly one HIP runtime (torch's streams and allocations
+        # are only valid in the runtime that made them).
+        import torch  # noqa: F401
         if not os.path.exists(LIB_PATH):
             from . import build as _build
             _build.build()
