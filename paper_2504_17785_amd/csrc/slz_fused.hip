@@ -1,7 +1,378 @@
-// placeholder until the fused kernel lands
+// Fused blind rotation for N = 2048, k = 1, l = 1 (the 128-bit-shaped low-precision parameter sets).
+//
+// One workgroup of four wavefronts owns one ciphertext for the whole blind rotation; the accumulator
+// never leaves the chip.  Wave (q, h): q = transform prime, h = GGSW row = accumulator component.
+// Per CMux step every wave
+//   1. stages its quarter of the accumulator in LDS, reads component h rotated by a~ and unrotated,
+//      subtracts, rounds and extracts the signed digit                      (rows are decomposed once per prime)
+//   2. forward negacyclic transform of the digit polynomial mod p_q         (one wave = one polynomial,
+//      32 coefficients per lane: 5 radix-2 stages in registers, one stage across the two half-waves with
+//      v_permlane32_swap, one LDS transposition, 5 more stages in registers)
+//   3. multiplies by the two prepared key polynomials of row h, keeps the product for component h and hands
+//      the other one to its sibling wave through LDS; sums and reduces
+//   4. inverse transform (cyclic decimation-in-time on the bit-reversed spectrum, then the psi^-j / N twist)
+//   5. exchanges half of the residues with the wave of the other prime, CRT-lifts its half of component h
+//      to an integer mod 2^64 and adds it to its quarter of the accumulator (kept in registers).
+// Key rows are read straight from L2 (every workgroup on the chip reads the same 128 KiB per step).
 #include "slz_internal.h"
-int slz_fused_supported(const slz_params *) { return 0; }
-int slz_fused_init(slz_ctx *) { return SLZ_E_UNSUPPORTED; }
-void slz_fused_destroy(slz_ctx *) {}
-int slz_fused_blind_rotate(slz_ctx *, const uint64_t *, const uint64_t *, const uint32_t *, const double *, uint32_t, uint64_t *,
-                           uint64_t *, uint32_t, hipStream_t) { return SLZ_E_UNSUPPORTED; }
+#include "slz_modarith.h"
+#include <vector>
+
+#define FN 2048u
+#define FLOGN 11u
+#define TBUF 2176u            // doubles per wave buffer: 2048 + 2 pad doubles per 32 (bank-conflict-free transposition)
+#define STAGE_OFF 1088u       // second half of a wave buffer: staging of 1024 accumulator words
+#define FUSED_THREADS 256
+
+struct fused_prime_tabs {
+    const double *fwd;        // natural forward table (fwd[m+i]); entries 1..63 are used as scalars / per half-wave
+    const double *fwdB;       // [31][64] per-lane twiddles of the last five forward stages
+    const double *inv;        // natural inverse table inv[t+j]
+    const double *post;       // post[j] = psi^-j / N
+};
+
+struct fused_args {
+    const uint64_t *lwe_in;
+    const uint64_t *luts;
+    const uint32_t *lut_idx;
+    const double *bskp;
+    uint64_t *acc_out;
+    uint64_t *lwe_out;
+    uint32_t n, n_steps, batch;
+    fused_prime_tabs tab[2];
+    slz_mod mod[2];
+    double p1inv_mod_p2;
+};
+
+__device__ __forceinline__ void wave_sync() {
+    // orders this wave's LDS writes before its later LDS reads of other lanes' data
+    __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
+    __builtin_amdgcn_wave_barrier();
+    __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
+}
+
+// a <- (a.low half-wave, b.low half-wave), b <- (a.high half-wave, b.high half-wave)
+__device__ __forceinline__ void swap32(double &a, double &b) {
+    uint32_t alo = (uint32_t)__double2loint(a), ahi = (uint32_t)__double2hiint(a);
+    uint32_t blo = (uint32_t)__double2loint(b), bhi = (uint32_t)__double2hiint(b);
+    auto lo = __builtin_amdgcn_permlane32_swap(alo, blo, false, false);
+    auto hi = __builtin_amdgcn_permlane32_swap(ahi, bhi, false, false);
+    a = __hiloint2double((int)hi[0], (int)lo[0]);
+    b = __hiloint2double((int)hi[1], (int)lo[1]);
+}
+
+// keeps the instruction scheduler from hoisting every table / key load of a phase to its start (which spills)
+#define SCHED_FENCE() __builtin_amdgcn_sched_barrier(0)
+
+__device__ __forceinline__ void bfly(double &a, double &b, double w, slz_mod m) {
+    double v = slz_mulmod(b, w, m);
+    b = a - v;
+    a = a + v;
+}
+__device__ __forceinline__ void bfly_nomul(double &a, double &b) {
+    double v = b;
+    b = a - v;
+    a = a + v;
+}
+
+// Forward transform.  In: x[e] = coefficient 64e + lane (|x| tiny).  Out: x[i] = spectrum position 32*lane + i,
+// |x| <= 4.9 p.  Worst-case growth per stage: a -> a + 1/2 + 0.1875 a (slz_mulmod_bound); six stages take the
+// digits to 4.81 p, one full reduction brings them back to p/2, five more stages end at 4.81 p.
+__device__ __forceinline__ void fused_fwd(double (&x)[32], double *T, const fused_prime_tabs &tb, slz_mod m, uint32_t lane) {
+    const uint32_t hh = lane >> 5, l5 = lane & 31u;
+#pragma unroll
+    for (int s = 0; s < 5; s++) {
+        const int half = 16 >> s;
+#pragma unroll
+        for (int blk = 0; blk < (1 << s); blk++) {
+            const double w = tb.fwd[(1 << s) + blk];            // uniform: block index comes from the register index
+#pragma unroll
+            for (int j = 0; j < half; j++) bfly(x[blk * 2 * half + j], x[blk * 2 * half + j + half], w, m);
+        }
+        SCHED_FENCE();
+    }
+    double *wb = T + 68u * hh + l5;
+#pragma unroll
+    for (int mm = 0; mm < 16; mm++) {
+        swap32(x[2 * mm], x[2 * mm + 1]);                        // stride 32: partner coefficient sits 32 lanes away
+        const double w = tb.fwd[32 + 2 * mm + hh];
+        bfly(x[2 * mm], x[2 * mm + 1], w, m);
+        wb[136 * mm] = slz_reduce(x[2 * mm], m);
+        wb[136 * mm + 34] = slz_reduce(x[2 * mm + 1], m);
+        if ((mm & 3) == 3) SCHED_FENCE();
+    }
+    wave_sync();
+    const double *rb = T + 34u * lane;
+#pragma unroll
+    for (int i = 0; i < 32; i += 2) {
+        const double2 v = *reinterpret_cast<const double2 *>(rb + i);
+        x[i] = v.x;
+        x[i + 1] = v.y;
+    }
+    int kk = 0;
+#pragma unroll
+    for (int s = 0; s < 5; s++) {
+        const int t = 16 >> s;
+#pragma unroll
+        for (int blk = 0; blk < (1 << s); blk++) {
+            const double w = tb.fwdB[(kk++) * 64 + lane];
+#pragma unroll
+            for (int j = 0; j < t; j++) bfly(x[blk * 2 * t + j], x[blk * 2 * t + j + t], w, m);
+            if (s == 4 && (blk & 3) == 3) SCHED_FENCE();
+        }
+        SCHED_FENCE();
+    }
+}
+
+// Inverse transform.  In: x[i] = spectrum position 32*lane + i, |x| <= 0.51 p.  Out: x[e] = coefficient 64e + lane
+// of the product polynomial mod p, |x| <= 1.7 p.  Bounds: stages 1,2 have unit twiddles (no multiply): 0.5 -> 1 -> 2;
+// stages 3..5 -> 2.88, 3.91, 5.15; reduce to 0.5; stages 6..11 -> 6.2; the final twist multiply gives 0.5 + 0.1875*6.2.
+__device__ __forceinline__ void fused_inv(double (&x)[32], double *T, const fused_prime_tabs &tb, slz_mod m, uint32_t lane) {
+    const uint32_t hh = lane >> 5, l5 = lane & 31u;
+#pragma unroll
+    for (int i = 0; i < 32; i += 2) bfly_nomul(x[i], x[i + 1]);                       // t = 1
+#pragma unroll
+    for (int blk = 0; blk < 8; blk++) {                                                 // t = 2
+        bfly_nomul(x[4 * blk], x[4 * blk + 2]);
+        bfly(x[4 * blk + 1], x[4 * blk + 3], tb.inv[3], m);
+    }
+#pragma unroll
+    for (int s = 2; s < 5; s++) {                                                       // t = 4, 8, 16
+        const int t = 1 << s;
+#pragma unroll
+        for (int j = 0; j < t; j++) {
+            const double w = tb.inv[t + j];                                             // uniform: depends on j only
+#pragma unroll
+            for (int blk = 0; blk < (16 >> s); blk++) bfly(x[blk * 2 * t + j], x[blk * 2 * t + j + t], w, m);
+        }
+        SCHED_FENCE();
+    }
+    wave_sync();                                                                        // earlier reads of T are done
+    double *wb = T + 34u * lane;
+#pragma unroll
+    for (int i = 0; i < 32; i += 2) {
+        double2 v;
+        v.x = slz_reduce(x[i], m);
+        v.y = slz_reduce(x[i + 1], m);
+        *reinterpret_cast<double2 *>(wb + i) = v;
+    }
+    wave_sync();
+    const double *rb = T + 68u * hh + l5;
+    const double w32 = tb.inv[32 + l5];
+#pragma unroll
+    for (int mm = 0; mm < 16; mm++) {                                                   // t = 32
+        x[2 * mm] = rb[136 * mm];
+        x[2 * mm + 1] = rb[136 * mm + 34];
+        bfly(x[2 * mm], x[2 * mm + 1], w32, m);
+        swap32(x[2 * mm], x[2 * mm + 1]);
+        if ((mm & 3) == 3) SCHED_FENCE();
+    }
+#pragma unroll
+    for (int s = 0; s < 5; s++) {                                                       // t = 64 .. 1024
+        const int half = 1 << s;
+#pragma unroll
+        for (int j = 0; j < half; j++) {
+            const double w = tb.inv[64 * half + 64 * j + lane];
+#pragma unroll
+            for (int blk = 0; blk < (16 >> s); blk++) bfly(x[blk * 2 * half + j], x[blk * 2 * half + j + half], w, m);
+            if ((j & 3) == 3) SCHED_FENCE();
+        }
+        SCHED_FENCE();
+    }
+#pragma unroll
+    for (int e = 0; e < 32; e++) {
+        x[e] = slz_mulmod(x[e], tb.post[64 * e + lane], m);
+        if ((e & 7) == 7) SCHED_FENCE();
+    }
+}
+
+__global__ void __launch_bounds__(FUSED_THREADS) __attribute__((amdgpu_waves_per_eu(2, 2)))
+k_fused_blind_rotate_n2048(fused_args A) {
+    extern __shared__ double lds[];
+    const uint32_t lane = threadIdx.x & 63u;
+    const uint32_t w = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
+    const uint32_t q = w >> 1, h = w & 1u;
+    double *T = lds + w * TBUF;                      // this wave's buffer
+    double *Tsib = lds + (w ^ 1u) * TBUF;            // same prime, other row
+    double *Toth = lds + (w ^ 2u) * TBUF;            // other prime, same row
+    // staged ACC_h: words 0..1023 in the buffer of wave (0,h), words 1024..2047 in the buffer of wave (1,h)
+    const uint64_t *Sh = reinterpret_cast<const uint64_t *>(lds + h * TBUF + STAGE_OFF);
+    uint64_t *Smine = reinterpret_cast<uint64_t *>(T + STAGE_OFF);
+    const slz_mod m = A.mod[q];
+    const fused_prime_tabs tb0 = A.tab[q];
+
+    for (uint32_t c = blockIdx.x; c < A.batch; c += gridDim.x) {
+        const uint64_t *lwe = A.lwe_in + (size_t)c * (A.n + 1);
+        // ---- accumulator quarter: coefficients 64*(16q + e) + lane of component h ----
+        uint64_t acc[16];
+        if (h == 1) {
+            const uint32_t bt = slz_modswitch(lwe[A.n], FLOGN + 1);
+            const uint32_t r = (2 * FN - bt) & (2 * FN - 1);
+            const uint64_t *lut = A.luts + (size_t)(A.lut_idx ? A.lut_idx[c] : 0) * FN;
+#pragma unroll
+            for (int e = 0; e < 16; e++)
+                acc[e] = slz_rot_coeff([&](uint32_t j) { return lut[j]; }, 64u * (16u * q + e) + lane, r, FN);
+        } else {
+#pragma unroll
+            for (int e = 0; e < 16; e++) acc[e] = 0;
+        }
+
+        for (uint32_t step = 0; step < A.n_steps; step++) {
+            const uint32_t at = slz_modswitch(lwe[step], FLOGN + 1);
+            // The twiddle tables do not change between steps, so the compiler would hoist all ~110 per-lane table
+            // loads out of this loop and spill them; passing the pointers through an empty asm makes each step
+            // reload them (they stay in L1/L2).
+            fused_prime_tabs tb = tb0;
+            asm volatile("" : "+s"(tb.fwd), "+s"(tb.fwdB), "+s"(tb.inv), "+s"(tb.post));
+            // 1. stage my quarter, then read component h rotated and unrotated
+#pragma unroll
+            for (int e = 0; e < 16; e++) Smine[64 * e + lane] = acc[e];
+            __syncthreads();
+            double x[32];
+            {
+                uint32_t r = at, neg0 = 0;
+                if (r >= FN) { r -= FN; neg0 = 1; }
+#pragma unroll
+                for (int e = 0; e < 32; e++) {
+                    const uint32_t idx = 64u * e + lane;
+                    const uint32_t j = (idx - r) & (FN - 1);
+                    const uint32_t neg = neg0 ^ (idx < r ? 1u : 0u);
+                    const uint64_t a = Sh[(j >> 10) * (2u * TBUF) + (j & 1023u)];
+                    const uint64_t b = Sh[(e >= 16 ? 2u * TBUF : 0u) + (idx & 1023u)];
+                    const uint64_t lam = (neg ? (uint64_t)0 - a : a) - b;
+                    uint64_t v = slz_round_top_bits(lam, 23);
+                    x[e] = (double)slz_next_digit(v, 23);
+                }
+            }
+            __syncthreads();                          // every wave has read the staged accumulator
+            // 2. forward transform
+            fused_fwd(x, T, tb, m, lane);
+            // 3. row h of the GGSW times the digits: component h stays, component 1-h goes to the sibling
+            {
+                const double *krow = A.bskp + ((size_t)step * 4 + q * 2 + h) * 2 * FN;   // [n][prime][row][comp][N]
+                const double *kown = krow + (size_t)h * FN, *ksib = krow + (size_t)(1u - h) * FN;
+                wave_sync();
+#pragma unroll
+                for (int i = 0; i < 32; i++) {
+                    const double xv = x[i];
+                    T[64 * i + lane] = slz_mulmod(xv, ksib[64 * i + lane], m);
+                    x[i] = slz_mulmod(xv, kown[64 * i + lane], m);
+                    if ((i & 3) == 3) SCHED_FENCE();
+                }
+            }
+            __syncthreads();
+#pragma unroll
+            for (int i = 0; i < 32; i++) {
+                x[i] = slz_reduce(x[i] + Tsib[64 * i + lane], m);
+                if ((i & 7) == 7) SCHED_FENCE();
+            }
+            __syncthreads();                          // sibling has read my buffer before I reuse it
+            // 4. inverse transform
+            fused_inv(x, T, tb, m, lane);
+            // 5. exchange the half I do not lift with the other prime's wave, CRT, accumulate
+            wave_sync();
+            if (q == 0) {
+#pragma unroll
+                for (int e = 0; e < 16; e++) T[64 * e + lane] = x[16 + e];
+            } else {
+#pragma unroll
+                for (int e = 0; e < 16; e++) T[64 * e + lane] = x[e];
+            }
+            __syncthreads();
+            if (q == 0) {
+#pragma unroll
+                for (int e = 0; e < 16; e++) acc[e] += slz_crt64(x[e], Toth[64 * e + lane], A.mod[1], A.p1inv_mod_p2);
+            } else {
+#pragma unroll
+                for (int e = 0; e < 16; e++) acc[e] += slz_crt64(Toth[64 * e + lane], x[16 + e], A.mod[1], A.p1inv_mod_p2);
+            }
+        }
+
+        // ---- output: accumulator, or the extracted LWE ciphertext ----
+        if (A.acc_out) {
+            uint64_t *dst = A.acc_out + ((size_t)c * 2 + h) * FN;
+#pragma unroll
+            for (int e = 0; e < 16; e++) dst[64u * (16u * q + e) + lane] = acc[e];
+        }
+        if (A.lwe_out) {
+            uint64_t *dst = A.lwe_out + (size_t)c * (FN + 1);
+            if (h == 0) {
+#pragma unroll
+                for (int e = 0; e < 16; e++) {
+                    const uint32_t idx = 64u * (16u * q + e) + lane;
+                    if (idx == 0) dst[0] = acc[e];
+                    else dst[FN - idx] = (uint64_t)0 - acc[e];
+                }
+            } else if (q == 0 && lane == 0) {
+                dst[FN] = acc[0];
+            }
+        }
+        __syncthreads();                              // the next ciphertext reuses the LDS buffers
+    }
+}
+
+// ---- host side -----------------------------------------------------------------------------------
+
+int slz_fused_supported(const slz_params *p) {
+    return p->N == FN && p->k == 1 && p->pbs_level == 1 && p->pbs_base_log == 23;
+}
+
+int slz_fused_init(slz_ctx *ctx) {
+    // per-lane twiddles of the last five forward stages: stage with half-size t = 16 >> s, block `blk` of lane l
+    // is block (N/(2t) index) (32 l)/(2t) + blk of the whole transform
+    std::vector<double> host((size_t)2 * 31 * 64), nat(FN);
+    for (int q = 0; q < 2; q++) {
+        SLZ_HIP(hipMemcpy(nat.data(), ctx->tab[q].fwd, FN * sizeof(double), hipMemcpyDeviceToHost));
+        int kk = 0;
+        for (int s = 0; s < 5; s++) {
+            const uint32_t t = 16u >> s, mblk = FN / (2 * t);
+            for (uint32_t blk = 0; blk < (1u << s); blk++, kk++)
+                for (uint32_t l = 0; l < 64; l++) host[((size_t)q * 31 + kk) * 64 + l] = nat[mblk + (32 * l) / (2 * t) + blk];
+        }
+    }
+    SLZ_HIP(hipMalloc((void **)&ctx->fused_tab, host.size() * sizeof(double)));
+    SLZ_HIP(hipMemcpy(ctx->fused_tab, host.data(), host.size() * sizeof(double), hipMemcpyHostToDevice));
+    // worst-case bounds of the fixed reduction schedule (units of p); everything must stay below 2^53 = 8 p
+    double a = 1e-6;
+    for (int s = 0; s < 6; s++) a += slz_mulmod_bound(a);
+    if (a > 7.5) return SLZ_E_UNSUPPORTED;
+    a = 0.5 + 1e-9;
+    for (int s = 0; s < 5; s++) a += slz_mulmod_bound(a);
+    const double fwd_out = a;
+    if (fwd_out > 7.5 || 2 * slz_mulmod_bound(fwd_out) > 7.5) return SLZ_E_UNSUPPORTED;
+    a = 2.0 * (0.5 + 1e-9) * 2.0;                      // two multiply-free stages double the bound
+    for (int s = 2; s < 5; s++) a += slz_mulmod_bound(a);
+    if (a > 7.5) return SLZ_E_UNSUPPORTED;
+    a = 0.5 + 1e-9;
+    for (int s = 5; s < 11; s++) a += slz_mulmod_bound(a);
+    if (a > 7.5 || slz_mulmod_bound(a) > 1.95) return SLZ_E_UNSUPPORTED;   // slz_d2i needs |r| < 2 p
+    SLZ_HIP(hipFuncSetAttribute((const void *)k_fused_blind_rotate_n2048, hipFuncAttributeMaxDynamicSharedMemorySize,
+                                4 * TBUF * sizeof(double)));
+    return SLZ_OK;
+}
+
+void slz_fused_destroy(slz_ctx *ctx) {
+    if (ctx->fused_tab) (void)hipFree(ctx->fused_tab);
+    ctx->fused_tab = nullptr;
+}
+
+int slz_fused_blind_rotate(slz_ctx *ctx, const uint64_t *lwe_in, const uint64_t *luts, const uint32_t *lut_idx,
+                           const double *bskp, uint32_t n_steps, uint64_t *acc_out, uint64_t *lwe_out, uint32_t batch,
+                           hipStream_t s) {
+    fused_args A;
+    A.lwe_in = lwe_in; A.luts = luts; A.lut_idx = lut_idx; A.bskp = bskp; A.acc_out = acc_out; A.lwe_out = lwe_out;
+    A.n = ctx->prm.n; A.n_steps = n_steps; A.batch = batch;
+    for (int q = 0; q < 2; q++) {
+        A.tab[q].fwd = ctx->tab[q].fwd;
+        A.tab[q].fwdB = ctx->fused_tab + (size_t)q * 31 * 64;
+        A.tab[q].inv = ctx->tab[q].inv;
+        A.tab[q].post = ctx->tab[q].post;
+        A.mod[q] = ctx->mod[q];
+    }
+    A.p1inv_mod_p2 = ctx->p1inv_mod_p2;
+    const uint32_t resident = 2u * 256u;               // two workgroups (68 KiB of LDS each) per compute unit
+    const uint32_t grid = batch < resident ? batch : resident;
+    hipLaunchKernelGGL(k_fused_blind_rotate_n2048, dim3(grid), dim3(FUSED_THREADS), 4 * TBUF * sizeof(double), s, A);
+    SLZ_HIP(hipGetLastError());
+    return SLZ_OK;
+}

@@ -177,3 +177,74 @@ def test_error_codes(slz):
     short = ctypes.c_size_t(need.value - 8)
     assert L.slz_bsk_prepare(ctx._h, x.data_ptr(), x.data_ptr(), ctypes.byref(short), None) == -1
     torch.cuda.synchronize()
+
+
+# ---------------------------------------------------------------- fused kernel (N = 2048, k = 1, l = 1, base 2^23)
+
+def _fused_case(slz, orc, n, batch, **kw):
+    p = synth.CONFIGS[2].with_(n=n, name="cfg2_n%d" % n, **kw)
+    case = Case(slz, orc, p, batch, n_tables=3, raw_inputs=True)
+    assert case.ctx.path == "fused_n2048"
+    return p, case
+
+
+def test_fused_blind_rotation_states_match_oracle(slz, orc):
+    p, case = _fused_case(slz, orc, 6, 5)
+    for steps in (0, 1, 2, 3, p.n):
+        want = orc.blind_rotate_batch(p, case.cts, case.luts, case.lut_idx, case.keys.bsk, steps)
+        got = slz.to_host_u64(case.ctx.blind_rotate_batch(case.d_cts, case.d_luts, case.d_idx, case.d_bsk, steps))
+        assert np.array_equal(got, want), "accumulators differ after %d steps" % steps
+    want = orc.pbs_batch(p, case.cts, case.luts, case.lut_idx, case.keys.bsk)
+    got = slz.to_host_u64(case.ctx.pbs_batch(case.d_cts, case.d_luts, case.d_idx, case.d_bsk))
+    assert np.array_equal(got, want)
+    got0 = slz.to_host_u64(case.ctx.pbs_batch(case.d_cts, case.d_luts, None, case.d_bsk))
+    assert np.array_equal(got0, orc.pbs_batch(p, case.cts, case.luts, None, case.keys.bsk))
+
+
+def test_fused_rotation_amounts_cover_every_wrap_case(slz, orc):
+    # a~ = 0, 1, N-1, N, N+1, 2N-1 and lane/register boundaries, for the body rotation and the step rotations
+    p, case = _fused_case(slz, orc, 2, 12)
+    N = p.N
+    amounts = [0, 1, 63, 64, 1023, 1024, N - 1, N, N + 1, N + 1025, 2 * N - 64, 2 * N - 1]
+    cts = case.cts.copy()
+    for c, a in enumerate(amounts):
+        cts[c, 0] = np.uint64(a << (64 - 12))
+        cts[c, 1] = np.uint64(amounts[(c + 5) % 12] << (64 - 12))
+        cts[c, 2] = np.uint64(amounts[(c + 7) % 12] << (64 - 12))     # body
+    d_cts = slz.to_device_u64(cts)
+    for steps in (0, 1, 2):
+        want = orc.blind_rotate_batch(p, cts, case.luts, case.lut_idx, case.keys.bsk, steps)
+        got = slz.to_host_u64(case.ctx.blind_rotate_batch(d_cts, case.d_luts, case.d_idx, case.d_bsk, steps))
+        assert np.array_equal(got, want), "accumulators differ after %d steps" % steps
+
+
+def test_fused_worst_case_magnitudes_and_generic_agreement(slz, orc):
+    p, case = _fused_case(slz, orc, 4, 3)
+    bsk = case.keys.bsk.copy()
+    flat = bsk.reshape(-1)
+    flat[0::3] = np.uint64(1 << 63)
+    flat[1::3] = np.uint64((1 << 63) - 1)
+    luts = case.luts.copy()
+    luts[:, 0::2] = np.uint64((1 << 63) - (1 << 40))
+    luts[:, 1::2] = np.uint64(1 << 63)
+    d_bsk = case.ctx.bsk_prepare(slz.to_device_u64(bsk))
+    d_luts = slz.to_device_u64(luts)
+    want = orc.blind_rotate_batch(p, case.cts, luts, case.lut_idx, bsk, p.n)
+    got = slz.to_host_u64(case.ctx.blind_rotate_batch(case.d_cts, d_luts, case.d_idx, d_bsk, p.n))
+    assert np.array_equal(got, want)
+    case.ctx.set_option(slz.SLZ_OPT_FORCE_GENERIC, 1)
+    gen = slz.to_host_u64(case.ctx.blind_rotate_batch(case.d_cts, d_luts, case.d_idx, d_bsk, p.n))
+    assert np.array_equal(gen, want)
+
+
+def test_fused_more_ciphertexts_than_resident_workgroups(slz, orc):
+    # 600 ciphertexts > 512 resident workgroups: some workgroups process two; compare the fused path with the
+    # generic path on all, and with the oracle on a sample
+    p, case = _fused_case(slz, orc, 3, 600)
+    fused = slz.to_host_u64(case.ctx.pbs_batch(case.d_cts, case.d_luts, case.d_idx, case.d_bsk))
+    case.ctx.set_option(slz.SLZ_OPT_FORCE_GENERIC, 1)
+    gen = slz.to_host_u64(case.ctx.pbs_batch(case.d_cts, case.d_luts, case.d_idx, case.d_bsk))
+    assert np.array_equal(fused, gen)
+    idx = np.array([0, 1, 255, 511, 512, 513, 599])
+    want = orc.pbs_batch(p, case.cts[idx], case.luts, case.lut_idx[idx], case.keys.bsk)
+    assert np.array_equal(fused[idx], want)
