@@ -44,6 +44,8 @@ def main():
     ap.add_argument("--batch", type=int, default=0, help="override the configuration's batch size")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--generic", action="store_true", help="force the generic multi-kernel path")
+    ap.add_argument("--calib-copy", action="store_true",
+                    help="also run one plain device copy of 256 MiB (a known-size kernel to scale FETCH_SIZE/WRITE_SIZE by)")
     args = ap.parse_args()
     if args.gpus != 1:
         print("bench.py measures one GPU only (this build has no multi-GPU path); run with --gpus 1", file=sys.stderr)
@@ -86,6 +88,12 @@ def main():
     for _ in range(args.warmup):
         step()
     torch.cuda.synchronize()
+    if args.calib_copy:
+        src = torch.ones(256 * 1024 * 1024 // 8, dtype=torch.int64, device="cuda")
+        dst = torch.empty_like(src)
+        dst.copy_(src)
+        torch.cuda.synchronize()
+        del src, dst
 
     # ---- timed region: exactly K steps; per-call HIP events on the launch stream give the kernel split ----
     ev = [[torch.cuda.Event(enable_timing=True) for _ in range(3)] for _ in range(args.steps)]

@@ -24,13 +24,6 @@
 #define STAGE_OFF 1088u       // second half of a wave buffer: staging of 1024 accumulator words
 #define FUSED_THREADS 256
 
-struct fused_prime_tabs {
-    const double *fwd;        // natural forward table (fwd[m+i]); entries 1..63 are used as scalars / per half-wave
-    const double *fwdB;       // [31][64] per-lane twiddles of the last five forward stages
-    const double *inv;        // natural inverse table inv[t+j]
-    const double *post;       // post[j] = psi^-j / N
-};
-
 struct fused_args {
     const uint64_t *lwe_in;
     const uint64_t *luts;
@@ -39,10 +32,22 @@ struct fused_args {
     uint64_t *acc_out;
     uint64_t *lwe_out;
     uint32_t n, n_steps, batch;
-    fused_prime_tabs tab[2];
+    // per-lane twiddle tables in HBM/L2, one per prime
+    const double *fwd6[2];    // [32]      fwd[32 + x]: stage with stride 32 (one value per half-wave and register pair)
+    const double *fwdB[2];    // [31][64]  last five forward stages, entry (k, lane)
+    const double *inv[2];     // [N]       inv[t + j]: cyclic inverse twiddles (t >= 32 are per lane)
+    const double *post[2];    // [N]       psi^-j / N
+    // lane-uniform twiddles travel in the kernel argument segment and are read with scalar loads
+    double tw_fwd[2][32];     // fwd[m + blk], m + blk < 32: first five forward stages
+    double tw_inv[2][32];     // inv[t + j], t + j < 32: first five inverse stages
     slz_mod mod[2];
     double p1inv_mod_p2;
 };
+
+// keeps the instruction scheduler from moving anything across this point: table and key loads are issued by hand
+// one phase ahead of their use (software prefetch); letting the scheduler hoist them all spills, letting it sink
+// them to their first use exposes the full L2 latency at two waves per SIMD
+#define SCHED_FENCE() __builtin_amdgcn_sched_barrier(0)
 
 __device__ __forceinline__ void wave_sync() {
     // orders this wave's LDS writes before its later LDS reads of other lanes' data
@@ -61,9 +66,6 @@ __device__ __forceinline__ void swap32(double &a, double &b) {
     b = __hiloint2double((int)hi[1], (int)lo[1]);
 }
 
-// keeps the instruction scheduler from hoisting every table / key load of a phase to its start (which spills)
-#define SCHED_FENCE() __builtin_amdgcn_sched_barrier(0)
-
 __device__ __forceinline__ void bfly(double &a, double &b, double w, slz_mod m) {
     double v = slz_mulmod(b, w, m);
     b = a - v;
@@ -78,29 +80,37 @@ __device__ __forceinline__ void bfly_nomul(double &a, double &b) {
 // Forward transform.  In: x[e] = coefficient 64e + lane (|x| tiny).  Out: x[i] = spectrum position 32*lane + i,
 // |x| <= 4.9 p.  Worst-case growth per stage: a -> a + 1/2 + 0.1875 a (slz_mulmod_bound); six stages take the
 // digits to 4.81 p, one full reduction brings them back to p/2, five more stages end at 4.81 p.
-__device__ __forceinline__ void fused_fwd(double (&x)[32], double *T, const fused_prime_tabs &tb, slz_mod m, uint32_t lane) {
+// tw6 (stage with stride 32) is loaded by the caller; twA = lane-uniform twiddles; the per-lane twiddles of the last
+// five stages are fetched here before the first stage starts.  z is an opaque zero (see the kernel).
+__device__ __forceinline__ void fused_fwd(double (&x)[32], double *T, const double (&tw6)[16], const double *twA,
+                                          const double *fwdB, slz_mod m, uint32_t lane, int z) {
     const uint32_t hh = lane >> 5, l5 = lane & 31u;
+    double twB[31];
+#pragma unroll
+    for (int k = 0; k < 15; k++) twB[k] = fwdB[k * 64 + lane + z];
+    SCHED_FENCE();
 #pragma unroll
     for (int s = 0; s < 5; s++) {
         const int half = 16 >> s;
 #pragma unroll
         for (int blk = 0; blk < (1 << s); blk++) {
-            const double w = tb.fwd[(1 << s) + blk];            // uniform: block index comes from the register index
+            const double w = twA[(1 << s) + blk + z];            // uniform: block index comes from the register index
 #pragma unroll
             for (int j = 0; j < half; j++) bfly(x[blk * 2 * half + j], x[blk * 2 * half + j + half], w, m);
         }
-        SCHED_FENCE();
     }
     double *wb = T + 68u * hh + l5;
 #pragma unroll
     for (int mm = 0; mm < 16; mm++) {
         swap32(x[2 * mm], x[2 * mm + 1]);                        // stride 32: partner coefficient sits 32 lanes away
-        const double w = tb.fwd[32 + 2 * mm + hh];
-        bfly(x[2 * mm], x[2 * mm + 1], w, m);
+        bfly(x[2 * mm], x[2 * mm + 1], tw6[mm], m);
         wb[136 * mm] = slz_reduce(x[2 * mm], m);
         wb[136 * mm + 34] = slz_reduce(x[2 * mm + 1], m);
-        if ((mm & 3) == 3) SCHED_FENCE();
     }
+    SCHED_FENCE();
+#pragma unroll
+    for (int k = 15; k < 31; k++) twB[k] = fwdB[k * 64 + lane + z];
+    SCHED_FENCE();
     wave_sync();
     const double *rb = T + 34u * lane;
 #pragma unroll
@@ -115,37 +125,49 @@ __device__ __forceinline__ void fused_fwd(double (&x)[32], double *T, const fuse
         const int t = 16 >> s;
 #pragma unroll
         for (int blk = 0; blk < (1 << s); blk++) {
-            const double w = tb.fwdB[(kk++) * 64 + lane];
+            const double w = twB[kk++];
 #pragma unroll
             for (int j = 0; j < t; j++) bfly(x[blk * 2 * t + j], x[blk * 2 * t + j + t], w, m);
-            if (s == 4 && (blk & 3) == 3) SCHED_FENCE();
         }
-        SCHED_FENCE();
     }
 }
 
 // Inverse transform.  In: x[i] = spectrum position 32*lane + i, |x| <= 0.51 p.  Out: x[e] = coefficient 64e + lane
 // of the product polynomial mod p, |x| <= 1.7 p.  Bounds: stages 1,2 have unit twiddles (no multiply): 0.5 -> 1 -> 2;
 // stages 3..5 -> 2.88, 3.91, 5.15; reduce to 0.5; stages 6..11 -> 6.2; the final twist multiply gives 0.5 + 0.1875*6.2.
-__device__ __forceinline__ void fused_inv(double (&x)[32], double *T, const fused_prime_tabs &tb, slz_mod m, uint32_t lane) {
+__device__ __forceinline__ void fused_inv(double (&x)[32], double *T, const double *twS, const double *inv,
+                                          const double *post, slz_mod m, uint32_t lane, int z) {
     const uint32_t hh = lane >> 5, l5 = lane & 31u;
+    // per-lane twiddles of the stages with half-size 32 .. 1024, fetched before the first stage
+    double twL[31];
+    const double w32 = inv[32 + l5 + z];
+    {
+        int kk = 0;
+#pragma unroll
+        for (int s = 0; s < 4; s++)
+#pragma unroll
+            for (int j = 0; j < (1 << s); j++) twL[kk++] = inv[64 * (1 << s) + 64 * j + lane + z];
+    }
+    SCHED_FENCE();
 #pragma unroll
     for (int i = 0; i < 32; i += 2) bfly_nomul(x[i], x[i + 1]);                       // t = 1
+    {
+        const double w = twS[3 + z];
 #pragma unroll
-    for (int blk = 0; blk < 8; blk++) {                                                 // t = 2
-        bfly_nomul(x[4 * blk], x[4 * blk + 2]);
-        bfly(x[4 * blk + 1], x[4 * blk + 3], tb.inv[3], m);
+        for (int blk = 0; blk < 8; blk++) {                                             // t = 2
+            bfly_nomul(x[4 * blk], x[4 * blk + 2]);
+            bfly(x[4 * blk + 1], x[4 * blk + 3], w, m);
+        }
     }
 #pragma unroll
     for (int s = 2; s < 5; s++) {                                                       // t = 4, 8, 16
         const int t = 1 << s;
 #pragma unroll
         for (int j = 0; j < t; j++) {
-            const double w = tb.inv[t + j];                                             // uniform: depends on j only
+            const double w = twS[t + j + z];                                            // uniform: depends on j only
 #pragma unroll
             for (int blk = 0; blk < (16 >> s); blk++) bfly(x[blk * 2 * t + j], x[blk * 2 * t + j + t], w, m);
         }
-        SCHED_FENCE();
     }
     wave_sync();                                                                        // earlier reads of T are done
     double *wb = T + 34u * lane;
@@ -158,32 +180,43 @@ __device__ __forceinline__ void fused_inv(double (&x)[32], double *T, const fuse
     }
     wave_sync();
     const double *rb = T + 68u * hh + l5;
-    const double w32 = tb.inv[32 + l5];
 #pragma unroll
     for (int mm = 0; mm < 16; mm++) {                                                   // t = 32
         x[2 * mm] = rb[136 * mm];
         x[2 * mm + 1] = rb[136 * mm + 34];
         bfly(x[2 * mm], x[2 * mm + 1], w32, m);
         swap32(x[2 * mm], x[2 * mm + 1]);
-        if ((mm & 3) == 3) SCHED_FENCE();
     }
+    SCHED_FENCE();
+#pragma unroll
+    for (int j = 0; j < 16; j++) twL[15 + j] = inv[64 * 16 + 64 * j + lane + z];
+    SCHED_FENCE();
+    double pw[32];
+    int kk = 0;
 #pragma unroll
     for (int s = 0; s < 5; s++) {                                                       // t = 64 .. 1024
         const int half = 1 << s;
+        if (s == 3) {
+            SCHED_FENCE();
+#pragma unroll
+            for (int e = 0; e < 16; e++) pw[e] = post[64 * e + lane + z];
+            SCHED_FENCE();
+        }
+        if (s == 4) {
+            SCHED_FENCE();
+#pragma unroll
+            for (int e = 16; e < 32; e++) pw[e] = post[64 * e + lane + z];
+            SCHED_FENCE();
+        }
 #pragma unroll
         for (int j = 0; j < half; j++) {
-            const double w = tb.inv[64 * half + 64 * j + lane];
+            const double w = twL[kk++];
 #pragma unroll
             for (int blk = 0; blk < (16 >> s); blk++) bfly(x[blk * 2 * half + j], x[blk * 2 * half + j + half], w, m);
-            if ((j & 3) == 3) SCHED_FENCE();
         }
-        SCHED_FENCE();
     }
 #pragma unroll
-    for (int e = 0; e < 32; e++) {
-        x[e] = slz_mulmod(x[e], tb.post[64 * e + lane], m);
-        if ((e & 7) == 7) SCHED_FENCE();
-    }
+    for (int e = 0; e < 32; e++) x[e] = slz_mulmod(x[e], pw[e], m);
 }
 
 __global__ void __launch_bounds__(FUSED_THREADS) __attribute__((amdgpu_waves_per_eu(2, 2)))
@@ -199,7 +232,9 @@ k_fused_blind_rotate_n2048(fused_args A) {
     const uint64_t *Sh = reinterpret_cast<const uint64_t *>(lds + h * TBUF + STAGE_OFF);
     uint64_t *Smine = reinterpret_cast<uint64_t *>(T + STAGE_OFF);
     const slz_mod m = A.mod[q];
-    const fused_prime_tabs tb0 = A.tab[q];
+    const double *fwd6 = A.fwd6[q], *fwdB = A.fwdB[q], *invt = A.inv[q], *post = A.post[q];
+    const double *twA = A.tw_fwd[q], *twS = A.tw_inv[q];
+    const uint32_t hh = lane >> 5;
 
     for (uint32_t c = blockIdx.x; c < A.batch; c += gridDim.x) {
         const uint64_t *lwe = A.lwe_in + (size_t)c * (A.n + 1);
@@ -218,12 +253,17 @@ k_fused_blind_rotate_n2048(fused_args A) {
         }
 
         for (uint32_t step = 0; step < A.n_steps; step++) {
+            // The tables do not change between steps, so the compiler would hoist their ~170 per-lane loads out of
+            // this loop and spill them.  An opaque zero added to every table index makes each step issue them again.
+            int z;
+            asm volatile("s_mov_b32 %0, 0" : "=s"(z));
             const uint32_t at = slz_modswitch(lwe[step], FLOGN + 1);
-            // The twiddle tables do not change between steps, so the compiler would hoist all ~110 per-lane table
-            // loads out of this loop and spill them; passing the pointers through an empty asm makes each step
-            // reload them (they stay in L1/L2).
-            fused_prime_tabs tb = tb0;
-            asm volatile("" : "+s"(tb.fwd), "+s"(tb.fwdB), "+s"(tb.inv), "+s"(tb.post));
+            const double *krow = A.bskp + ((size_t)step * 4 + q * 2 + h) * 2 * FN + z;   // [n][prime][row][comp][N]
+            const double *kown = krow + (size_t)h * FN, *ksib = krow + (size_t)(1u - h) * FN;
+            double tw6[16];
+#pragma unroll
+            for (int mm = 0; mm < 16; mm++) tw6[mm] = fwd6[2 * mm + hh + z];
+            SCHED_FENCE();
             // 1. stage my quarter, then read component h rotated and unrotated
 #pragma unroll
             for (int e = 0; e < 16; e++) Smine[64 * e + lane] = acc[e];
@@ -246,29 +286,39 @@ k_fused_blind_rotate_n2048(fused_args A) {
             }
             __syncthreads();                          // every wave has read the staged accumulator
             // 2. forward transform
-            fused_fwd(x, T, tb, m, lane);
-            // 3. row h of the GGSW times the digits: component h stays, component 1-h goes to the sibling
+            fused_fwd(x, T, tw6, twA, fwdB, m, lane, z);
+            // 3. row h of the GGSW times the digits: component h stays, component 1-h goes to the sibling.
+            //    Key words are fetched eight positions (two chunks of 2 x 8 doubles in flight) ahead.
             {
-                const double *krow = A.bskp + ((size_t)step * 4 + q * 2 + h) * 2 * FN;   // [n][prime][row][comp][N]
-                const double *kown = krow + (size_t)h * FN, *ksib = krow + (size_t)(1u - h) * FN;
+                double ks[2][8], ko[2][8];
+#pragma unroll
+                for (int i = 0; i < 8; i++) { ks[0][i] = ksib[64 * i + lane]; ko[0][i] = kown[64 * i + lane]; }
                 wave_sync();
 #pragma unroll
-                for (int i = 0; i < 32; i++) {
-                    const double xv = x[i];
-                    T[64 * i + lane] = slz_mulmod(xv, ksib[64 * i + lane], m);
-                    x[i] = slz_mulmod(xv, kown[64 * i + lane], m);
-                    if ((i & 3) == 3) SCHED_FENCE();
+                for (int ch = 0; ch < 4; ch++) {
+                    SCHED_FENCE();
+                    if (ch < 3) {
+#pragma unroll
+                        for (int i = 0; i < 8; i++) {
+                            ks[(ch + 1) & 1][i] = ksib[64 * (8 * (ch + 1) + i) + lane];
+                            ko[(ch + 1) & 1][i] = kown[64 * (8 * (ch + 1) + i) + lane];
+                        }
+                    }
+                    SCHED_FENCE();
+#pragma unroll
+                    for (int i = 0; i < 8; i++) {
+                        const double xv = x[8 * ch + i];
+                        T[64 * (8 * ch + i) + lane] = slz_mulmod(xv, ks[ch & 1][i], m);
+                        x[8 * ch + i] = slz_mulmod(xv, ko[ch & 1][i], m);
+                    }
                 }
             }
             __syncthreads();
 #pragma unroll
-            for (int i = 0; i < 32; i++) {
-                x[i] = slz_reduce(x[i] + Tsib[64 * i + lane], m);
-                if ((i & 7) == 7) SCHED_FENCE();
-            }
+            for (int i = 0; i < 32; i++) x[i] = slz_reduce(x[i] + Tsib[64 * i + lane], m);
             __syncthreads();                          // sibling has read my buffer before I reuse it
             // 4. inverse transform
-            fused_inv(x, T, tb, m, lane);
+            fused_inv(x, T, twS, invt, post, m, lane, z);
             // 5. exchange the half I do not lift with the other prime's wave, CRT, accumulate
             wave_sync();
             if (q == 0) {
@@ -330,6 +380,10 @@ int slz_fused_init(slz_ctx *ctx) {
                 for (uint32_t l = 0; l < 64; l++) host[((size_t)q * 31 + kk) * 64 + l] = nat[mblk + (32 * l) / (2 * t) + blk];
         }
     }
+    for (int q = 0; q < 2; q++) {
+        SLZ_HIP(hipMemcpy(ctx->fused_scalars[q][0], ctx->tab[q].fwd, 32 * sizeof(double), hipMemcpyDeviceToHost));
+        SLZ_HIP(hipMemcpy(ctx->fused_scalars[q][1], ctx->tab[q].inv, 32 * sizeof(double), hipMemcpyDeviceToHost));
+    }
     SLZ_HIP(hipMalloc((void **)&ctx->fused_tab, host.size() * sizeof(double)));
     SLZ_HIP(hipMemcpy(ctx->fused_tab, host.data(), host.size() * sizeof(double), hipMemcpyHostToDevice));
     // worst-case bounds of the fixed reduction schedule (units of p); everything must stay below 2^53 = 8 p
@@ -363,11 +417,12 @@ int slz_fused_blind_rotate(slz_ctx *ctx, const uint64_t *lwe_in, const uint64_t 
     A.lwe_in = lwe_in; A.luts = luts; A.lut_idx = lut_idx; A.bskp = bskp; A.acc_out = acc_out; A.lwe_out = lwe_out;
     A.n = ctx->prm.n; A.n_steps = n_steps; A.batch = batch;
     for (int q = 0; q < 2; q++) {
-        A.tab[q].fwd = ctx->tab[q].fwd;
-        A.tab[q].fwdB = ctx->fused_tab + (size_t)q * 31 * 64;
-        A.tab[q].inv = ctx->tab[q].inv;
-        A.tab[q].post = ctx->tab[q].post;
+        A.fwd6[q] = ctx->tab[q].fwd + 32;
+        A.fwdB[q] = ctx->fused_tab + (size_t)q * 31 * 64;
+        A.inv[q] = ctx->tab[q].inv;
+        A.post[q] = ctx->tab[q].post;
         A.mod[q] = ctx->mod[q];
+        for (int x = 0; x < 32; x++) { A.tw_fwd[q][x] = ctx->fused_scalars[q][0][x]; A.tw_inv[q][x] = ctx->fused_scalars[q][1][x]; }
     }
     A.p1inv_mod_p2 = ctx->p1inv_mod_p2;
     const uint32_t resident = 2u * 256u;               // two workgroups (68 KiB of LDS each) per compute unit

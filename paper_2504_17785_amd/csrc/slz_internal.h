@@ -47,6 +47,7 @@ struct slz_ctx {
     double p1inv_mod_p2;      // p1^{-1} mod p2 (centred)
     slz_tables tab[2];
     double *fused_tab;        // tables re-laid-out for the fused kernel (or null)
+    double fused_scalars[2][2][32];   // [prime][forward, inverse]: the lane-uniform twiddles of the fused kernel
     // scratch for the generic path, sized for max_batch
     uint64_t *acc;            // [max_batch][k+1][N]
     double *dig;              // [max_batch][(k+1)l][N]
