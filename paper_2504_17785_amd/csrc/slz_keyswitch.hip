@@ -3,9 +3,9 @@
 #include "slz_internal.h"
 #include "slz_modarith.h"
 
-#define KS_THREADS 256
+#define KS_THREADS 128
 #define KS_TB 8            // ciphertexts per workgroup (each key word is reused KS_TB times from a register)
-#define KS_IC 32           // mask words decomposed per LDS refill
+#define KS_IC 16           // mask words decomposed per LDS refill
 #define KS_MAX_L 16
 
 __global__ void __launch_bounds__(KS_THREADS)
@@ -18,53 +18,59 @@ k_ks_init(const uint64_t *__restrict__ lwe_in, uint64_t *__restrict__ out, uint3
 }
 
 // out[c][x] -= sum_{i in segment} sum_j d_j(a'_{c,i}) * KSK[i][j][x]
-// grid: (x tiles, ciphertext tiles, segments of the mask index)
+// grid: (x tiles, ciphertext tiles, segments of the mask index).
+// The signed digit d in [-B/2, B/2) is held as u = d + B/2 >= 0, so that a product with a 64-bit key word is two
+// 32x32+64 multiply-adds (low and high half of the word, separate 64-bit accumulators):
+//   sum d w = sum u w - (B/2) sum w,   sum u w = accL + 2^32 accH  (mod 2^64).
 __global__ void __launch_bounds__(KS_THREADS)
 k_keyswitch(const uint64_t *__restrict__ lwe_in, const uint64_t *__restrict__ ksk, uint64_t *__restrict__ out, uint32_t kN,
             uint32_t n, uint32_t beta, uint32_t l, uint32_t batch, uint32_t seg_len) {
-    __shared__ int32_t dig[KS_IC * KS_MAX_L * KS_TB];      // [ii][j][c]
+    __shared__ __attribute__((aligned(16))) uint32_t dig[KS_IC * KS_MAX_L * KS_TB];      // [ii][j][c]
     const uint32_t x = blockIdx.x * KS_THREADS + threadIdx.x;
     const uint32_t c0 = blockIdx.y * KS_TB;
     const uint32_t i_begin = blockIdx.z * seg_len;
     const uint32_t i_end = min(kN, i_begin + seg_len);
     const bool active = x <= n;
-    uint64_t acc[KS_TB];
+    const uint32_t half_b = 1u << (beta - 1);
+    uint64_t accL[KS_TB], accH[KS_TB], sumw = 0;
 #pragma unroll
-    for (int c = 0; c < KS_TB; c++) acc[c] = 0;
+    for (int c = 0; c < KS_TB; c++) { accL[c] = 0; accH[c] = 0; }
     for (uint32_t ib = i_begin; ib < i_end; ib += KS_IC) {
         __syncthreads();
-        // decompose KS_TB x KS_IC mask words (one per thread)
-        {
-            uint32_t c = threadIdx.x / KS_IC, ii = threadIdx.x % KS_IC;      // KS_THREADS == KS_TB*KS_IC
+        {   // decompose KS_TB x KS_IC mask words, one per thread; words past the end give u = B/2 (digit 0)
+            uint32_t c = threadIdx.x / KS_IC, ii = threadIdx.x % KS_IC;
             uint32_t i = ib + ii;
             uint64_t v = 0;
             if (c0 + c < batch && i < i_end) v = slz_round_top_bits(lwe_in[(size_t)(c0 + c) * (kN + 1) + i], beta * l);
-            for (int j = (int)l - 1; j >= 0; j--) {
-                uint64_t B = 1ull << beta, d = v & (B - 1);
-                v >>= beta;
-                int64_t sd = (int64_t)d;
-                if (d >= (B >> 1)) { sd -= (int64_t)B; v += 1; }
-                dig[(ii * l + j) * KS_TB + c] = (int32_t)sd;
-            }
+            for (int j = (int)l - 1; j >= 0; j--) dig[(ii * l + j) * KS_TB + c] = (uint32_t)(slz_next_digit(v, beta) + (int32_t)half_b);
         }
         __syncthreads();
         if (active) {
-            uint32_t cnt = min((uint32_t)KS_IC, i_end - ib);
-            for (uint32_t ii = 0; ii < cnt; ii++) {
-                const uint64_t *row = ksk + ((size_t)(ib + ii) * l) * (n + 1) + x;
-                for (uint32_t j = 0; j < l; j++) {
-                    uint64_t w = row[(size_t)j * (n + 1)];
-                    const int32_t *d = &dig[(ii * l + j) * KS_TB];
+            const uint32_t cnt = min((uint32_t)KS_IC, i_end - ib) * l;
+            const uint64_t *row = ksk + ((size_t)ib * l) * (n + 1) + x;
+            for (uint32_t r = 0; r < cnt; r++) {
+                const uint64_t w = row[(size_t)r * (n + 1)];
+                const uint32_t wl = (uint32_t)w, wh = (uint32_t)(w >> 32);
+                const uint4 d0 = *reinterpret_cast<const uint4 *>(&dig[r * KS_TB]);
+                const uint4 d1 = *reinterpret_cast<const uint4 *>(&dig[r * KS_TB + 4]);
+                const uint32_t u[KS_TB] = {d0.x, d0.y, d0.z, d0.w, d1.x, d1.y, d1.z, d1.w};
+                sumw += w;
 #pragma unroll
-                    for (int c = 0; c < KS_TB; c++) acc[c] -= (uint64_t)(int64_t)d[c] * w;
+                for (int c = 0; c < KS_TB; c++) {
+                    accL[c] += (uint64_t)u[c] * wl;
+                    accH[c] += (uint64_t)u[c] * wh;
                 }
             }
         }
     }
     if (active) {
+        const uint64_t corr = sumw * (uint64_t)half_b;
 #pragma unroll
         for (int c = 0; c < KS_TB; c++)
-            if (c0 + c < batch) atomicAdd((unsigned long long *)&out[(size_t)(c0 + c) * (n + 1) + x], (unsigned long long)acc[c]);
+            if (c0 + c < batch) {
+                const uint64_t delta = corr - (accL[c] + (accH[c] << 32));
+                atomicAdd((unsigned long long *)&out[(size_t)(c0 + c) * (n + 1) + x], (unsigned long long)delta);
+            }
     }
 }
 
@@ -80,9 +86,10 @@ int slz_keyswitch_launch(slz_ctx *ctx, const uint64_t *lwe_in, const uint64_t *k
     uint32_t xt = (n + 1 + KS_THREADS - 1) / KS_THREADS, ct = (batch + KS_TB - 1) / KS_TB;
     // enough segments of the mask index to give the 256 CUs several workgroups each
     uint32_t segs = 1;
-    while ((size_t)xt * ct * segs < 2048 && segs < kN / (4 * KS_IC)) segs *= 2;
+    while ((size_t)xt * ct * segs < 4096 && segs < kN / (4 * KS_IC)) segs *= 2;
     uint32_t seg_len = ((kN + segs - 1) / segs + KS_IC - 1) / KS_IC * KS_IC;
     segs = (kN + seg_len - 1) / seg_len;
+    if (ct > 65535 || segs > 65535) return SLZ_E_UNSUPPORTED;
     hipLaunchKernelGGL(k_keyswitch, dim3(xt, ct, segs), dim3(KS_THREADS), 0, s, lwe_in, ksk, lwe_out, kN, n, p.ks_base_log,
                        p.ks_level, batch, seg_len);
     SLZ_HIP(hipGetLastError());
