@@ -17,6 +17,7 @@
 #include "slz_internal.h"
 #include "slz_modarith.h"
 #include <vector>
+#include <cstdio>
 
 #define FN 2048u
 #define FLOGN 11u
@@ -42,12 +43,29 @@ struct fused_args {
     double tw_inv[2][32];     // inv[t + j], t + j < 32: first five inverse stages
     slz_mod mod[2];
     double p1inv_mod_p2;
+#ifdef SLZ_PHASE_TIMING
+    unsigned long long *dbg;  // [4 waves][16 marks]: cycles spent before each mark, summed over the steps of block 0
+#endif
 };
+
+#ifdef SLZ_PHASE_TIMING
+#define MARK(k) do { if (blockIdx.x == 0) { unsigned long long t_ = __builtin_amdgcn_s_memtime(); \
+                     if (lane == 0) A.dbg[w * 16 + (k)] += t_ - tprev; tprev = t_; } } while (0)
+#else
+#define MARK(k) do { } while (0)
+#endif
 
 // keeps the instruction scheduler from moving anything across this point: table and key loads are issued by hand
 // one phase ahead of their use (software prefetch); letting the scheduler hoist them all spills, letting it sink
 // them to their first use exposes the full L2 latency at two waves per SIMD
 #define SCHED_FENCE() __builtin_amdgcn_sched_barrier(0)
+
+// Per-lane table load as "uniform base (SGPR pair) + 32-bit lane offset": keeps one address register for all
+// tables instead of a 64-bit address pair per load group (those pairs spill, and a spill reload drains the
+// whole queue of prefetches in flight).
+__device__ __forceinline__ double ldl(const double *uniform_base, uint32_t lane_byte_off) {
+    return *reinterpret_cast<const double *>(reinterpret_cast<const char *>(uniform_base) + lane_byte_off);
+}
 
 __device__ __forceinline__ void wave_sync() {
     // orders this wave's LDS writes before its later LDS reads of other lanes' data
@@ -87,7 +105,7 @@ __device__ __forceinline__ void fused_fwd(double (&x)[32], double *T, const doub
     const uint32_t hh = lane >> 5, l5 = lane & 31u;
     double twB[31];
 #pragma unroll
-    for (int k = 0; k < 15; k++) twB[k] = fwdB[k * 64 + lane + z];
+    for (int k = 0; k < 15; k++) twB[k] = ldl(fwdB + k * 64 + z, lane * 8u);
     SCHED_FENCE();
 #pragma unroll
     for (int s = 0; s < 5; s++) {
@@ -109,7 +127,7 @@ __device__ __forceinline__ void fused_fwd(double (&x)[32], double *T, const doub
     }
     SCHED_FENCE();
 #pragma unroll
-    for (int k = 15; k < 31; k++) twB[k] = fwdB[k * 64 + lane + z];
+    for (int k = 15; k < 31; k++) twB[k] = ldl(fwdB + k * 64 + z, lane * 8u);
     SCHED_FENCE();
     wave_sync();
     const double *rb = T + 34u * lane;
@@ -140,13 +158,13 @@ __device__ __forceinline__ void fused_inv(double (&x)[32], double *T, const doub
     const uint32_t hh = lane >> 5, l5 = lane & 31u;
     // per-lane twiddles of the stages with half-size 32 .. 1024, fetched before the first stage
     double twL[31];
-    const double w32 = inv[32 + l5 + z];
+    const double w32 = ldl(inv + 32 + z, l5 * 8u);
     {
         int kk = 0;
 #pragma unroll
         for (int s = 0; s < 4; s++)
 #pragma unroll
-            for (int j = 0; j < (1 << s); j++) twL[kk++] = inv[64 * (1 << s) + 64 * j + lane + z];
+            for (int j = 0; j < (1 << s); j++) twL[kk++] = ldl(inv + 64 * (1 << s) + 64 * j + z, lane * 8u);
     }
     SCHED_FENCE();
 #pragma unroll
@@ -189,7 +207,7 @@ __device__ __forceinline__ void fused_inv(double (&x)[32], double *T, const doub
     }
     SCHED_FENCE();
 #pragma unroll
-    for (int j = 0; j < 16; j++) twL[15 + j] = inv[64 * 16 + 64 * j + lane + z];
+    for (int j = 0; j < 16; j++) twL[15 + j] = ldl(inv + 64 * 16 + 64 * j + z, lane * 8u);
     SCHED_FENCE();
     double pw[32];
     int kk = 0;
@@ -199,13 +217,13 @@ __device__ __forceinline__ void fused_inv(double (&x)[32], double *T, const doub
         if (s == 3) {
             SCHED_FENCE();
 #pragma unroll
-            for (int e = 0; e < 16; e++) pw[e] = post[64 * e + lane + z];
+            for (int e = 0; e < 16; e++) pw[e] = ldl(post + 64 * e + z, lane * 8u);
             SCHED_FENCE();
         }
         if (s == 4) {
             SCHED_FENCE();
 #pragma unroll
-            for (int e = 16; e < 32; e++) pw[e] = post[64 * e + lane + z];
+            for (int e = 16; e < 32; e++) pw[e] = ldl(post + 64 * e + z, lane * 8u);
             SCHED_FENCE();
         }
 #pragma unroll
@@ -257,17 +275,22 @@ k_fused_blind_rotate_n2048(fused_args A) {
             // this loop and spill them.  An opaque zero added to every table index makes each step issue them again.
             int z;
             asm volatile("s_mov_b32 %0, 0" : "=s"(z));
+#ifdef SLZ_PHASE_TIMING
+            unsigned long long tprev = __builtin_amdgcn_s_memtime();
+#endif
             const uint32_t at = slz_modswitch(lwe[step], FLOGN + 1);
             const double *krow = A.bskp + ((size_t)step * 4 + q * 2 + h) * 2 * FN + z;   // [n][prime][row][comp][N]
             const double *kown = krow + (size_t)h * FN, *ksib = krow + (size_t)(1u - h) * FN;
             double tw6[16];
 #pragma unroll
-            for (int mm = 0; mm < 16; mm++) tw6[mm] = fwd6[2 * mm + hh + z];
+            for (int mm = 0; mm < 16; mm++) tw6[mm] = ldl(fwd6 + 2 * mm + z, hh * 8u);
             SCHED_FENCE();
             // 1. stage my quarter, then read component h rotated and unrotated
 #pragma unroll
             for (int e = 0; e < 16; e++) Smine[64 * e + lane] = acc[e];
+            MARK(0);
             __syncthreads();
+            MARK(1);
             double x[32];
             {
                 uint32_t r = at, neg0 = 0;
@@ -284,15 +307,18 @@ k_fused_blind_rotate_n2048(fused_args A) {
                     x[e] = (double)slz_next_digit(v, 23);
                 }
             }
+            MARK(2);
             __syncthreads();                          // every wave has read the staged accumulator
+            MARK(3);
             // 2. forward transform
             fused_fwd(x, T, tw6, twA, fwdB, m, lane, z);
+            MARK(4);
             // 3. row h of the GGSW times the digits: component h stays, component 1-h goes to the sibling.
             //    Key words are fetched eight positions (two chunks of 2 x 8 doubles in flight) ahead.
             {
                 double ks[2][8], ko[2][8];
 #pragma unroll
-                for (int i = 0; i < 8; i++) { ks[0][i] = ksib[64 * i + lane]; ko[0][i] = kown[64 * i + lane]; }
+                for (int i = 0; i < 8; i++) { ks[0][i] = ldl(ksib + 64 * i, lane * 8u); ko[0][i] = ldl(kown + 64 * i, lane * 8u); }
                 wave_sync();
 #pragma unroll
                 for (int ch = 0; ch < 4; ch++) {
@@ -300,8 +326,8 @@ k_fused_blind_rotate_n2048(fused_args A) {
                     if (ch < 3) {
 #pragma unroll
                         for (int i = 0; i < 8; i++) {
-                            ks[(ch + 1) & 1][i] = ksib[64 * (8 * (ch + 1) + i) + lane];
-                            ko[(ch + 1) & 1][i] = kown[64 * (8 * (ch + 1) + i) + lane];
+                            ks[(ch + 1) & 1][i] = ldl(ksib + 64 * (8 * (ch + 1) + i), lane * 8u);
+                            ko[(ch + 1) & 1][i] = ldl(kown + 64 * (8 * (ch + 1) + i), lane * 8u);
                         }
                     }
                     SCHED_FENCE();
@@ -313,12 +339,17 @@ k_fused_blind_rotate_n2048(fused_args A) {
                     }
                 }
             }
+            MARK(5);
             __syncthreads();
+            MARK(6);
 #pragma unroll
             for (int i = 0; i < 32; i++) x[i] = slz_reduce(x[i] + Tsib[64 * i + lane], m);
+            MARK(7);
             __syncthreads();                          // sibling has read my buffer before I reuse it
+            MARK(8);
             // 4. inverse transform
             fused_inv(x, T, twS, invt, post, m, lane, z);
+            MARK(9);
             // 5. exchange the half I do not lift with the other prime's wave, CRT, accumulate
             wave_sync();
             if (q == 0) {
@@ -328,7 +359,9 @@ k_fused_blind_rotate_n2048(fused_args A) {
 #pragma unroll
                 for (int e = 0; e < 16; e++) T[64 * e + lane] = x[e];
             }
+            MARK(10);
             __syncthreads();
+            MARK(11);
             if (q == 0) {
 #pragma unroll
                 for (int e = 0; e < 16; e++) acc[e] += slz_crt64(x[e], Toth[64 * e + lane], A.mod[1], A.p1inv_mod_p2);
@@ -336,6 +369,7 @@ k_fused_blind_rotate_n2048(fused_args A) {
 #pragma unroll
                 for (int e = 0; e < 16; e++) acc[e] += slz_crt64(Toth[64 * e + lane], x[16 + e], A.mod[1], A.p1inv_mod_p2);
             }
+            MARK(12);
         }
 
         // ---- output: accumulator, or the extracted LWE ciphertext ----
@@ -425,9 +459,29 @@ int slz_fused_blind_rotate(slz_ctx *ctx, const uint64_t *lwe_in, const uint64_t 
         for (int x = 0; x < 32; x++) { A.tw_fwd[q][x] = ctx->fused_scalars[q][0][x]; A.tw_inv[q][x] = ctx->fused_scalars[q][1][x]; }
     }
     A.p1inv_mod_p2 = ctx->p1inv_mod_p2;
+#ifdef SLZ_PHASE_TIMING
+    static unsigned long long *dbg = nullptr;
+    if (!dbg) { SLZ_HIP(hipMalloc((void **)&dbg, 64 * 8)); }
+    SLZ_HIP(hipMemsetAsync(dbg, 0, 64 * 8, s));
+    A.dbg = dbg;
+#endif
     const uint32_t resident = 2u * 256u;               // two workgroups (68 KiB of LDS each) per compute unit
     const uint32_t grid = batch < resident ? batch : resident;
     hipLaunchKernelGGL(k_fused_blind_rotate_n2048, dim3(grid), dim3(FUSED_THREADS), 4 * TBUF * sizeof(double), s, A);
     SLZ_HIP(hipGetLastError());
+#ifdef SLZ_PHASE_TIMING
+    {
+        unsigned long long h[64];
+        SLZ_HIP(hipMemcpy(h, dbg, sizeof(h), hipMemcpyDeviceToHost));
+        static const char *names[13] = {"stage-write", "B1", "decompose", "B2", "fwd", "pointwise", "B3", "sum", "B4", "inverse",
+                                        "xchg-write", "B5", "crt"};
+        const double steps = (double)n_steps * ((batch + grid - 1) / grid);
+        for (int w = 0; w < 4; w++) {
+            fprintf(stderr, "wave %d cycles/step:", w);
+            for (int k = 0; k < 13; k++) fprintf(stderr, " %s=%.0f", names[k], (double)h[w * 16 + k] / steps);
+            fprintf(stderr, "\n");
+        }
+    }
+#endif
     return SLZ_OK;
 }
