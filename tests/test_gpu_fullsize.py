@@ -1,0 +1,116 @@
+"""Full-size GPU checks in the launch configuration bench.py times: real keys, real encryptions, the whole batch
+decrypt-checked against the lookup table, and sampled ciphertexts compared bit for bit with the CPU oracle (one
+oracle PBS at these parameters is about 1.2e10 multiply-adds, so only a sample is affordable)."""
+import numpy as np
+import pytest
+
+import synth
+
+pytestmark = pytest.mark.gpu
+
+torch = pytest.importorskip("torch")
+
+
+@pytest.fixture(scope="module")
+def slz():
+    if not torch.cuda.is_available():
+        pytest.fail("the gpu tests need a GPU: torch.cuda.is_available() is False")
+    import paper_2504_17785_amd as m
+    m.lib()
+    return m
+
+
+def _expected(tables, lut_idx, msgs, t):
+    """Table value for messages in [0, t); the negacyclic extension -f(m - t) mod 2t for m in [t, 2t)."""
+    msgs = msgs.astype(np.int64)
+    f = tables[lut_idx, msgs % t].astype(np.int64)
+    return np.where(msgs < t, f, (-f) % (2 * t)).astype(np.uint64)
+
+
+def _run_config(slz, orc, cfg, sample):
+    p = synth.CONFIGS[cfg]
+    keys = orc.Keys(p, synth)
+    tables = synth.config_tables(cfg)
+    luts = slz.lut_encode(p, tables)
+    assert np.array_equal(luts, orc.lut_encode(p, tables))
+    lut_idx = synth.config_lut_idx(cfg)
+    msgs = synth.config_messages(cfg)
+    cts = orc.encrypt_messages(p, synth, keys.lwe_sk, msgs)
+    ctx = slz.Context(p, p.batch)
+    assert ctx.path == "fused_n2048"
+    d_bsk = ctx.bsk_prepare(slz.to_device_u64(keys.bsk))
+    d_idx = torch.from_numpy(lut_idx.astype(np.int32)).cuda()
+    big = ctx.pbs_batch(slz.to_device_u64(cts), slz.to_device_u64(luts), d_idx, d_bsk)
+    small = ctx.keyswitch_batch(big, slz.to_device_u64(keys.ksk))
+    big_h, small_h = slz.to_host_u64(big), slz.to_host_u64(small)
+    # the whole batch decrypts to the table values, under the big key after the PBS and the small key after the keyswitch
+    want = _expected(tables, lut_idx, msgs, p.t)
+    got_big, err_big = orc.decode(orc.lwe_phase(keys.big_sk, big_h), p.msg_bits)
+    got_small, err_small = orc.decode(orc.lwe_phase(keys.lwe_sk, small_h), p.msg_bits)
+    assert np.array_equal(got_big, want)
+    assert np.array_equal(got_small, want)
+    # measured output noise against the closed forms (blind rotation: rounding term dominates at these parameters)
+    hw, hwS = int(keys.lwe_sk.sum()), int(keys.glwe_sk.sum())
+    B = 2.0 ** p.pbs_base_log
+    var_br = p.n * 2 * p.pbs_level * p.N * ((B * B + 2) / 12.0) * p.sigma_bsk ** 2 + hw * (1 + hwS) / (12.0 * B ** (2 * p.pbs_level))
+    assert abs(float(np.var(err_big)) / var_br - 1.0) < 0.25
+    Bk = 2.0 ** p.ks_base_log
+    var_ks = p.N * p.ks_level * ((Bk * Bk + 2) / 12.0) * p.sigma_lwe ** 2 + hwS / (12.0 * Bk ** (2 * p.ks_level))
+    assert abs(float(np.var(err_small)) / (var_br + var_ks) - 1.0) < 0.25
+    # sampled ciphertexts, bit for bit
+    idx = np.unique(np.concatenate([np.array([0, p.batch - 1]), np.linspace(0, p.batch - 1, sample).astype(np.int64)]))[:sample]
+    o_big = orc.pbs_batch(p, cts[idx], luts, lut_idx[idx], keys.bsk)
+    o_small = orc.keyswitch_batch(p, o_big, keys.ksk)
+    assert np.array_equal(big_h[idx], o_big)
+    assert np.array_equal(small_h[idx], o_small)
+    return ctx, keys
+
+
+def test_config2_full_batch(slz, orc):
+    _run_config(slz, orc, 2, sample=6)
+
+
+def test_config5_large_batch_multi_lut(slz, orc):
+    _run_config(slz, orc, 5, sample=4)
+
+
+def test_config4_gadget_lincomb_pbs_keyswitch(slz, orc):
+    # one MLP layer step of the matmul gadget's shape: per residue modulus r in {7, 11, 13}, 32 x 784 encrypted residues,
+    # a clear 784 x 128 weight matrix, leveled sums, then one mod-r PBS (+ keyswitch) per output.
+    p = synth.CONFIGS[4]
+    keys = orc.Keys(p, synth)
+    xs, ws = synth.cfg4_clear_inputs()                         # [3][32][784], [3][784][128]
+    tables = synth.config_tables(4)
+    luts = slz.lut_encode(p, tables)
+    B, J, O = synth.CFG4_BATCH, synth.CFG4_IN, synth.CFG4_OUT
+    ctx = slz.Context(p, p.batch)
+    d_bsk = ctx.bsk_prepare(slz.to_device_u64(keys.bsk))
+    d_ksk = slz.to_device_u64(keys.ksk)
+    d_luts = slz.to_device_u64(luts)
+    pbs_in = torch.empty((3, B, O, p.n + 1), dtype=torch.int64, device="cuda")
+    for r in range(3):
+        cts = orc.encrypt_messages(p, synth, keys.lwe_sk, xs[r].reshape(-1), offset=r * B * J).reshape(B, J, p.n + 1)
+        d_cts = slz.to_device_u64(cts)
+        d_w = torch.from_numpy(ws[r]).cuda()
+        ctx.lwe_lincomb_batch(d_cts, d_w, out=pbs_in[r])
+        # the linear part, bit for bit, on two of the 32 groups
+        got = slz.to_host_u64(pbs_in[r][[0, B - 1]])
+        assert np.array_equal(got, orc.lwe_lincomb_batch(cts[[0, B - 1]], ws[r]))
+        del d_cts
+    flat_in = pbs_in.reshape(3 * B * O, p.n + 1)
+    lut_idx = np.repeat(np.arange(3, dtype=np.uint32), B * O)
+    d_idx = torch.from_numpy(lut_idx.astype(np.int32)).cuda()
+    big = ctx.pbs_batch(flat_in, d_luts, d_idx, d_bsk)
+    small = ctx.keyswitch_batch(big, d_ksk)
+    small_h = slz.to_host_u64(small)
+    # 784-term sums wrap mod 2t = 32 on the torus, so the expected value is the negacyclic extension of the table
+    sums = np.stack([(xs[r].astype(np.int64) @ ws[r].astype(np.int64)) % (2 * p.t) for r in range(3)]).reshape(-1).astype(np.uint64)
+    want = _expected(tables, lut_idx, sums, p.t)
+    got, _ = orc.decode(orc.lwe_phase(keys.lwe_sk, small_h), p.msg_bits)
+    assert np.array_equal(got, want)
+    # sampled PBS + keyswitch outputs, bit for bit
+    idx = np.array([0, 3 * B * O // 2 + 17, 3 * B * O - 1])
+    flat_h = slz.to_host_u64(flat_in)
+    o_big = orc.pbs_batch(p, flat_h[idx], luts, lut_idx[idx], keys.bsk)
+    assert np.array_equal(slz.to_host_u64(big)[idx], o_big)
+    assert np.array_equal(small_h[idx], orc.keyswitch_batch(p, o_big, keys.ksk))
