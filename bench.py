@@ -81,7 +81,25 @@ def main():
     d_small = torch.empty((batch, p.n + 1), dtype=torch.int64, device="cuda")
     torch.cuda.synchronize()
 
+    # configuration 4 adds the leveled linear part in front: per modulus, 32 x 784 ciphertexts times a clear 784 x 128 matrix
+    lin = None
+    if args.config == 4 and not args.batch:
+        G, J, O = synth.CFG4_BATCH, synth.CFG4_IN, synth.CFG4_OUT
+        _, ws = synth.cfg4_clear_inputs()
+        lin_cts = [slz.to_device_u64(synth.raw_words(p, "lin_mask", G * J * (p.n + 1), r * G * J * (p.n + 1)).reshape(G, J, p.n + 1))
+                   for r in range(3)]
+        lin_w = [torch.from_numpy(ws[r]).cuda() for r in range(3)]
+        lin_out = d_cts.view(3, G, O, p.n + 1)
+        lin = (lin_cts, lin_w, lin_out)
+    ev_lin = [torch.cuda.Event(enable_timing=True) for _ in range(args.steps)]
+
+    def lincomb():
+        if lin is not None:
+            for r in range(3):
+                ctx.lwe_lincomb_batch(lin[0][r], lin[1][r], out=lin[2][r])
+
     def step():
+        lincomb()
         ctx.pbs_batch(d_cts, d_luts, d_idx, d_bskp, out=d_big)
         ctx.keyswitch_batch(d_big, d_ksk, out=d_small)
 
@@ -99,6 +117,8 @@ def main():
     ev = [[torch.cuda.Event(enable_timing=True) for _ in range(3)] for _ in range(args.steps)]
     t0 = time.perf_counter()
     for k in range(args.steps):
+        ev_lin[k].record()
+        lincomb()
         ev[k][0].record()
         ctx.pbs_batch(d_cts, d_luts, d_idx, d_bskp, out=d_big)
         ev[k][1].record()
@@ -108,6 +128,7 @@ def main():
     wall = time.perf_counter() - t0
     pbs_ms = float(np.mean([e[0].elapsed_time(e[1]) for e in ev]))
     ks_ms = float(np.mean([e[1].elapsed_time(e[2]) for e in ev]))
+    lin_ms = float(np.mean([ev_lin[k].elapsed_time(ev[k][0]) for k in range(args.steps)])) if lin is not None else None
     ms_per_step = wall * 1e3 / args.steps
 
     model_ops = alu_model_ops_per_pbs(p) * batch
@@ -124,7 +145,7 @@ def main():
             p.name, batch, p.n, p.k, p.N, p.pbs_base_log, p.pbs_level, p.ks_base_log, p.ks_level),
             "path": ctx.path},
         "pbs_per_s": batch / (pbs_ms * 1e-3), "keyswitch_per_s": batch / (ks_ms * 1e-3),
-        "pbs_ms": pbs_ms, "keyswitch_ms": ks_ms,
+        "pbs_ms": pbs_ms, "keyswitch_ms": ks_ms, "lincomb_ms": lin_ms,
         "bsk_prepared_bytes": prepared_bytes,
         "bsk_stream_GBps_min": prepared_bytes / (pbs_ms * 1e-3) / 1e9,
         "roofline": {"bound": "alu", "kernel": "blind rotation (slz_pbs_batch)", "achieved": achieved,
@@ -140,7 +161,8 @@ def main():
         sample = int(max(1, min(batch, threads * max(1, int(budget_macs / threads / macs_per_pbs)))))
         idx = np.linspace(0, batch - 1, sample).astype(np.int64)
         t1 = time.perf_counter()
-        o_big = oracle.pbs_batch(p, cts[idx], luts, lut_idx[idx], bsk)
+        cts_h = slz.to_host_u64(d_cts)          # configuration 4: the PBS inputs are the GPU's own linear combinations
+        o_big = oracle.pbs_batch(p, cts_h[idx], luts, lut_idx[idx], bsk)
         t2 = time.perf_counter()
         o_small = oracle.keyswitch_batch(p, o_big, ksk)
         t3 = time.perf_counter()
