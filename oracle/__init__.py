@@ -38,7 +38,8 @@ _lib = None
 def lib():
     global _lib
     if _lib is None:
-        _lib = ctypes.CDLL(build())
+        # TFHE_ORACLE_LIB lets the mutation tests load a deliberately broken build of the oracle
+        _lib = ctypes.CDLL(os.environ.get("TFHE_ORACLE_LIB") or build())
         _lib.orc_modswitch.restype = ctypes.c_uint32
         _lib.orc_modswitch.argtypes = [ctypes.c_uint64, ctypes.c_uint32]
         _lib.orc_lwe_phase.restype = ctypes.c_uint64
