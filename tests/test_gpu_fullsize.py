@@ -114,3 +114,38 @@ def test_config4_gadget_lincomb_pbs_keyswitch(slz, orc):
     o_big = orc.pbs_batch(p, flat_h[idx], luts, lut_idx[idx], keys.bsk)
     assert np.array_equal(slz.to_host_u64(big)[idx], o_big)
     assert np.array_equal(small_h[idx], orc.keyswitch_batch(p, o_big, keys.ksk))
+
+
+def test_config3_shape_blind_rotation_and_keyswitch(slz, orc):
+    # N = 32768, l = 2 (generic path: the accumulator does not fit on chip).  A full PBS of this size is ~9e12
+    # multiply-adds in the oracle, so the blind rotation is checked on its first steps (the parameter set with n cut to 2,
+    # full batch of 256, uniform-word key and inputs, four sampled ciphertexts), and the keyswitch at its full dimensions.
+    p3 = synth.CONFIGS[3]
+    p = p3.with_(n=2, name="cfg3_first_steps")
+    batch = p3.batch
+    R, C = (p.k + 1) * p.pbs_level, p.k + 1
+    bsk = synth.raw_words(p, "raw_bsk", p.n * R * C * p.N).reshape(p.n, p.k + 1, p.pbs_level, C, p.N)
+    cts = synth.raw_words(p, "raw_ct", batch * (p.n + 1)).reshape(batch, p.n + 1)
+    tables = synth.config_tables(3)
+    luts = slz.lut_encode(p, tables)
+    lut_idx = synth.config_lut_idx(3)
+    ctx = slz.Context(p, batch)
+    assert ctx.path == "generic"
+    d_bsk = ctx.bsk_prepare(slz.to_device_u64(bsk))
+    d_idx = torch.from_numpy(lut_idx.astype(np.int32)).cuda()
+    d_cts, d_luts = slz.to_device_u64(cts), slz.to_device_u64(luts)
+    idx = np.array([0, 85, 170, 255])
+    for steps in (1, 2):
+        got = slz.to_host_u64(ctx.blind_rotate_batch(d_cts, d_luts, d_idx, d_bsk, steps))
+        want = orc.blind_rotate_batch(p, cts[idx], luts, lut_idx[idx], bsk, steps)
+        assert np.array_equal(got[idx], want), steps
+    big = slz.to_host_u64(ctx.pbs_batch(d_cts, d_luts, d_idx, d_bsk))
+    assert np.array_equal(big[idx], orc.pbs_batch(p, cts[idx], luts, lut_idx[idx], bsk))
+    del ctx, d_bsk
+    # keyswitch: kN = 32768 -> n = 1024, base 2^4 x 5 levels, 1.34 GB key
+    ksk = synth.raw_words(p3, "raw_ksk", p3.N * p3.ks_level * (p3.n + 1)).reshape(p3.N, p3.ks_level, p3.n + 1)
+    cts_big = synth.raw_words(p3, "raw_ct", batch * (p3.N + 1), offset=1 << 24).reshape(batch, p3.N + 1)
+    ctx3 = slz.Context(p3, batch)
+    small = slz.to_host_u64(ctx3.keyswitch_batch(slz.to_device_u64(cts_big), slz.to_device_u64(ksk)))
+    idx = np.array([0, 1, 100, 128, 200, 255])
+    assert np.array_equal(small[idx], orc.keyswitch_batch(p3, cts_big[idx], ksk))
