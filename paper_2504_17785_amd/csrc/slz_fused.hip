@@ -89,6 +89,63 @@ __device__ __forceinline__ void bfly(double &a, double &b, double w, slz_mod m) 
     b = a - v;
     a = a + v;
 }
+// K independent butterflies with their instructions interleaved step by step.  A dependent FP64 instruction can
+// issue only every other slot (measured: 9 cycles per instruction in a dependent chain against 4.8 with four
+// independent chains), so a wave that runs its butterflies one after the other uses half of its SIMD.
+template <int K>
+__device__ __forceinline__ void bfly_k(double *(&a)[K], double *(&b)[K], const double (&w)[K], slz_mod m) {
+    double h[K], l[K], q[K];
+#pragma unroll
+    for (int i = 0; i < K; i++) h[i] = *b[i] * w[i];
+#pragma unroll
+    for (int i = 0; i < K; i++) q[i] = h[i] * m.pinv;
+#pragma unroll
+    for (int i = 0; i < K; i++) l[i] = __builtin_fma(*b[i], w[i], -h[i]);
+#pragma unroll
+    for (int i = 0; i < K; i++) q[i] = __builtin_rint(q[i]);
+#pragma unroll
+    for (int i = 0; i < K; i++) h[i] = __builtin_fma(-q[i], m.p, h[i]);
+#pragma unroll
+    for (int i = 0; i < K; i++) h[i] = h[i] + l[i];
+#pragma unroll
+    for (int i = 0; i < K; i++) *b[i] = *a[i] - h[i];
+#pragma unroll
+    for (int i = 0; i < K; i++) *a[i] = *a[i] + h[i];
+}
+
+// K independent modular multiplications / reductions, interleaved the same way
+template <int K>
+__device__ __forceinline__ void mulmod_k(double (&r)[K], const double (&xv)[K], const double (&w)[K], slz_mod m) {
+    double h[K], l[K], q[K];
+#pragma unroll
+    for (int i = 0; i < K; i++) h[i] = xv[i] * w[i];
+#pragma unroll
+    for (int i = 0; i < K; i++) q[i] = h[i] * m.pinv;
+#pragma unroll
+    for (int i = 0; i < K; i++) l[i] = __builtin_fma(xv[i], w[i], -h[i]);
+#pragma unroll
+    for (int i = 0; i < K; i++) q[i] = __builtin_rint(q[i]);
+#pragma unroll
+    for (int i = 0; i < K; i++) h[i] = __builtin_fma(-q[i], m.p, h[i]);
+#pragma unroll
+    for (int i = 0; i < K; i++) r[i] = h[i] + l[i];
+}
+template <int K>
+__device__ __forceinline__ void reduce_k(double (&r)[K], const double (&xv)[K], slz_mod m) {
+    double q[K];
+#pragma unroll
+    for (int i = 0; i < K; i++) q[i] = xv[i] * m.pinv;
+#pragma unroll
+    for (int i = 0; i < K; i++) q[i] = __builtin_rint(q[i]);
+#pragma unroll
+    for (int i = 0; i < K; i++) r[i] = __builtin_fma(-q[i], m.p, xv[i]);
+}
+
+// all butterflies (x[ia], x[ib]) of a stage given by index lists, four at a time
+#define BF4(i0, j0, w0, i1, j1, w1, i2, j2, w2, i3, j3, w3) do { \
+    double *pa_[4] = {&x[i0], &x[i1], &x[i2], &x[i3]}; double *pb_[4] = {&x[j0], &x[j1], &x[j2], &x[j3]}; \
+    const double pw_[4] = {w0, w1, w2, w3}; bfly_k<4>(pa_, pb_, pw_, m); } while (0)
+
 __device__ __forceinline__ void bfly_nomul(double &a, double &b) {
     double v = b;
     b = a - v;
@@ -111,19 +168,31 @@ __device__ __forceinline__ void fused_fwd(double (&x)[32], double *T, const doub
     for (int s = 0; s < 5; s++) {
         const int half = 16 >> s;
 #pragma unroll
-        for (int blk = 0; blk < (1 << s); blk++) {
-            const double w = twA[(1 << s) + blk + z];            // uniform: block index comes from the register index
-#pragma unroll
-            for (int j = 0; j < half; j++) bfly(x[blk * 2 * half + j], x[blk * 2 * half + j + half], w, m);
+        for (int g = 0; g < 4; g++) {                            // 16 butterflies per stage, four at a time
+            // butterfly number b in [0,16): block b / half, position b % half; uniform twiddle per block
+#define FA_I(b) (((b) / half) * 2 * half + (b) % half)
+#define FA_W(b) twA[(1 << s) + (b) / half + z]
+            BF4(FA_I(4 * g), FA_I(4 * g) + half, FA_W(4 * g), FA_I(4 * g + 1), FA_I(4 * g + 1) + half, FA_W(4 * g + 1),
+                FA_I(4 * g + 2), FA_I(4 * g + 2) + half, FA_W(4 * g + 2), FA_I(4 * g + 3), FA_I(4 * g + 3) + half, FA_W(4 * g + 3));
         }
     }
     double *wb = T + 68u * hh + l5;
 #pragma unroll
-    for (int mm = 0; mm < 16; mm++) {
-        swap32(x[2 * mm], x[2 * mm + 1]);                        // stride 32: partner coefficient sits 32 lanes away
-        bfly(x[2 * mm], x[2 * mm + 1], tw6[mm], m);
-        wb[136 * mm] = slz_reduce(x[2 * mm], m);
-        wb[136 * mm + 34] = slz_reduce(x[2 * mm + 1], m);
+    for (int g = 0; g < 4; g++) {
+#pragma unroll
+        for (int mm = 4 * g; mm < 4 * g + 4; mm++) swap32(x[2 * mm], x[2 * mm + 1]);   // stride 32: partner sits 32 lanes away
+        BF4(8 * g, 8 * g + 1, tw6[4 * g], 8 * g + 2, 8 * g + 3, tw6[4 * g + 1], 8 * g + 4, 8 * g + 5, tw6[4 * g + 2],
+            8 * g + 6, 8 * g + 7, tw6[4 * g + 3]);
+        {
+            double r8[8];
+            const double x8[8] = {x[8 * g], x[8 * g + 1], x[8 * g + 2], x[8 * g + 3], x[8 * g + 4], x[8 * g + 5], x[8 * g + 6], x[8 * g + 7]};
+            reduce_k<8>(r8, x8, m);
+#pragma unroll
+            for (int u = 0; u < 4; u++) {
+                wb[136 * (4 * g + u)] = r8[2 * u];
+                wb[136 * (4 * g + u) + 34] = r8[2 * u + 1];
+            }
+        }
     }
     SCHED_FENCE();
 #pragma unroll
@@ -137,15 +206,15 @@ __device__ __forceinline__ void fused_fwd(double (&x)[32], double *T, const doub
         x[i] = v.x;
         x[i + 1] = v.y;
     }
-    int kk = 0;
 #pragma unroll
     for (int s = 0; s < 5; s++) {
         const int t = 16 >> s;
 #pragma unroll
-        for (int blk = 0; blk < (1 << s); blk++) {
-            const double w = twB[kk++];
-#pragma unroll
-            for (int j = 0; j < t; j++) bfly(x[blk * 2 * t + j], x[blk * 2 * t + j + t], w, m);
+        for (int g = 0; g < 4; g++) {
+#define FB_I(b) (((b) / t) * 2 * t + (b) % t)
+#define FB_W(b) twB[(1 << s) - 1 + (b) / t]
+            BF4(FB_I(4 * g), FB_I(4 * g) + t, FB_W(4 * g), FB_I(4 * g + 1), FB_I(4 * g + 1) + t, FB_W(4 * g + 1),
+                FB_I(4 * g + 2), FB_I(4 * g + 2) + t, FB_W(4 * g + 2), FB_I(4 * g + 3), FB_I(4 * g + 3) + t, FB_W(4 * g + 3));
         }
     }
 }
@@ -172,45 +241,56 @@ __device__ __forceinline__ void fused_inv(double (&x)[32], double *T, const doub
     {
         const double w = twS[3 + z];
 #pragma unroll
-        for (int blk = 0; blk < 8; blk++) {                                             // t = 2
-            bfly_nomul(x[4 * blk], x[4 * blk + 2]);
-            bfly(x[4 * blk + 1], x[4 * blk + 3], w, m);
-        }
+        for (int blk = 0; blk < 8; blk++) bfly_nomul(x[4 * blk], x[4 * blk + 2]);      // t = 2, unit twiddle
+#pragma unroll
+        for (int g = 0; g < 2; g++)                                                     // t = 2, twiddle inv[3]
+            BF4(16 * g + 1, 16 * g + 3, w, 16 * g + 5, 16 * g + 7, w, 16 * g + 9, 16 * g + 11, w, 16 * g + 13, 16 * g + 15, w);
     }
 #pragma unroll
     for (int s = 2; s < 5; s++) {                                                       // t = 4, 8, 16
         const int t = 1 << s;
 #pragma unroll
-        for (int j = 0; j < t; j++) {
-            const double w = twS[t + j + z];                                            // uniform: depends on j only
-#pragma unroll
-            for (int blk = 0; blk < (16 >> s); blk++) bfly(x[blk * 2 * t + j], x[blk * 2 * t + j + t], w, m);
+        for (int g = 0; g < 4; g++) {
+            // butterfly b in [0,16): position j = b % t in block b / t; the twiddle depends on j only (uniform)
+#define IB_I(b) (((b) / t) * 2 * t + (b) % t)
+#define IB_W(b) twS[t + (b) % t + z]
+            BF4(IB_I(4 * g), IB_I(4 * g) + t, IB_W(4 * g), IB_I(4 * g + 1), IB_I(4 * g + 1) + t, IB_W(4 * g + 1),
+                IB_I(4 * g + 2), IB_I(4 * g + 2) + t, IB_W(4 * g + 2), IB_I(4 * g + 3), IB_I(4 * g + 3) + t, IB_W(4 * g + 3));
         }
     }
     wave_sync();                                                                        // earlier reads of T are done
     double *wb = T + 34u * lane;
 #pragma unroll
-    for (int i = 0; i < 32; i += 2) {
-        double2 v;
-        v.x = slz_reduce(x[i], m);
-        v.y = slz_reduce(x[i + 1], m);
-        *reinterpret_cast<double2 *>(wb + i) = v;
+    for (int g = 0; g < 4; g++) {
+        double r8[8];
+        const double x8[8] = {x[8 * g], x[8 * g + 1], x[8 * g + 2], x[8 * g + 3], x[8 * g + 4], x[8 * g + 5], x[8 * g + 6], x[8 * g + 7]};
+        reduce_k<8>(r8, x8, m);
+#pragma unroll
+        for (int u = 0; u < 4; u++) {
+            double2 v;
+            v.x = r8[2 * u];
+            v.y = r8[2 * u + 1];
+            *reinterpret_cast<double2 *>(wb + 8 * g + 2 * u) = v;
+        }
     }
     wave_sync();
     const double *rb = T + 68u * hh + l5;
 #pragma unroll
-    for (int mm = 0; mm < 16; mm++) {                                                   // t = 32
+    for (int mm = 0; mm < 16; mm++) {
         x[2 * mm] = rb[136 * mm];
         x[2 * mm + 1] = rb[136 * mm + 34];
-        bfly(x[2 * mm], x[2 * mm + 1], w32, m);
-        swap32(x[2 * mm], x[2 * mm + 1]);
+    }
+#pragma unroll
+    for (int g = 0; g < 4; g++) {                                                       // t = 32
+        BF4(8 * g, 8 * g + 1, w32, 8 * g + 2, 8 * g + 3, w32, 8 * g + 4, 8 * g + 5, w32, 8 * g + 6, 8 * g + 7, w32);
+#pragma unroll
+        for (int mm = 4 * g; mm < 4 * g + 4; mm++) swap32(x[2 * mm], x[2 * mm + 1]);
     }
     SCHED_FENCE();
 #pragma unroll
     for (int j = 0; j < 16; j++) twL[15 + j] = ldl(inv + 64 * 16 + 64 * j + z, lane * 8u);
     SCHED_FENCE();
     double pw[32];
-    int kk = 0;
 #pragma unroll
     for (int s = 0; s < 5; s++) {                                                       // t = 64 .. 1024
         const int half = 1 << s;
@@ -227,14 +307,23 @@ __device__ __forceinline__ void fused_inv(double (&x)[32], double *T, const doub
             SCHED_FENCE();
         }
 #pragma unroll
-        for (int j = 0; j < half; j++) {
-            const double w = twL[kk++];
-#pragma unroll
-            for (int blk = 0; blk < (16 >> s); blk++) bfly(x[blk * 2 * half + j], x[blk * 2 * half + j + half], w, m);
+        for (int g = 0; g < 4; g++) {
+            // butterfly b in [0,16): position j = b % half in block b / half; per-lane twiddle twL[half - 1 + j]
+#define IA_I(b) (((b) / half) * 2 * half + (b) % half)
+#define IA_W(b) twL[half - 1 + (b) % half]
+            BF4(IA_I(4 * g), IA_I(4 * g) + half, IA_W(4 * g), IA_I(4 * g + 1), IA_I(4 * g + 1) + half, IA_W(4 * g + 1),
+                IA_I(4 * g + 2), IA_I(4 * g + 2) + half, IA_W(4 * g + 2), IA_I(4 * g + 3), IA_I(4 * g + 3) + half, IA_W(4 * g + 3));
         }
     }
 #pragma unroll
-    for (int e = 0; e < 32; e++) x[e] = slz_mulmod(x[e], pw[e], m);
+    for (int g = 0; g < 8; g++) {
+        double r4[4];
+        const double x4[4] = {x[4 * g], x[4 * g + 1], x[4 * g + 2], x[4 * g + 3]};
+        const double w4[4] = {pw[4 * g], pw[4 * g + 1], pw[4 * g + 2], pw[4 * g + 3]};
+        mulmod_k<4>(r4, x4, w4, m);
+#pragma unroll
+        for (int u = 0; u < 4; u++) x[4 * g + u] = r4[u];
+    }
 }
 
 __global__ void __launch_bounds__(FUSED_THREADS) __attribute__((amdgpu_waves_per_eu(2, 2)))
@@ -332,10 +421,15 @@ k_fused_blind_rotate_n2048(fused_args A) {
                     }
                     SCHED_FENCE();
 #pragma unroll
-                    for (int i = 0; i < 8; i++) {
-                        const double xv = x[8 * ch + i];
-                        T[64 * (8 * ch + i) + lane] = slz_mulmod(xv, ks[ch & 1][i], m);
-                        x[8 * ch + i] = slz_mulmod(xv, ko[ch & 1][i], m);
+                    for (int i = 0; i < 8; i += 2) {
+                        double r4[4];
+                        const double x4[4] = {x[8 * ch + i], x[8 * ch + i], x[8 * ch + i + 1], x[8 * ch + i + 1]};
+                        const double w4[4] = {ks[ch & 1][i], ko[ch & 1][i], ks[ch & 1][i + 1], ko[ch & 1][i + 1]};
+                        mulmod_k<4>(r4, x4, w4, m);
+                        T[64 * (8 * ch + i) + lane] = r4[0];
+                        x[8 * ch + i] = r4[1];
+                        T[64 * (8 * ch + i + 1) + lane] = r4[2];
+                        x[8 * ch + i + 1] = r4[3];
                     }
                 }
             }
@@ -343,7 +437,14 @@ k_fused_blind_rotate_n2048(fused_args A) {
             __syncthreads();
             MARK(6);
 #pragma unroll
-            for (int i = 0; i < 32; i++) x[i] = slz_reduce(x[i] + Tsib[64 * i + lane], m);
+            for (int g = 0; g < 4; g++) {
+                double r8[8], x8[8];
+#pragma unroll
+                for (int u = 0; u < 8; u++) x8[u] = x[8 * g + u] + Tsib[64 * (8 * g + u) + lane];
+                reduce_k<8>(r8, x8, m);
+#pragma unroll
+                for (int u = 0; u < 8; u++) x[8 * g + u] = r8[u];
+            }
             MARK(7);
             __syncthreads();                          // sibling has read my buffer before I reuse it
             MARK(8);
