@@ -380,25 +380,40 @@ k_fused_blind_rotate_n2048(fused_args A) {
             MARK(0);
             __syncthreads();
             MARK(1);
-            double x[32];
+            // Each row is needed by both primes' waves: wave (q,h) decomposes the half of component h whose
+            // unrotated words are its own accumulator quarter (registers) and passes the digits to wave (1-q,h)
+            // through that wave's buffer, which nobody else touches between the two barriers.
+            int32_t dg[16];
             {
                 uint32_t r = at, neg0 = 0;
                 if (r >= FN) { r -= FN; neg0 = 1; }
+                int32_t *pd = reinterpret_cast<int32_t *>(Toth);
 #pragma unroll
-                for (int e = 0; e < 32; e++) {
-                    const uint32_t idx = 64u * e + lane;
+                for (int e = 0; e < 16; e++) {
+                    const uint32_t idx = 1024u * q + 64u * e + lane;
                     const uint32_t j = (idx - r) & (FN - 1);
                     const uint32_t neg = neg0 ^ (idx < r ? 1u : 0u);
                     const uint64_t a = Sh[(j >> 10) * (2u * TBUF) + (j & 1023u)];
-                    const uint64_t b = Sh[(e >= 16 ? 2u * TBUF : 0u) + (idx & 1023u)];
-                    const uint64_t lam = (neg ? (uint64_t)0 - a : a) - b;
+                    const uint64_t lam = (neg ? (uint64_t)0 - a : a) - acc[e];
                     uint64_t v = slz_round_top_bits(lam, 23);
-                    x[e] = (double)slz_next_digit(v, 23);
+                    dg[e] = slz_next_digit(v, 23);
+                    pd[64 * e + lane] = dg[e];
                 }
             }
             MARK(2);
-            __syncthreads();                          // every wave has read the staged accumulator
+            __syncthreads();                          // every wave has read the staged accumulator and sent its digits
             MARK(3);
+            double x[32];
+            {
+                const int32_t *md = reinterpret_cast<const int32_t *>(T);
+                if (q == 0) {
+#pragma unroll
+                    for (int e = 0; e < 16; e++) { x[e] = (double)dg[e]; x[16 + e] = (double)md[64 * e + lane]; }
+                } else {
+#pragma unroll
+                    for (int e = 0; e < 16; e++) { x[16 + e] = (double)dg[e]; x[e] = (double)md[64 * e + lane]; }
+                }
+            }
             // 2. forward transform
             fused_fwd(x, T, tw6, twA, fwdB, m, lane, z);
             MARK(4);
