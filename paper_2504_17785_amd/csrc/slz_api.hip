@@ -43,9 +43,16 @@ extern "C" int slz_ctx_create(const slz_params *params, uint32_t max_batch, slz_
     ctx->logN = logN;
     if (hipGetDevice(&ctx->device) != hipSuccess) { delete ctx; return SLZ_E_HIP; }
     rc = slz_build_tables(ctx);
+    // specialised paths are optional: a shape they decline (SLZ_E_UNSUPPORTED) runs on the generic path
     if (rc == SLZ_OK && slz_fused_supported(params)) {
         rc = slz_fused_init(ctx);
         ctx->has_fused = (rc == SLZ_OK);
+        if (rc == SLZ_E_UNSUPPORTED) rc = SLZ_OK;
+    }
+    if (rc == SLZ_OK && slz_bign_supported(params)) {
+        rc = slz_bign_init(ctx);
+        ctx->has_bign = (rc == SLZ_OK);
+        if (rc == SLZ_E_UNSUPPORTED) rc = SLZ_OK;
     }
     if (rc != SLZ_OK) { slz_ctx_destroy(ctx); return rc; }
     *out = ctx;
@@ -55,6 +62,7 @@ extern "C" int slz_ctx_create(const slz_params *params, uint32_t max_batch, slz_
 extern "C" int slz_ctx_destroy(slz_ctx *ctx) {
     if (!ctx) return SLZ_E_INVALID_ARG;
     slz_fused_destroy(ctx);
+    slz_bign_destroy(ctx);
     slz_free_tables(ctx);
     if (ctx->acc) (void)hipFree(ctx->acc);
     if (ctx->dig) (void)hipFree(ctx->dig);
@@ -72,7 +80,8 @@ extern "C" int slz_ctx_set_option(slz_ctx *ctx, int option, int value) {
 
 extern "C" const char *slz_pbs_path(const slz_ctx *ctx) {
     if (!ctx) return "none";
-    return (ctx->has_fused && !ctx->force_generic) ? "fused_n2048" : "generic";
+    if (ctx->force_generic) return "generic";
+    return ctx->has_fused ? "fused_n2048" : (ctx->has_bign ? "three_pass_large_n" : "generic");
 }
 
 extern "C" int slz_lut_encode(const slz_params *p, const uint64_t *table, uint32_t n_tables, uint64_t *lut_out) {

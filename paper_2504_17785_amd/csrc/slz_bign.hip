@@ -1,0 +1,325 @@
+// Blind rotation for large polynomials, N = 2048 * G with G in {2,4,8,16,32}, k = 1 (the 8-bit-precision-shaped
+// parameter sets: N = 32768).  The accumulator (512 KiB per ciphertext at N = 32768) cannot stay on chip, so a CMux
+// step is three passes over a per-ciphertext workspace that stays in L2 / Infinity Cache when ciphertexts are
+// processed in chunks:
+//   P1 "columns, forward":  per accumulator column c (coefficients 2048 i + c, i < G): rotate, subtract, decompose,
+//                           then the first log2(G) transform stages (they pair coefficients 2048 rows apart, so a
+//                           lane holding one column does them in registers), for every level and both primes.
+//   P2 "rows":              per prime and 2048-block: the remaining 11 forward stages with the wave-level transform
+//                           of the N = 2048 kernel (block-specific twiddles), multiply-accumulate with the prepared
+//                           key over all GGSW rows, the first 11 inverse stages.
+//   P3 "columns, inverse":  the last log2(G) inverse stages per column, the psi^-j / N twist, CRT lift, accumulate.
+#include "slz_internal.h"
+#include "slz_modarith.h"
+#include "slz_wave_ntt.h"
+#include <vector>
+
+#define BIG_MAX_L 4
+
+struct bign_tabs {                 // per prime
+    const double *fwd;             // natural forward table of the full transform (fwd[m + blk])
+    const double *rowA;            // [G][64]      block-specific twiddles of stages with 1..32 sub-blocks (uniform per wave)
+    const double *rowB;            // [G][31][64]  block-specific per-lane twiddles of the last five forward stages
+    const double *inv;             // natural inverse table
+    const double *post;            // natural twist table
+};
+
+struct bign_args {
+    const uint64_t *lwe_in;
+    uint64_t *acc;                 // [batch][2][N]
+    double *X;                     // [batch][2 primes][R][N]
+    double *Y;                     // [batch][2 primes][2][N]
+    const double *bskp_step;       // prepared GGSW of this step: [2][R][2][N]
+    uint32_t n, step, N, logG, beta, l, batch;
+    bign_tabs tab[2];
+    slz_mod mod[2];
+    double p1inv_mod_p2;
+};
+
+// ---- P1 ------------------------------------------------------------------------------------------
+template <int G>
+__global__ void __launch_bounds__(256)
+k_big_cols_fwd(bign_args A) {
+    const uint32_t c = blockIdx.x * 256 + threadIdx.x;          // column, < 2048
+    const uint32_t comp = blockIdx.y, b = blockIdx.z;
+    const uint32_t N = A.N, R = 2 * A.l;
+    uint32_t logN2 = 12;                                         // log2(2N) = 12 + log2 G
+    for (uint32_t g = G; g > 1; g >>= 1) logN2++;
+    const uint32_t at = slz_modswitch(A.lwe_in[(size_t)b * (A.n + 1) + A.step], logN2);
+    const uint64_t *poly = A.acc + ((size_t)b * 2 + comp) * N;
+    uint64_t lam[G];
+#pragma unroll
+    for (int i = 0; i < G; i++) {
+        const uint32_t idx = 2048u * i + c;
+        lam[i] = slz_rot_coeff([&](uint32_t j) { return poly[j]; }, idx, at, N) - poly[idx];
+        lam[i] = slz_round_top_bits(lam[i], A.beta * A.l);
+    }
+    for (int lev = (int)A.l - 1; lev >= 0; lev--) {              // least significant level first (carries go up)
+        double d[G];
+#pragma unroll
+        for (int i = 0; i < G; i++) d[i] = (double)slz_next_digit(lam[i], A.beta);
+        for (int q = 0; q < 2; q++) {
+            const slz_mod m = A.mod[q];
+            const double *tw = A.tab[q].fwd;
+            double y[G];
+#pragma unroll
+            for (int i = 0; i < G; i++) y[i] = d[i];
+            // stages with strides N/2 .. 2048: pairs of rows, twiddle by block of rows (uniform)
+#pragma unroll
+            for (int half = G / 2, blocks = 1; half >= 1; half >>= 1, blocks <<= 1) {
+#pragma unroll
+                for (int blk = 0; blk < blocks; blk++) {
+                    const double w = tw[blocks + blk];
+#pragma unroll
+                    for (int j = 0; j < half; j++) bfly(y[blk * 2 * half + j], y[blk * 2 * half + j + half], w, m);
+                }
+            }
+            double *dst = A.X + (((size_t)b * 2 + q) * R + (comp * A.l + lev)) * N + c;
+#pragma unroll
+            for (int i = 0; i < G; i++) dst[2048u * i] = slz_reduce(y[i], m);
+        }
+    }
+}
+
+// ---- P2 ------------------------------------------------------------------------------------------
+// one wave per (ciphertext, prime, 2048-block); four independent waves per workgroup
+__global__ void __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(2, 2)))
+k_big_rows(bign_args A, uint32_t G, uint32_t n_tasks) {
+    extern __shared__ double lds[];
+    const uint32_t lane = threadIdx.x & 63u;
+    const uint32_t wv = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
+    const uint32_t task = blockIdx.x * 4 + wv;
+    if (task >= n_tasks) return;                                 // whole wave leaves; no workgroup barriers below
+    double *T = lds + wv * TBUF;
+    const uint32_t row = task % G, q = (task / G) & 1u, b = task / (2 * G);
+    const uint32_t N = A.N, R = 2 * A.l, hh = lane >> 5;
+    const slz_mod m = A.mod[q];
+    const bign_tabs tb = A.tab[q];
+    const double *twA = tb.rowA + (size_t)row * 64, *fwd6 = twA + 32, *fwdB = tb.rowB + (size_t)row * 31 * 64;
+    double o0[32], o1[32];
+    for (uint32_t r = 0; r < R; r++) {
+        int z;
+        asm volatile("s_mov_b32 %0, 0" : "=s"(z));              // tables are reloaded per GGSW row (they would spill if hoisted)
+        double tw6[16];
+#pragma unroll
+        for (int mm = 0; mm < 16; mm++) tw6[mm] = ldl(fwd6 + 2 * mm + z, hh * 8u);
+        const double *src = A.X + (((size_t)b * 2 + q) * R + r) * N + 2048u * row + z;
+        double x[32];
+#pragma unroll
+        for (int e = 0; e < 32; e++) x[e] = ldl(src + 64 * e, lane * 8u);
+        fused_fwd(x, T, tw6, twA, fwdB, m, lane, z);
+        // multiply-accumulate with the key polynomials of GGSW row r (both components); spectrum index of x[i] is
+        // 2048 row + 32 lane + i, stored at position i * (N/32) + 64 row + lane of the prepared polynomial
+        const double *k0 = A.bskp_step + (((size_t)q * R + r) * 2 + 0) * N + 64u * row + z;
+        const double *k1 = k0 + N;
+        const uint32_t stride = N / 32;
+#pragma unroll
+        for (int g = 0; g < 8; g++) {
+            double kk0[4], kk1[4], r0[4], r1[4];
+#pragma unroll
+            for (int u = 0; u < 4; u++) { kk0[u] = ldl(k0 + (size_t)(4 * g + u) * stride, lane * 8u); kk1[u] = ldl(k1 + (size_t)(4 * g + u) * stride, lane * 8u); }
+            const double x4[4] = {x[4 * g], x[4 * g + 1], x[4 * g + 2], x[4 * g + 3]};
+            mulmod_k<4>(r0, x4, kk0, m);
+            mulmod_k<4>(r1, x4, kk1, m);
+#pragma unroll
+            for (int u = 0; u < 4; u++) {
+                o0[4 * g + u] = (r == 0) ? r0[u] : o0[4 * g + u] + r0[u];
+                o1[4 * g + u] = (r == 0) ? r1[u] : o1[4 * g + u] + r1[u];
+            }
+        }
+        if ((r & 3u) == 3u && r + 1 < R) {                       // more than four rows: keep the running sums below 8 p
+#pragma unroll
+            for (int g = 0; g < 8; g++) {
+                double a4[4], b4[4];
+                const double xa[4] = {o0[4 * g], o0[4 * g + 1], o0[4 * g + 2], o0[4 * g + 3]};
+                const double xb[4] = {o1[4 * g], o1[4 * g + 1], o1[4 * g + 2], o1[4 * g + 3]};
+                reduce_k<4>(a4, xa, m);
+                reduce_k<4>(b4, xb, m);
+#pragma unroll
+                for (int u = 0; u < 4; u++) { o0[4 * g + u] = a4[u]; o1[4 * g + u] = b4[u]; }
+            }
+        }
+        wave_sync();
+    }
+    // inverse: first 11 stages inside the block, reduce, hand the block to the column pass
+    for (int comp = 0; comp < 2; comp++) {
+        int z;
+        asm volatile("s_mov_b32 %0, 0" : "=s"(z));
+        double x[32];
+#pragma unroll
+        for (int g = 0; g < 4; g++) {
+            double r8[8], x8[8];
+#pragma unroll
+            for (int u = 0; u < 8; u++) x8[u] = comp ? o1[8 * g + u] : o0[8 * g + u];
+            reduce_k<8>(r8, x8, m);
+#pragma unroll
+            for (int u = 0; u < 8; u++) x[8 * g + u] = r8[u];
+        }
+        fused_inv<false>(x, T, tb.inv, tb.inv, tb.post, m, lane, z);
+        double *dst = A.Y + (((size_t)b * 2 + q) * 2 + comp) * N + 2048u * row;
+#pragma unroll
+        for (int g = 0; g < 4; g++) {
+            double r8[8], x8[8];
+#pragma unroll
+            for (int u = 0; u < 8; u++) x8[u] = x[8 * g + u];
+            reduce_k<8>(r8, x8, m);
+#pragma unroll
+            for (int u = 0; u < 8; u++) dst[64 * (8 * g + u) + lane] = r8[u];
+        }
+        wave_sync();
+    }
+}
+
+// ---- P3 ------------------------------------------------------------------------------------------
+template <int G>
+__global__ void __launch_bounds__(256)
+k_big_cols_inv(bign_args A) {
+    const uint32_t c = blockIdx.x * 256 + threadIdx.x;
+    const uint32_t comp = blockIdx.y, b = blockIdx.z;
+    const uint32_t N = A.N;
+    double res[2][G];
+    for (int q = 0; q < 2; q++) {
+        const slz_mod m = A.mod[q];
+        const double *src = A.Y + (((size_t)b * 2 + q) * 2 + comp) * N + c;
+        const double *tw = A.tab[q].inv, *post = A.tab[q].post;
+        double y[G];
+#pragma unroll
+        for (int i = 0; i < G; i++) y[i] = src[2048u * i];
+        // stages with half-size t = 2048 * half: pairs of rows i, i + half; twiddle inv[t + 2048 (i mod half) + c]
+#pragma unroll
+        for (int half = 1; half < G; half <<= 1) {
+#pragma unroll
+            for (int j = 0; j < half; j++) {
+                const double w = tw[2048u * half + 2048u * j + c];
+#pragma unroll
+                for (int blk = 0; blk < G / (2 * half); blk++) bfly(y[blk * 2 * half + j], y[blk * 2 * half + j + half], w, m);
+            }
+        }
+#pragma unroll
+        for (int i = 0; i < G; i++) res[q][i] = slz_mulmod(y[i], post[2048u * i + c], m);
+    }
+    uint64_t *poly = A.acc + ((size_t)b * 2 + comp) * N + c;
+#pragma unroll
+    for (int i = 0; i < G; i++) poly[2048u * i] += slz_crt64(res[0][i], res[1][i], A.mod[1], A.p1inv_mod_p2);
+}
+
+// ---- host ------------------------------------------------------------------------------------------
+
+int slz_bign_supported(const slz_params *p) {
+    if (p->k != 1 || p->pbs_level > BIG_MAX_L) return 0;
+    for (uint32_t G = 2; G <= 32; G <<= 1)
+        if (p->N == 2048u * G) return 1;
+    return 0;
+}
+
+int slz_bign_init(slz_ctx *ctx) {
+    const uint32_t N = ctx->prm.N, G = N / 2048;
+    // worst-case bounds (units of p): column stages start from digits, rows from reduced values
+    double a = 1e-6;
+    for (uint32_t g = G; g > 1; g >>= 1) a += slz_mulmod_bound(a);
+    if (a > 7.5) return SLZ_E_UNSUPPORTED;
+    a = 0.5 + 1e-9;
+    for (int s = 0; s < 6; s++) a += slz_mulmod_bound(a);        // block stages 1..6, then the reduction inside fused_fwd
+    if (a > 7.5) return SLZ_E_UNSUPPORTED;
+    a = 0.5 + 1e-9;
+    for (int s = 0; s < 5; s++) a += slz_mulmod_bound(a);
+    // sums over the GGSW rows are reduced after every fourth row
+    if (0.5 + 4.0 * slz_mulmod_bound(a) > 7.5) return SLZ_E_UNSUPPORTED;
+    a = 0.5 + 1e-9;
+    for (uint32_t g = G; g > 1; g >>= 1) a += slz_mulmod_bound(a);
+    if (slz_mulmod_bound(a) > 1.95) return SLZ_E_UNSUPPORTED;
+    std::vector<double> nat(N), rowA((size_t)2 * G * 64), rowB((size_t)2 * G * 31 * 64);
+    for (int q = 0; q < 2; q++) {
+        SLZ_HIP(hipMemcpy(nat.data(), ctx->tab[q].fwd, (size_t)N * sizeof(double), hipMemcpyDeviceToHost));
+        for (uint32_t row = 0; row < G; row++) {
+            // the 2048-block `row` continues the transform with sub-block counts m' = 1, 2, ..., 1024; its sub-block blk
+            // at that stage is block (G + row) * m' + blk ... i.e. table entry fwd[(G + row) * m' + blk]
+            double *ra = &rowA[((size_t)q * G + row) * 64];
+            ra[0] = 1.0;
+            for (uint32_t x = 1; x < 64; x++) {
+                uint32_t mp = 1;
+                while (mp * 2 <= x) mp *= 2;
+                ra[x] = nat[(size_t)(G + row) * mp + (x - mp)];
+            }
+            int kk = 0;
+            for (int s = 0; s < 5; s++) {
+                const uint32_t t = 16u >> s, mp = FN / (2 * t);
+                for (uint32_t blk = 0; blk < (1u << s); blk++, kk++)
+                    for (uint32_t l = 0; l < 64; l++)
+                        rowB[(((size_t)q * G + row) * 31 + kk) * 64 + l] = nat[(size_t)(G + row) * mp + (32 * l) / (2 * t) + blk];
+            }
+        }
+    }
+    SLZ_HIP(hipMalloc((void **)&ctx->bign_rowA, rowA.size() * sizeof(double)));
+    SLZ_HIP(hipMalloc((void **)&ctx->bign_rowB, rowB.size() * sizeof(double)));
+    SLZ_HIP(hipMemcpy(ctx->bign_rowA, rowA.data(), rowA.size() * sizeof(double), hipMemcpyHostToDevice));
+    SLZ_HIP(hipMemcpy(ctx->bign_rowB, rowB.data(), rowB.size() * sizeof(double), hipMemcpyHostToDevice));
+    SLZ_HIP(hipFuncSetAttribute((const void *)k_big_rows, hipFuncAttributeMaxDynamicSharedMemorySize, 4 * TBUF * sizeof(double)));
+    return SLZ_OK;
+}
+
+void slz_bign_destroy(slz_ctx *ctx) {
+    if (ctx->bign_rowA) (void)hipFree(ctx->bign_rowA);
+    if (ctx->bign_rowB) (void)hipFree(ctx->bign_rowB);
+    ctx->bign_rowA = ctx->bign_rowB = nullptr;
+}
+
+template <int G>
+static void launch_cols(bool fwd, const bign_args &A, uint32_t batch, hipStream_t s) {
+    dim3 grid(2048 / 256, 2, batch);
+    if (fwd) hipLaunchKernelGGL(k_big_cols_fwd<G>, grid, dim3(256), 0, s, A);
+    else hipLaunchKernelGGL(k_big_cols_inv<G>, grid, dim3(256), 0, s, A);
+}
+
+static void launch_cols_any(bool fwd, uint32_t G, const bign_args &A, uint32_t batch, hipStream_t s) {
+    switch (G) {
+        case 2: launch_cols<2>(fwd, A, batch, s); break;
+        case 4: launch_cols<4>(fwd, A, batch, s); break;
+        case 8: launch_cols<8>(fwd, A, batch, s); break;
+        case 16: launch_cols<16>(fwd, A, batch, s); break;
+        default: launch_cols<32>(fwd, A, batch, s); break;
+    }
+}
+
+// Runs steps [0, n_steps) on accumulators that the caller has initialised in `acc` ([batch][2][N]).
+int slz_bign_cmux_steps(slz_ctx *ctx, const uint64_t *lwe_in, const double *bskp, uint32_t n_steps, uint64_t *acc,
+                        uint32_t batch, hipStream_t s) {
+    const slz_params &p = ctx->prm;
+    const uint32_t N = p.N, G = N / 2048, R = 2 * p.pbs_level;
+    uint32_t logG = 0;
+    while ((1u << logG) < G) logG++;
+    // Ciphertexts go through all steps in chunks whose workspace (X, Y, accumulators: (2R + 4 + 2) N doubles each) stays
+    // in the 256 MB Infinity Cache; the key (read once per chunk and step) streams from HBM.
+    const size_t per_ct = (size_t)(2 * R + 4 + 2) * N * 8;
+    uint32_t chunk = (uint32_t)((size_t)192 * 1024 * 1024 / per_ct);
+    if (chunk < 16) chunk = 16;
+    if (chunk > batch) chunk = batch;
+    for (uint32_t c0 = 0; c0 < batch; c0 += chunk) {
+        const uint32_t nb = (batch - c0 < chunk) ? batch - c0 : chunk;
+        bign_args A;
+        A.lwe_in = lwe_in + (size_t)c0 * (p.n + 1);
+        A.acc = acc + (size_t)c0 * 2 * N;
+        A.X = ctx->xhat;
+        A.Y = ctx->outhat;
+        A.n = p.n; A.N = N; A.logG = logG; A.beta = p.pbs_base_log; A.l = p.pbs_level; A.batch = nb;
+        for (int q = 0; q < 2; q++) {
+            A.tab[q].fwd = ctx->tab[q].fwd;
+            A.tab[q].rowA = ctx->bign_rowA + (size_t)q * G * 64;
+            A.tab[q].rowB = ctx->bign_rowB + (size_t)q * G * 31 * 64;
+            A.tab[q].inv = ctx->tab[q].inv;
+            A.tab[q].post = ctx->tab[q].post;
+            A.mod[q] = ctx->mod[q];
+        }
+        A.p1inv_mod_p2 = ctx->p1inv_mod_p2;
+        const uint32_t n_tasks = nb * 2 * G;
+        for (uint32_t step = 0; step < n_steps; step++) {
+            A.step = step;
+            A.bskp_step = bskp + (size_t)step * 2 * R * 2 * N;
+            launch_cols_any(true, G, A, nb, s);
+            hipLaunchKernelGGL(k_big_rows, dim3((n_tasks + 3) / 4), dim3(256), 4 * TBUF * sizeof(double), s, A, G, n_tasks);
+            launch_cols_any(false, G, A, nb, s);
+        }
+    }
+    SLZ_HIP(hipGetLastError());
+    return SLZ_OK;
+}

@@ -315,6 +315,11 @@ int slz_generic_blind_rotate(slz_ctx *ctx, const uint64_t *lwe_in, const uint64_
     hipLaunchKernelGGL(k_acc_init, dim3(blocks_for(glwe)), dim3(GEN_THREADS), 0, s, lwe_in, luts, lut_idx, acc, p.n, p.k, N,
                        ctx->logN, batch);
     const size_t ggsw = (size_t)2 * R * C * N;
+    if (ctx->has_bign && !ctx->force_generic) {
+        int rc = slz_bign_cmux_steps(ctx, lwe_in, bskp, n_steps, acc, batch, s);
+        if (rc != SLZ_OK) return rc;
+        n_steps = 0;                                   // the per-step kernels below are skipped
+    }
     for (uint32_t i = 0; i < n_steps; i++) {
         hipLaunchKernelGGL(k_decompose, dim3(blocks_for(glwe)), dim3(GEN_THREADS), 0, s, acc, lwe_in, i, ctx->dig, p.n, p.k, N,
                            ctx->logN, p.pbs_base_log, p.pbs_level, batch);

@@ -48,6 +48,9 @@ struct slz_ctx {
     slz_tables tab[2];
     double *fused_tab;        // tables re-laid-out for the fused kernel (or null)
     double fused_scalars[2][2][32];   // [prime][forward, inverse]: the lane-uniform twiddles of the fused kernel
+    int has_bign;             // large-N three-pass path available (N = 2048 G, k = 1)
+    double *bign_rowA;        // [2][G][64] block-specific lane-uniform forward twiddles
+    double *bign_rowB;        // [2][G][31][64] block-specific per-lane forward twiddles
     // scratch for the generic path, sized for max_batch
     uint64_t *acc;            // [max_batch][k+1][N]
     double *dig;              // [max_batch][(k+1)l][N]
@@ -78,6 +81,12 @@ void slz_fused_destroy(slz_ctx *ctx);
 int slz_fused_blind_rotate(slz_ctx *ctx, const uint64_t *lwe_in, const uint64_t *luts, const uint32_t *lut_idx,
                            const double *bskp, uint32_t n_steps, uint64_t *acc_out, uint64_t *lwe_out,
                            uint32_t batch, hipStream_t s);
+// large-N path (slz_bign.hip)
+int slz_bign_supported(const slz_params *p);
+int slz_bign_init(slz_ctx *ctx);
+void slz_bign_destroy(slz_ctx *ctx);
+int slz_bign_cmux_steps(slz_ctx *ctx, const uint64_t *lwe_in, const double *bskp, uint32_t n_steps, uint64_t *acc,
+                        uint32_t batch, hipStream_t s);
 // keyswitch / lincomb (slz_keyswitch.hip)
 int slz_keyswitch_launch(slz_ctx *ctx, const uint64_t *lwe_in, const uint64_t *ksk, uint64_t *lwe_out,
                          uint32_t batch, hipStream_t s);

@@ -117,7 +117,7 @@ def test_config4_gadget_lincomb_pbs_keyswitch(slz, orc):
 
 
 def test_config3_shape_blind_rotation_and_keyswitch(slz, orc):
-    # N = 32768, l = 2 (generic path: the accumulator does not fit on chip).  A full PBS of this size is ~9e12
+    # N = 32768, l = 2 (three-pass path: the accumulator does not fit on chip).  A full PBS of this size is ~9e12
     # multiply-adds in the oracle, so the blind rotation is checked on its first steps (the parameter set with n cut to 2,
     # full batch of 256, uniform-word key and inputs, four sampled ciphertexts), and the keyswitch at its full dimensions.
     p3 = synth.CONFIGS[3]
@@ -130,7 +130,7 @@ def test_config3_shape_blind_rotation_and_keyswitch(slz, orc):
     luts = slz.lut_encode(p, tables)
     lut_idx = synth.config_lut_idx(3)
     ctx = slz.Context(p, batch)
-    assert ctx.path == "generic"
+    assert ctx.path == "three_pass_large_n"
     d_bsk = ctx.bsk_prepare(slz.to_device_u64(bsk))
     d_idx = torch.from_numpy(lut_idx.astype(np.int32)).cuda()
     d_cts, d_luts = slz.to_device_u64(cts), slz.to_device_u64(luts)

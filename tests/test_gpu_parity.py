@@ -248,3 +248,45 @@ def test_fused_more_ciphertexts_than_resident_workgroups(slz, orc):
     idx = np.array([0, 1, 255, 511, 512, 513, 599])
     want = orc.pbs_batch(p, case.cts[idx], case.luts, case.lut_idx[idx], case.keys.bsk)
     assert np.array_equal(fused[idx], want)
+
+
+# ---------------------------------------------------------------- large-N three-pass path (N = 2048 G, k = 1)
+
+@pytest.mark.parametrize("shape", [
+    dict(n=3, N=4096, k=1, pbs_base_log=11, pbs_level=2),
+    dict(n=3, N=8192, k=1, pbs_base_log=15, pbs_level=1),
+    dict(n=2, N=16384, k=1, pbs_base_log=7, pbs_level=4),
+    dict(n=2, N=32768, k=1, pbs_base_log=15, pbs_level=2),
+], ids=lambda s: "N%d_l%d" % (s["N"], s["pbs_level"]))
+def test_large_n_path_matches_oracle_and_generic(slz, orc, shape):
+    p = tiny(**shape)
+    batch = 5
+    case = Case(slz, orc, p, batch, raw_inputs=True)
+    assert case.ctx.path == "three_pass_large_n"
+    for steps in sorted({0, 1, p.n}):
+        want = orc.blind_rotate_batch(p, case.cts, case.luts, case.lut_idx, case.keys.bsk, steps)
+        got = slz.to_host_u64(case.ctx.blind_rotate_batch(case.d_cts, case.d_luts, case.d_idx, case.d_bsk, steps))
+        assert np.array_equal(got, want), "accumulators differ after %d steps" % steps
+    want = orc.pbs_batch(p, case.cts, case.luts, case.lut_idx, case.keys.bsk)
+    got = slz.to_host_u64(case.ctx.pbs_batch(case.d_cts, case.d_luts, case.d_idx, case.d_bsk))
+    assert np.array_equal(got, want)
+    case.ctx.set_option(slz.SLZ_OPT_FORCE_GENERIC, 1)
+    gen = slz.to_host_u64(case.ctx.pbs_batch(case.d_cts, case.d_luts, case.d_idx, case.d_bsk))
+    assert np.array_equal(gen, want)
+
+
+def test_large_n_worst_case_magnitudes(slz, orc):
+    p = tiny(n=2, N=8192, k=1, pbs_base_log=21, pbs_level=1)      # 2 * 8192 * 2^20 * 2^63 = 2^97: the largest sums allowed
+    case = Case(slz, orc, p, 3, raw_inputs=True)
+    assert case.ctx.path == "three_pass_large_n"
+    bsk = case.keys.bsk.copy()
+    flat = bsk.reshape(-1)
+    flat[0::3] = np.uint64(1 << 63)
+    flat[1::3] = np.uint64((1 << 63) - 1)
+    luts = case.luts.copy()
+    luts[:, 0::2] = np.uint64((1 << 63) - (1 << 42))
+    luts[:, 1::2] = np.uint64(1 << 63)
+    d_bsk = case.ctx.bsk_prepare(slz.to_device_u64(bsk))
+    want = orc.blind_rotate_batch(p, case.cts, luts, case.lut_idx, bsk, p.n)
+    got = slz.to_host_u64(case.ctx.blind_rotate_batch(case.d_cts, slz.to_device_u64(luts), case.d_idx, d_bsk, p.n))
+    assert np.array_equal(got, want)
