@@ -83,7 +83,7 @@ k_big_cols_fwd(bign_args A) {
 
 // ---- P2 ------------------------------------------------------------------------------------------
 // one wave per (ciphertext, prime, 2048-block); four independent waves per workgroup
-__global__ void __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(2, 2)))
+__global__ void __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(1, 1)))
 k_big_rows(bign_args A, uint32_t G, uint32_t n_tasks) {
     extern __shared__ double lds[];
     const uint32_t lane = threadIdx.x & 63u;
@@ -291,8 +291,10 @@ int slz_bign_cmux_steps(slz_ctx *ctx, const uint64_t *lwe_in, const double *bskp
     // Ciphertexts go through all steps in chunks whose workspace (X, Y, accumulators: (2R + 4 + 2) N doubles each) stays
     // in the 256 MB Infinity Cache; the key (read once per chunk and step) streams from HBM.
     const size_t per_ct = (size_t)(2 * R + 4 + 2) * N * 8;
-    uint32_t chunk = (uint32_t)((size_t)192 * 1024 * 1024 / per_ct);
-    if (chunk < 16) chunk = 16;
+    uint32_t chunk = (uint32_t)((size_t)224 * 1024 * 1024 / per_ct);
+    const uint32_t fill = 1024u / (2 * G) ? 1024u / (2 * G) : 1;      // ciphertexts whose row tasks fill the chip once (4 waves per CU)
+    chunk = chunk / fill * fill;
+    if (chunk < fill) chunk = fill;
     if (chunk > batch) chunk = batch;
     for (uint32_t c0 = 0; c0 < batch; c0 += chunk) {
         const uint32_t nb = (batch - c0 < chunk) ? batch - c0 : chunk;
