@@ -133,7 +133,7 @@ def main():
 
     # HBM bytes per launch of the dominant kernel from the rocprofv3 FETCH_SIZE / WRITE_SIZE passes kept under
     # profiles/ (scaled by the copy-kernel calibration); only known for the workload those passes were run on
-    traffic = 2.0 * 1520690 * 1024 + 43040 * 1024 if (args.config == 2 and batch == 1024 and ctx.path == "fused_n2048") else None
+    traffic = 2.0 * 1511371 * 1024 + 34849 * 1024 if (args.config == 2 and batch == 1024 and ctx.path == "fused_n2048") else None
     model_ops = alu_model_ops_per_pbs(p) * batch
     achieved = model_ops / (pbs_ms * 1e-3) / 1e12
     prepared_bytes = ctx.bsk_prepared_bytes()
