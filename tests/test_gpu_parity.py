@@ -290,3 +290,21 @@ def test_large_n_worst_case_magnitudes(slz, orc):
     want = orc.blind_rotate_batch(p, case.cts, luts, case.lut_idx, bsk, p.n)
     got = slz.to_host_u64(case.ctx.blind_rotate_batch(case.d_cts, slz.to_device_u64(luts), case.d_idx, d_bsk, p.n))
     assert np.array_equal(got, want)
+
+
+def test_work_is_enqueued_on_the_callers_stream(slz, orc):
+    # a non-default torch stream: the library must launch on the hipStream_t it is given (same HIP runtime as torch)
+    p, case = _fused_case(slz, orc, 3, 7)
+    want = orc.pbs_batch(p, case.cts, case.luts, case.lut_idx, case.keys.bsk)
+    want_small = orc.keyswitch_batch(p, want, case.keys.ksk)
+    stream = torch.cuda.Stream()
+    torch.cuda.synchronize()
+    with torch.cuda.stream(stream):
+        big = case.ctx.pbs_batch(case.d_cts, case.d_luts, case.d_idx, case.d_bsk)
+        small = case.ctx.keyswitch_batch(big, case.d_ksk)
+        case.ctx.set_option(slz.SLZ_OPT_FORCE_GENERIC, 1)
+        big_gen = case.ctx.pbs_batch(case.d_cts, case.d_luts, case.d_idx, case.d_bsk)
+    stream.synchronize()
+    assert np.array_equal(slz.to_host_u64(big), want)
+    assert np.array_equal(slz.to_host_u64(big_gen), want)
+    assert np.array_equal(slz.to_host_u64(small), want_small)
