@@ -84,11 +84,19 @@ k_big_cols_fwd(bign_args A) {
 // ---- P2 ------------------------------------------------------------------------------------------
 // one wave per (ciphertext, prime, 2048-block); four independent waves per workgroup
 __global__ void __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(1, 1)))
-k_big_rows(bign_args A, uint32_t G, uint32_t n_tasks) {
+k_big_rows(bign_args A, uint32_t G, uint32_t n_tasks, int xcd_aware) {
     extern __shared__ double lds[];
     const uint32_t lane = threadIdx.x & 63u;
     const uint32_t wv = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
-    const uint32_t task = blockIdx.x * 4 + wv;
+    // Workgroups are dealt round-robin to the 8 XCDs, each with its own 4 MiB L2, and one step's key is as large as
+    // one L2.  With xcd_aware the 2G (prime, block) combinations are split between the XCDs, so that an XCD only
+    // touches its 1/8 of the key and re-reads it from its L2 for every ciphertext of the chunk.
+    uint32_t task = blockIdx.x * 4 + wv;
+    if (xcd_aware) {
+        const uint32_t cpx = 2 * G / 8;                          // combinations per XCD
+        const uint32_t xcd = blockIdx.x & 7u, v = (blockIdx.x >> 3) * 4 + wv;
+        task = (v / cpx) * 2 * G + xcd * cpx + v % cpx;
+    }
     if (task >= n_tasks) return;                                 // whole wave leaves; no workgroup barriers below
     double *T = lds + wv * TBUF;
     const uint32_t row = task % G, q = (task / G) & 1u, b = task / (2 * G);
@@ -318,7 +326,9 @@ int slz_bign_cmux_steps(slz_ctx *ctx, const uint64_t *lwe_in, const double *bskp
             A.step = step;
             A.bskp_step = bskp + (size_t)step * 2 * R * 2 * N;
             launch_cols_any(true, G, A, nb, s);
-            hipLaunchKernelGGL(k_big_rows, dim3((n_tasks + 3) / 4), dim3(256), 4 * TBUF * sizeof(double), s, A, G, n_tasks);
+            // the XCD-aware order needs the task count to split evenly over 8 XCDs x 4 waves x (2G/8) combinations
+            const int xcd_aware = (2 * G) % 8 == 0 && n_tasks % 32 == 0 && (n_tasks / 8) % (2 * G / 8) == 0;
+            hipLaunchKernelGGL(k_big_rows, dim3((n_tasks + 3) / 4), dim3(256), 4 * TBUF * sizeof(double), s, A, G, n_tasks, xcd_aware);
             launch_cols_any(false, G, A, nb, s);
         }
     }
