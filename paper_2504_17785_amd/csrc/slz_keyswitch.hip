@@ -48,17 +48,32 @@ k_keyswitch(const uint64_t *__restrict__ lwe_in, const uint64_t *__restrict__ ks
         if (active) {
             const uint32_t cnt = min((uint32_t)KS_IC, i_end - ib) * l;
             const uint64_t *row = ksk + ((size_t)ib * l) * (n + 1) + x;
-            for (uint32_t r = 0; r < cnt; r++) {
-                const uint64_t w = row[(size_t)r * (n + 1)];
-                const uint32_t wl = (uint32_t)w, wh = (uint32_t)(w >> 32);
-                const uint4 d0 = *reinterpret_cast<const uint4 *>(&dig[r * KS_TB]);
-                const uint4 d1 = *reinterpret_cast<const uint4 *>(&dig[r * KS_TB + 4]);
-                const uint32_t u[KS_TB] = {d0.x, d0.y, d0.z, d0.w, d1.x, d1.y, d1.z, d1.w};
-                sumw += w;
+            // key words are requested four rows ahead of the multiply-adds that use them
+            uint64_t wq[4];
 #pragma unroll
-                for (int c = 0; c < KS_TB; c++) {
-                    accL[c] += (uint64_t)u[c] * wl;
-                    accH[c] += (uint64_t)u[c] * wh;
+            for (int u = 0; u < 4; u++) wq[u] = (uint32_t)u < cnt ? row[(size_t)u * (n + 1)] : 0ull;
+            for (uint32_t r0 = 0; r0 < cnt; r0 += 4) {
+                uint64_t wc[4];
+#pragma unroll
+                for (int u = 0; u < 4; u++) wc[u] = wq[u];
+#pragma unroll
+                for (int u = 0; u < 4; u++) wq[u] = (r0 + 4 + u < cnt) ? row[(size_t)(r0 + 4 + u) * (n + 1)] : 0ull;
+#pragma unroll
+                for (int u = 0; u < 4; u++) {
+                    const uint32_t r = r0 + u;
+                    if (r < cnt) {
+                        const uint64_t w = wc[u];
+                        const uint32_t wl = (uint32_t)w, wh = (uint32_t)(w >> 32);
+                        const uint4 d0 = *reinterpret_cast<const uint4 *>(&dig[r * KS_TB]);
+                        const uint4 d1 = *reinterpret_cast<const uint4 *>(&dig[r * KS_TB + 4]);
+                        const uint32_t u8[KS_TB] = {d0.x, d0.y, d0.z, d0.w, d1.x, d1.y, d1.z, d1.w};
+                        sumw += w;
+#pragma unroll
+                        for (int c = 0; c < KS_TB; c++) {
+                            accL[c] += (uint64_t)u8[c] * wl;
+                            accH[c] += (uint64_t)u8[c] * wh;
+                        }
+                    }
                 }
             }
         }
