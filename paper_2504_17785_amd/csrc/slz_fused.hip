@@ -1,4 +1,4 @@
-// Fused blind rotation for N = 2048, k = 1, l = 1 (the 128-bit-shaped low-precision parameter sets).
+// Fused blind rotation for N = 2048, k = 1, l = 1, any base (the 128-bit-shaped low-precision parameter sets).
 //
 // One workgroup of four wavefronts owns one ciphertext for the whole blind rotation; the accumulator
 // never leaves the chip.  Wave (q, h): q = transform prime, h = GGSW row = accumulator component.
@@ -29,7 +29,7 @@ struct fused_args {
     const double *bskp;
     uint64_t *acc_out;
     uint64_t *lwe_out;
-    uint32_t n, n_steps, batch;
+    uint32_t n, n_steps, batch, beta;
     // per-lane twiddle tables in HBM/L2, one per prime
     const double *fwd6[2];    // [32]      fwd[32 + x]: stage with stride 32 (one value per half-wave and register pair)
     const double *fwdB[2];    // [31][64]  last five forward stages, entry (k, lane)
@@ -123,8 +123,8 @@ k_fused_blind_rotate_n2048(fused_args A) {
                     const uint32_t neg = neg0 ^ (idx < r ? 1u : 0u);
                     const uint64_t a = Sh[(j >> 10) * (2u * TBUF) + (j & 1023u)];
                     const uint64_t lam = (neg ? (uint64_t)0 - a : a) - acc[e];
-                    uint64_t v = slz_round_top_bits(lam, 23);
-                    dg[e] = slz_next_digit(v, 23);
+                    uint64_t v = slz_round_top_bits(lam, A.beta);
+                    dg[e] = slz_next_digit(v, A.beta);
                     pd[64 * e + lane] = dg[e];
                 }
             }
@@ -242,7 +242,7 @@ k_fused_blind_rotate_n2048(fused_args A) {
 // ---- host side -----------------------------------------------------------------------------------
 
 int slz_fused_supported(const slz_params *p) {
-    return p->N == FN && p->k == 1 && p->pbs_level == 1 && p->pbs_base_log == 23;
+    return p->N == FN && p->k == 1 && p->pbs_level == 1 && p->pbs_base_log <= 30;
 }
 
 int slz_fused_init(slz_ctx *ctx) {
@@ -293,7 +293,7 @@ int slz_fused_blind_rotate(slz_ctx *ctx, const uint64_t *lwe_in, const uint64_t 
                            hipStream_t s) {
     fused_args A;
     A.lwe_in = lwe_in; A.luts = luts; A.lut_idx = lut_idx; A.bskp = bskp; A.acc_out = acc_out; A.lwe_out = lwe_out;
-    A.n = ctx->prm.n; A.n_steps = n_steps; A.batch = batch;
+    A.n = ctx->prm.n; A.n_steps = n_steps; A.batch = batch; A.beta = ctx->prm.pbs_base_log;
     for (int q = 0; q < 2; q++) {
         A.fwd6[q] = ctx->tab[q].fwd + 32;
         A.fwdB[q] = ctx->fused_tab + (size_t)q * 31 * 64;

@@ -237,6 +237,14 @@ def test_fused_worst_case_magnitudes_and_generic_agreement(slz, orc):
     assert np.array_equal(gen, want)
 
 
+def test_fused_other_gadget_bases(slz, orc):
+    for beta in (8, 16, 21):
+        p, case = _fused_case(slz, orc, 3, 4, pbs_base_log=beta)
+        want = orc.pbs_batch(p, case.cts, case.luts, case.lut_idx, case.keys.bsk)
+        got = slz.to_host_u64(case.ctx.pbs_batch(case.d_cts, case.d_luts, case.d_idx, case.d_bsk))
+        assert np.array_equal(got, want), beta
+
+
 def test_fused_more_ciphertexts_than_resident_workgroups(slz, orc):
     # 600 ciphertexts > 512 resident workgroups: some workgroups process two; compare the fused path with the
     # generic path on all, and with the oracle on a sample
