@@ -56,6 +56,7 @@ struct slz_ctx {
     double *dig;              // [max_batch][(k+1)l][N]
     double *xhat;             // [max_batch][2][(k+1)l][N]
     double *outhat;           // [max_batch][2][k+1][N]
+    void *ks_dig;             // digit bytes of the matrix-core keyswitch (allocated at its first call)
     uint32_t fwd_reduce_mask; // bit s: fully reduce all values before forward stage s (0-based)
     uint32_t inv_reduce_mask; // same for the inverse stages
     double fwd_out_bound;     // bound (in units of p) of forward outputs
@@ -90,5 +91,10 @@ int slz_bign_cmux_steps(slz_ctx *ctx, const uint64_t *lwe_in, const double *bskp
 // keyswitch / lincomb (slz_keyswitch.hip)
 int slz_keyswitch_launch(slz_ctx *ctx, const uint64_t *lwe_in, const uint64_t *ksk, uint64_t *lwe_out,
                          uint32_t batch, hipStream_t s);
+// matrix-core keyswitch (slz_keyswitch_mfma.hip); lwe_out must already hold (0, .., 0, b')
+int slz_ksm_supported(const slz_params *p);
+void slz_ksm_destroy(slz_ctx *ctx);
+int slz_ksm_launch(slz_ctx *ctx, const uint64_t *lwe_in, const uint64_t *ksk, uint64_t *lwe_out, uint32_t batch,
+                   hipStream_t s);
 int slz_lincomb_launch(slz_ctx *ctx, const uint64_t *cts, const int32_t *w, uint64_t *out, uint32_t G, uint32_t J,
                        uint32_t O, hipStream_t s);

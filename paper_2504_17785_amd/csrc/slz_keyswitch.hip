@@ -7,6 +7,7 @@
 #define KS_TB 8            // ciphertexts per workgroup (each key word is reused KS_TB times from a register)
 #define KS_IC 16           // mask words decomposed per LDS refill
 #define KS_MAX_L 16
+#define KS_MFMA_MIN_BATCH 16
 
 __global__ void __launch_bounds__(KS_THREADS)
 k_ks_init(const uint64_t *__restrict__ lwe_in, uint64_t *__restrict__ out, uint32_t kN, uint32_t n, uint32_t batch) {
@@ -98,6 +99,11 @@ int slz_keyswitch_launch(slz_ctx *ctx, const uint64_t *lwe_in, const uint64_t *k
     size_t total = (size_t)batch * (n + 1);
     hipLaunchKernelGGL(k_ks_init, dim3((unsigned)((total + KS_THREADS - 1) / KS_THREADS)), dim3(KS_THREADS), 0, s, lwe_in, lwe_out,
                        kN, n, batch);
+    // digits of at most a byte and enough ciphertexts to fill matrix-core tiles: int8 MFMA contraction
+    if (!ctx->force_generic && batch >= KS_MFMA_MIN_BATCH && slz_ksm_supported(&p)) {
+        int rc = slz_ksm_launch(ctx, lwe_in, ksk, lwe_out, batch, s);
+        if (rc != SLZ_E_UNSUPPORTED) return rc;
+    }
     uint32_t xt = (n + 1 + KS_THREADS - 1) / KS_THREADS, ct = (batch + KS_TB - 1) / KS_TB;
     // enough segments of the mask index to give the 256 CUs several workgroups each
     uint32_t segs = 1;

@@ -1,0 +1,261 @@
+// LWE key switching as an int8 matrix-core contraction (gfx950 v_mfma_i32_32x32x32_i8).
+//
+// out[c][x] -= sum_rho d_rho(c) * KSK_rho[x] (mod 2^64) is a dense product of the digit matrix (ciphertexts x key rows,
+// digits in [-B/2, B/2), one byte each when B <= 2^8) with the key matrix (key rows x output words).  A 64-bit key word w
+// is recoded into eight signed bytes s_p in [-128, 128) with w = sum_p s_p 2^(8p) (mod 2^64): s_p is byte p of
+// (w + 0x80..80) with its top bit flipped.  Each byte plane is one int8 x int8 -> int32 contraction; the eight plane sums
+// are recombined with shifts at the end.  Products are at most 2^14 in magnitude, so an int32 accumulator is exact for
+// fewer than 2^17 key rows; the host keeps every segment of the row index below that.
+//
+// Row order inside the contraction is level-major, rho = j * kN + i, so that 16 consecutive rows are 16 consecutive mask
+// words at one level (kN must be a multiple of 32).
+#include "slz_internal.h"
+#include "slz_modarith.h"
+
+typedef int v16i __attribute__((ext_vector_type(16)));
+typedef int v4i __attribute__((ext_vector_type(4)));
+
+#define KM_WAVES 8                      // waves per workgroup = 32-ciphertext tiles per workgroup
+#define KM_THREADS (64 * KM_WAVES)
+#define KM_IT_KB 4                      // 32-row blocks per iteration: each thread brings in 8 rows of one output word
+#define KM_BUF_V4 (KM_IT_KB * 2 * 8 * 32)   // 16-byte slots per LDS buffer: [block][half][plane][x]
+
+// ---- digits --------------------------------------------------------------------------------------------------------
+// dig[tile][kb][lane] (16 bytes): the A operand of lane `lane` for 32-row block kb of 32-ciphertext tile `tile`:
+// ciphertext 32 tile + lane % 32, rows 32 kb + 16 (lane / 32) + t for byte t.  Ciphertexts past the batch get zero digits.
+// Signed digits without a carry chain: with H = sum_j (B/2) B^(l-j), digit j of v is ((v + H) >> beta (l-j)) mod B - B/2.
+__global__ void __launch_bounds__(256)
+k_ksm_digits(const uint64_t *__restrict__ lwe_in, v4i *__restrict__ dig, uint32_t kN, uint32_t beta, uint32_t l, uint32_t batch,
+             uint32_t n_kb) {
+    const uint32_t cin = threadIdx.x % 32;
+    const uint32_t g16 = blockIdx.x * 8 + threadIdx.x / 32;     // group of 16 mask words
+    const uint32_t tile = blockIdx.y;
+    if (g16 >= kN / 16) return;
+    const uint32_t c = tile * 32 + cin;
+    const uint32_t bits = beta * l;
+    const uint32_t half_b = 1u << (beta - 1);
+    uint64_t H = 0;
+    for (uint32_t j = 0; j < l; j++) H |= (uint64_t)half_b << (beta * j);
+    uint64_t v[16];
+#pragma unroll
+    for (int t = 0; t < 16; t++) {
+        uint64_t a = c < batch ? lwe_in[(size_t)c * (kN + 1) + 16 * g16 + t] : 0ull;
+        v[t] = slz_round_top_bits(a, bits) + H;
+    }
+    for (uint32_t jj = 0; jj < l; jj++) {                       // level jj + 1, most significant first
+        const uint32_t sh = beta * (l - 1 - jj);
+        uint32_t wds[4];
+#pragma unroll
+        for (int q = 0; q < 4; q++) {
+            uint32_t wd = 0;
+#pragma unroll
+            for (int t = 0; t < 4; t++) {
+                uint32_t u = (uint32_t)(v[4 * q + t] >> sh) & (2 * half_b - 1);
+                wd |= ((u - half_b) & 0xffu) << (8 * t);
+            }
+            wds[q] = wd;
+        }
+        v4i o = {(int)wds[0], (int)wds[1], (int)wds[2], (int)wds[3]};
+        const uint32_t kb = (jj * kN + 16 * g16) / 32;
+        dig[((size_t)tile * n_kb + kb) * 64 + cin + 32 * (g16 & 1)] = o;
+    }
+}
+
+// ---- contraction ---------------------------------------------------------------------------------------------------
+struct ksm_args {
+    const uint64_t *ksk;
+    const v4i *dig;
+    uint64_t *out;
+    uint32_t kN, n, l, batch;
+    uint32_t n_tiles;       // 32-ciphertext tiles in dig
+    uint32_t n_kb;          // 32-row blocks in total (l kN / 32)
+    uint32_t kb_per_seg;    // multiple of KM_IT_KB
+    uint32_t x_tiles, ct_groups, total;   // work items: (segment, x tile, ciphertext group), group fastest
+    uint32_t per_xcd;
+};
+
+// 4x4 byte transpose of four dwords: o[p] = byte p of a0, a1, a2, a3 (a0 in the low byte)
+__device__ __forceinline__ void ksm_tr4(uint32_t a0, uint32_t a1, uint32_t a2, uint32_t a3, uint32_t o[4]) {
+    uint32_t t01l = __builtin_amdgcn_perm(a1, a0, 0x05010400u);   // a0.b0 a1.b0 a0.b1 a1.b1
+    uint32_t t01h = __builtin_amdgcn_perm(a1, a0, 0x07030602u);   // a0.b2 a1.b2 a0.b3 a1.b3
+    uint32_t t23l = __builtin_amdgcn_perm(a3, a2, 0x05010400u);
+    uint32_t t23h = __builtin_amdgcn_perm(a3, a2, 0x07030602u);
+    o[0] = __builtin_amdgcn_perm(t23l, t01l, 0x05040100u);
+    o[1] = __builtin_amdgcn_perm(t23l, t01l, 0x07060302u);
+    o[2] = __builtin_amdgcn_perm(t23h, t01h, 0x05040100u);
+    o[3] = __builtin_amdgcn_perm(t23h, t01h, 0x07060302u);
+}
+
+__global__ void __launch_bounds__(KM_THREADS) __attribute__((amdgpu_waves_per_eu(2, 2)))
+k_ksm_main(ksm_args A) {
+    __shared__ v4i lds[2 * KM_BUF_V4];                              // 64 KiB
+    // work items are dealt so that one XCD (workgroups b, b+8, ...) walks a contiguous range: the workgroups resident on
+    // it share a segment of the key and neighbouring output words, which its L2 then serves
+    const uint32_t item = (blockIdx.x % 8) * A.per_xcd + blockIdx.x / 8;
+    if (blockIdx.x / 8 >= A.per_xcd || item >= A.total) return;
+    const uint32_t cg = item % A.ct_groups;
+    const uint32_t xt = (item / A.ct_groups) % A.x_tiles;
+    const uint32_t seg = item / (A.ct_groups * A.x_tiles);
+    const uint32_t lane = threadIdx.x % 64;
+    const uint32_t wave = __builtin_amdgcn_readfirstlane(threadIdx.x / 64);
+    const uint32_t tile = cg * KM_WAVES + wave;
+    const bool tile_ok = tile < A.n_tiles;
+    const uint32_t kb_begin = seg * A.kb_per_seg;
+    const uint32_t kb_end = min(A.n_kb, kb_begin + A.kb_per_seg);
+    const uint32_t width = A.n + 1;
+
+    // key-loading role: output word x, rows 8 oct .. 8 oct + 7 of the iteration's 128 rows
+    const uint32_t xl = lane % 32;
+    const uint32_t x = xt * 32 + xl;
+    const uint32_t oct = 2 * wave + lane / 32;
+    const bool x_ok = x < width;
+    const size_t row_stride = (size_t)A.l * width;                  // words between consecutive mask indices at one level
+    // level j and mask index i of this thread's first row; both advance by 128 rows per iteration
+    uint32_t rho = kb_begin * 32 + 8 * oct;
+    uint32_t j = rho / A.kN, i = rho % A.kN;
+    const uint32_t lds_w = ((((oct / 4) * 2 + (oct / 2) % 2) * 8) * 32 + xl) * 2 + (oct & 1);   // in 8-byte units, plane 0
+
+    uint64_t kw[8];
+    v4i an[KM_IT_KB];
+    auto load_key = [&](uint32_t it) {
+        const bool ok = x_ok && (it + oct / 4 < kb_end);
+        const uint64_t *src = A.ksk + ((size_t)i * A.l + j) * width + x;
+#pragma unroll
+        for (int t = 0; t < 8; t++) kw[t] = ok ? src[(size_t)t * row_stride] : 0ull;
+        i += 128;
+        while (i >= A.kN) { i -= A.kN; j++; }
+    };
+    auto load_dig = [&](uint32_t it) {
+#pragma unroll
+        for (int q = 0; q < KM_IT_KB; q++) {
+            v4i z = {0, 0, 0, 0};
+            an[q] = (tile_ok && it + q < kb_end) ? A.dig[((size_t)tile * A.n_kb + it + q) * 64 + lane] : z;
+        }
+    };
+
+    v16i acc[8];
+#pragma unroll
+    for (int p = 0; p < 8; p++)
+#pragma unroll
+        for (int r = 0; r < 16; r++) acc[p][r] = 0;
+
+    load_key(kb_begin);
+    load_dig(kb_begin);
+    uint32_t buf = 0;
+    for (uint32_t it = kb_begin; it < kb_end; it += KM_IT_KB) {
+        // recode to signed bytes, transpose 8 rows x 8 planes, park the plane operands in LDS
+        {
+            uint32_t lo[8], hi[8];
+#pragma unroll
+            for (int t = 0; t < 8; t++) {
+                uint64_t w = (kw[t] + 0x8080808080808080ull) ^ 0x8080808080808080ull;
+                lo[t] = (uint32_t)w;
+                hi[t] = (uint32_t)(w >> 32);
+            }
+            uint32_t pl0[4], pl1[4], ph0[4], ph1[4];
+            ksm_tr4(lo[0], lo[1], lo[2], lo[3], pl0);               // planes 0..3, rows 0..3
+            ksm_tr4(lo[4], lo[5], lo[6], lo[7], pl1);               // planes 0..3, rows 4..7
+            ksm_tr4(hi[0], hi[1], hi[2], hi[3], ph0);               // planes 4..7, rows 0..3
+            ksm_tr4(hi[4], hi[5], hi[6], hi[7], ph1);
+            uint64_t *dst = reinterpret_cast<uint64_t *>(lds + buf * KM_BUF_V4) + lds_w;
+#pragma unroll
+            for (int p = 0; p < 4; p++) {
+                dst[(size_t)p * 64] = (uint64_t)pl0[p] | ((uint64_t)pl1[p] << 32);
+                dst[(size_t)(p + 4) * 64] = (uint64_t)ph0[p] | ((uint64_t)ph1[p] << 32);
+            }
+        }
+        v4i ac[KM_IT_KB];
+#pragma unroll
+        for (int q = 0; q < KM_IT_KB; q++) ac[q] = an[q];
+        if (it + KM_IT_KB < kb_end) {                               // next iteration's words are in flight during the MFMAs
+            load_key(it + KM_IT_KB);
+            load_dig(it + KM_IT_KB);
+        }
+        __syncthreads();
+        // one barrier per iteration is enough with two buffers: a wave reaches the barrier of iteration t only after it
+        // has read everything of iteration t-1, and buffer (t+1)%2 is not written before that barrier
+        if (tile_ok) {
+            const v4i *src = lds + buf * KM_BUF_V4 + (lane / 32) * (8 * 32) + xl;
+#pragma unroll
+            for (int q = 0; q < KM_IT_KB; q++) {
+                if (it + q < kb_end) {
+#pragma unroll
+                    for (int p = 0; p < 8; p++) {
+                        v4i b = src[(q * 2 * 8 + p) * 32];
+                        acc[p] = __builtin_amdgcn_mfma_i32_32x32x32_i8(ac[q], b, acc[p], 0, 0, 0);
+                    }
+                }
+            }
+        }
+        buf ^= 1;
+    }
+    if (!tile_ok || !x_ok) return;
+    // accumulator register r of a lane is ciphertext 8 (r / 4) + 4 (lane / 32) + r % 4 of the tile, output word x
+#pragma unroll
+    for (int r = 0; r < 16; r++) {
+        const uint32_t c = tile * 32 + 8 * (r / 4) + 4 * (lane / 32) + (r % 4);
+        if (c < A.batch) {
+            uint64_t val = 0;
+#pragma unroll
+            for (int p = 0; p < 8; p++) val += (uint64_t)(int64_t)acc[p][r] << (8 * p);
+            atomicAdd((unsigned long long *)&A.out[(size_t)c * width + x], (unsigned long long)(0 - val));
+        }
+    }
+}
+
+int slz_ksm_supported(const slz_params *p) {
+    return p->ks_base_log <= 8 && ((uint64_t)p->k * p->N) % 32 == 0;
+}
+
+void slz_ksm_destroy(slz_ctx *ctx) {
+    if (ctx->ks_dig) (void)hipFree(ctx->ks_dig);
+    ctx->ks_dig = nullptr;
+}
+
+// `lwe_out` must already hold (0, .., 0, b').
+int slz_ksm_launch(slz_ctx *ctx, const uint64_t *lwe_in, const uint64_t *ksk, uint64_t *lwe_out, uint32_t batch, hipStream_t s) {
+    const slz_params &p = ctx->prm;
+    const uint32_t kN = p.k * p.N;
+    const uint64_t n_kb64 = (uint64_t)p.ks_level * kN / 32;
+    if (n_kb64 > (1u << 26)) return SLZ_E_UNSUPPORTED;
+    const uint32_t n_kb = (uint32_t)n_kb64;
+    const uint32_t max_tiles = min((ctx->max_batch + 31) / 32, 32768u);
+    if (!ctx->ks_dig) {     // digit scratch, sized for max_batch (larger batches go through in chunks)
+        if (hipMalloc((void **)&ctx->ks_dig, (size_t)max_tiles * n_kb * 1024) != hipSuccess) {
+            (void)hipGetLastError();
+            ctx->ks_dig = nullptr;
+            return SLZ_E_NOMEM;
+        }
+    }
+    ksm_args A;
+    A.ksk = ksk;
+    A.dig = (const v4i *)ctx->ks_dig;
+    A.kN = kN; A.n = p.n; A.l = p.ks_level;
+    A.n_kb = n_kb;
+    A.x_tiles = (p.n + 1 + 31) / 32;
+    // int32 accumulators: 32 kb_per_seg rows of |digit * byte| <= 2^(beta-1) * 2^7 must stay strictly below 2^31
+    const uint32_t kb_cap = (1u << (20 - p.ks_base_log)) - KM_IT_KB;
+    for (uint32_t c0 = 0; c0 < batch; c0 += max_tiles * 32) {
+        const uint32_t nb = min(batch - c0, max_tiles * 32);
+        A.batch = nb;
+        A.n_tiles = (nb + 31) / 32;
+        A.ct_groups = (A.n_tiles + KM_WAVES - 1) / KM_WAVES;
+        A.out = lwe_out + (size_t)c0 * (p.n + 1);
+        // segments of the row index: enough workgroups for three rounds over the 256 CUs
+        uint32_t segs = (768 + A.x_tiles * A.ct_groups - 1) / (A.x_tiles * A.ct_groups);
+        segs = max(1u, min(segs, (n_kb + 7) / 8));
+        uint32_t kbs = ((n_kb + segs - 1) / segs + KM_IT_KB - 1) / KM_IT_KB * KM_IT_KB;
+        kbs = min(kbs, kb_cap);
+        segs = (n_kb + kbs - 1) / kbs;
+        A.kb_per_seg = kbs;
+        const uint64_t total = (uint64_t)segs * A.x_tiles * A.ct_groups;
+        if (total > (1u << 30)) return SLZ_E_UNSUPPORTED;
+        A.total = (uint32_t)total;
+        A.per_xcd = (A.total + 7) / 8;
+        hipLaunchKernelGGL(k_ksm_digits, dim3((kN / 16 + 7) / 8, A.n_tiles), dim3(256), 0, s,
+                           lwe_in + (size_t)c0 * (kN + 1), (v4i *)ctx->ks_dig, kN, p.ks_base_log, p.ks_level, nb, n_kb);
+        hipLaunchKernelGGL(k_ksm_main, dim3(A.per_xcd * 8), dim3(KM_THREADS), 0, s, A);
+    }
+    SLZ_HIP(hipGetLastError());
+    return SLZ_OK;
+}

@@ -113,6 +113,44 @@ def test_keyswitch_matches_oracle(slz, orc, batch, kN, n, beta, l):
     assert np.array_equal(got, orc.keyswitch_batch(p, cts, ksk))
 
 
+@pytest.mark.parametrize("batch,k,N,n,beta,l", [(16, 1, 32, 5, 8, 8), (300, 3, 32, 100, 1, 7), (65, 1, 512, 31, 7, 9),
+                                                 (257, 1, 256, 32, 4, 16), (1024, 1, 1024, 63, 2, 3), (33, 2, 64, 64, 6, 1)])
+def test_matrix_core_keyswitch_matches_oracle_and_scalar_path(slz, orc, batch, k, N, n, beta, l):
+    # digits of at most a byte and 16 or more ciphertexts: the int8 matrix-core contraction.  Ragged ciphertext tiles,
+    # ragged output-word tiles, several workgroup groups, 64-bit decompositions, k > 1.
+    p = tiny(n=n, N=N, k=k, ks_base_log=beta, ks_level=l)
+    kN = k * N
+    ksk = synth.raw_words(p, "raw_ksk", kN * l * (n + 1)).reshape(kN, l, n + 1)
+    cts = synth.raw_words(p, "raw_ct", batch * (kN + 1)).reshape(batch, kN + 1)
+    want = orc.keyswitch_batch(p, cts, ksk)
+    d_cts, d_ksk = slz.to_device_u64(cts), slz.to_device_u64(ksk)
+    ctx = slz.Context(p, batch)
+    assert np.array_equal(slz.to_host_u64(ctx.keyswitch_batch(d_cts, d_ksk)), want)
+    ctx.set_option(slz.SLZ_OPT_FORCE_GENERIC, 1)
+    assert np.array_equal(slz.to_host_u64(ctx.keyswitch_batch(d_cts, d_ksk)), want)
+    # a context made for fewer ciphertexts takes the batch in chunks
+    ctx_small = slz.Context(p, 40)
+    assert np.array_equal(slz.to_host_u64(ctx_small.keyswitch_batch(d_cts, d_ksk)), want)
+
+
+def test_matrix_core_keyswitch_extreme_bytes_and_digits(slz, orc):
+    # key words whose bytes sit at the edges of the signed-byte recoding (0x7f / 0x80 / 0xff / 0x00 with and without carry
+    # into the next byte) against mask words whose digits are all -B/2, all B/2 - 1, or carry through every level
+    p = tiny(n=70, N=256, k=1, ks_base_log=8, ks_level=8)
+    kN, l, n, batch = 256, 8, 70, 48
+    pats = np.array([0x8080808080808080, 0x7f7f7f7f7f7f7f7f, 0xffffffffffffffff, 0x0000000000000000, 0x807f807f807f807f,
+                     0x7f807f807f807f80, 0xff7fff80007f0080, 0x0100000000000080], dtype=np.uint64)
+    ksk = pats[(np.arange(kN * l * (n + 1)) * 5 // 3) % len(pats)].reshape(kN, l, n + 1)
+    cts = pats[(np.arange(batch * (kN + 1)) // 7) % len(pats)].reshape(batch, kN + 1)
+    cts[0, :] = np.uint64(0x8080808080808080)
+    cts[1, :] = np.uint64(0x7f7f7f7f7f7f7f7f)
+    ksk[:, :, 0] = np.uint64(0x8080808080808080)
+    ksk[:, :, 1] = np.uint64(0x7f7f7f7f7f7f7f7f)
+    ctx = slz.Context(p, batch)
+    got = slz.to_host_u64(ctx.keyswitch_batch(slz.to_device_u64(cts), slz.to_device_u64(ksk)))
+    assert np.array_equal(got, orc.keyswitch_batch(p, cts, ksk))
+
+
 def test_lincomb_matches_oracle(slz, orc):
     p = tiny(n=42)
     G, J, O = 5, 37, 19
