@@ -65,7 +65,8 @@ typedef struct {
 typedef struct slz_ctx slz_ctx;   /* opaque: parameter copy, twiddle tables, scratch for max_batch */
 
 /* Context options for slz_ctx_set_option. */
-#define SLZ_OPT_FORCE_GENERIC 1   /* value != 0: always use the multi-kernel global-memory path */
+#define SLZ_OPT_FORCE_GENERIC 1   /* value != 0: always use the multi-kernel global-memory blind rotation and the
+                                     scalar-ALU keyswitch (the kernels every shape has; for cross-checks) */
 
 /* Creates a context on the current device.  Allocates transform tables and scratch sized for
  * `max_batch` ciphertexts.  Fails with SLZ_E_UNSUPPORTED when the exactness bound
@@ -109,7 +110,10 @@ int slz_blind_rotate_batch(slz_ctx *ctx, const uint64_t *lwe_in_dev, const uint6
 
 /* LWE key switching from dimension kN to n:
  *   out = (0,..,0, b') - sum_{i<kN} sum_{j=1..l_ks} d_j(a'_i) * KSK[i][j]   (vectors of n+1 words).
- * lwe_in_dev [batch][kN+1];  ksk_dev [kN][l_ks][n+1];  lwe_out_dev [batch][n+1]. */
+ * lwe_in_dev [batch][kN+1];  ksk_dev [kN][l_ks][n+1];  lwe_out_dev [batch][n+1].
+ * With a keyswitch base of at most 2^8 and kN a multiple of 32 the contraction runs on the int8 matrix cores; its
+ * digit scratch (32 * ceil(max_batch / 32) * kN * l_ks bytes) is allocated by the first such call (SLZ_E_NOMEM if
+ * that fails) and larger batches are taken in chunks of max_batch. */
 int slz_keyswitch_batch(slz_ctx *ctx, const uint64_t *lwe_in_dev, const uint64_t *ksk_dev,
                         uint64_t *lwe_out_dev, uint32_t batch, void *hip_stream);
 

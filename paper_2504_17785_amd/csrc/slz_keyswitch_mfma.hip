@@ -17,7 +17,8 @@ typedef int v4i __attribute__((ext_vector_type(4)));
 
 #define KM_WAVES 8                      // waves per workgroup = 32-ciphertext tiles per workgroup
 #define KM_THREADS (64 * KM_WAVES)
-#define KM_IT_KB 4                      // 32-row blocks per iteration: each thread brings in 8 rows of one output word
+#define KM_IT_KB (KM_WAVES / 2)         // 32-row blocks per iteration: each thread brings in 8 rows of one output word
+#define KM_TARGET_WGS 768               // workgroups aimed for when the row index is cut into segments (three per CU)
 #define KM_BUF_V4 (KM_IT_KB * 2 * 8 * 32)   // 16-byte slots per LDS buffer: [block][half][plane][x]
 
 // ---- digits --------------------------------------------------------------------------------------------------------
@@ -69,7 +70,7 @@ struct ksm_args {
     uint32_t kN, n, l, batch;
     uint32_t n_tiles;       // 32-ciphertext tiles in dig
     uint32_t n_kb;          // 32-row blocks in total (l kN / 32)
-    uint32_t kb_per_seg;    // multiple of KM_IT_KB
+    uint32_t kb_per_seg;    // multiple of 2 KM_IT_KB
     uint32_t x_tiles, ct_groups, total;   // work items: (segment, x tile, ciphertext group), group fastest
     uint32_t per_xcd;
 };
@@ -104,33 +105,36 @@ k_ksm_main(ksm_args A) {
     const uint32_t kb_end = min(A.n_kb, kb_begin + A.kb_per_seg);
     const uint32_t width = A.n + 1;
 
-    // key-loading role: output word x, rows 8 oct .. 8 oct + 7 of the iteration's 128 rows
+    // key-loading role: output word x, rows 8 oct .. 8 oct + 7 of the iteration's 32 KM_IT_KB rows
     const uint32_t xl = lane % 32;
     const uint32_t x = xt * 32 + xl;
     const uint32_t oct = 2 * wave + lane / 32;
     const bool x_ok = x < width;
     const size_t row_stride = (size_t)A.l * width;                  // words between consecutive mask indices at one level
-    // level j and mask index i of this thread's first row; both advance by 128 rows per iteration
+    // level j and mask index i of this thread's first row; both advance by 32 KM_IT_KB rows per iteration
     uint32_t rho = kb_begin * 32 + 8 * oct;
     uint32_t j = rho / A.kN, i = rho % A.kN;
     const uint32_t lds_w = ((((oct / 4) * 2 + (oct / 2) % 2) * 8) * 32 + xl) * 2 + (oct & 1);   // in 8-byte units, plane 0
 
-    uint64_t kw[8];
-    v4i an[KM_IT_KB];
-    auto load_key = [&](uint32_t it) {
-        const bool ok = x_ok && (it + oct / 4 < kb_end);
-        const uint64_t *src = A.ksk + ((size_t)i * A.l + j) * width + x;
+    // Two register stages of key words and digit operands: what iteration t consumes was requested during iteration t-2,
+    // so a load has two iterations of MFMAs to arrive.  Loads are unconditional (rows or words out of range read a valid
+    // address and are replaced by zero when consumed), which keeps the wait counts static.
+    uint64_t kw0[8], kw1[8];
+    bool ok0, ok1;
+    v4i an0[KM_IT_KB], an1[KM_IT_KB];
+    auto load_key = [&](uint64_t (&kw)[8], bool &ok, uint32_t it) {
+        ok = x_ok && (it + oct / 4 < kb_end);
+        const uint64_t *src = A.ksk + (ok ? ((size_t)i * A.l + j) * width + x : (size_t)0);
 #pragma unroll
-        for (int t = 0; t < 8; t++) kw[t] = ok ? src[(size_t)t * row_stride] : 0ull;
-        i += 128;
+        for (int t = 0; t < 8; t++) kw[t] = src[(size_t)t * row_stride];
+        i += 32 * KM_IT_KB;
         while (i >= A.kN) { i -= A.kN; j++; }
     };
-    auto load_dig = [&](uint32_t it) {
+    const size_t dig_base = (size_t)(tile_ok ? tile : 0) * A.n_kb;
+    auto load_dig = [&](v4i (&an)[KM_IT_KB], uint32_t it) {
+        // blocks past the end of the segment meet zero key bytes, so their digits need no masking
 #pragma unroll
-        for (int q = 0; q < KM_IT_KB; q++) {
-            v4i z = {0, 0, 0, 0};
-            an[q] = (tile_ok && it + q < kb_end) ? A.dig[((size_t)tile * A.n_kb + it + q) * 64 + lane] : z;
-        }
+        for (int q = 0; q < KM_IT_KB; q++) an[q] = A.dig[(dig_base + min(it + q, A.n_kb - 1)) * 64 + lane];
     };
 
     v16i acc[8];
@@ -139,16 +143,14 @@ k_ksm_main(ksm_args A) {
 #pragma unroll
         for (int r = 0; r < 16; r++) acc[p][r] = 0;
 
-    load_key(kb_begin);
-    load_dig(kb_begin);
     uint32_t buf = 0;
-    for (uint32_t it = kb_begin; it < kb_end; it += KM_IT_KB) {
+    auto body = [&](uint64_t (&kw)[8], bool &ok, v4i (&an)[KM_IT_KB], uint32_t it) {
         // recode to signed bytes, transpose 8 rows x 8 planes, park the plane operands in LDS
         {
             uint32_t lo[8], hi[8];
 #pragma unroll
             for (int t = 0; t < 8; t++) {
-                uint64_t w = (kw[t] + 0x8080808080808080ull) ^ 0x8080808080808080ull;
+                uint64_t w = ok ? (kw[t] + 0x8080808080808080ull) ^ 0x8080808080808080ull : 0ull;
                 lo[t] = (uint32_t)w;
                 hi[t] = (uint32_t)(w >> 32);
             }
@@ -164,30 +166,39 @@ k_ksm_main(ksm_args A) {
                 dst[(size_t)(p + 4) * 64] = (uint64_t)ph0[p] | ((uint64_t)ph1[p] << 32);
             }
         }
-        v4i ac[KM_IT_KB];
-#pragma unroll
-        for (int q = 0; q < KM_IT_KB; q++) ac[q] = an[q];
-        if (it + KM_IT_KB < kb_end) {                               // next iteration's words are in flight during the MFMAs
-            load_key(it + KM_IT_KB);
-            load_dig(it + KM_IT_KB);
-        }
+        load_key(kw, ok, it + 2 * KM_IT_KB);
         __syncthreads();
         // one barrier per iteration is enough with two buffers: a wave reaches the barrier of iteration t only after it
         // has read everything of iteration t-1, and buffer (t+1)%2 is not written before that barrier
         if (tile_ok) {
+            // the plane operands of the next half block are read from LDS while four MFMAs run
             const v4i *src = lds + buf * KM_BUF_V4 + (lane / 32) * (8 * 32) + xl;
+            v4i bb[2][4];
 #pragma unroll
-            for (int q = 0; q < KM_IT_KB; q++) {
-                if (it + q < kb_end) {
+            for (int p = 0; p < 4; p++) bb[0][p] = src[p * 32];
 #pragma unroll
-                    for (int p = 0; p < 8; p++) {
-                        v4i b = src[(q * 2 * 8 + p) * 32];
-                        acc[p] = __builtin_amdgcn_mfma_i32_32x32x32_i8(ac[q], b, acc[p], 0, 0, 0);
-                    }
+            for (int g = 0; g < 2 * KM_IT_KB; g++) {               // half block g: block g/2, planes 4 (g%2) .. +3
+                if (g + 1 < 2 * KM_IT_KB) {
+#pragma unroll
+                    for (int p = 0; p < 4; p++) bb[(g + 1) & 1][p] = src[(((g + 1) / 2) * 2 * 8 + 4 * ((g + 1) % 2) + p) * 32];
                 }
+                __builtin_amdgcn_sched_barrier(0);      // keep the reads above the MFMAs they overlap with
+#pragma unroll
+                for (int p = 0; p < 4; p++)
+                    acc[4 * (g % 2) + p] = __builtin_amdgcn_mfma_i32_32x32x32_i8(an[g / 2], bb[g & 1][p], acc[4 * (g % 2) + p], 0, 0, 0);
+                __builtin_amdgcn_sched_barrier(0);
             }
         }
+        load_dig(an, it + 2 * KM_IT_KB);
         buf ^= 1;
+    };
+    load_key(kw0, ok0, kb_begin);
+    load_dig(an0, kb_begin);
+    load_key(kw1, ok1, kb_begin + KM_IT_KB);
+    load_dig(an1, kb_begin + KM_IT_KB);
+    for (uint32_t it = kb_begin; it < kb_end; it += 2 * KM_IT_KB) {  // kb_per_seg is a multiple of 2 KM_IT_KB
+        body(kw0, ok0, an0, it);
+        body(kw1, ok1, an1, it + KM_IT_KB);
     }
     if (!tile_ok || !x_ok) return;
     // accumulator register r of a lane is ciphertext 8 (r / 4) + 4 (lane / 32) + r % 4 of the tile, output word x
@@ -234,17 +245,18 @@ int slz_ksm_launch(slz_ctx *ctx, const uint64_t *lwe_in, const uint64_t *ksk, ui
     A.n_kb = n_kb;
     A.x_tiles = (p.n + 1 + 31) / 32;
     // int32 accumulators: 32 kb_per_seg rows of |digit * byte| <= 2^(beta-1) * 2^7 must stay strictly below 2^31
-    const uint32_t kb_cap = (1u << (20 - p.ks_base_log)) - KM_IT_KB;
+    const uint32_t kb_cap = (1u << (20 - p.ks_base_log)) - 2 * KM_IT_KB;
     for (uint32_t c0 = 0; c0 < batch; c0 += max_tiles * 32) {
         const uint32_t nb = min(batch - c0, max_tiles * 32);
         A.batch = nb;
         A.n_tiles = (nb + 31) / 32;
         A.ct_groups = (A.n_tiles + KM_WAVES - 1) / KM_WAVES;
         A.out = lwe_out + (size_t)c0 * (p.n + 1);
-        // segments of the row index: enough workgroups for three rounds over the 256 CUs
-        uint32_t segs = (768 + A.x_tiles * A.ct_groups - 1) / (A.x_tiles * A.ct_groups);
+        // segments of the row index: enough workgroups for three rounds over the 256 CUs (a workgroup spends about half
+        // its time outside the MFMA loop at cfg2's ten iterations, so fewer, longer segments with idle CUs measured no better)
+        uint32_t segs = (KM_TARGET_WGS + A.x_tiles * A.ct_groups - 1) / (A.x_tiles * A.ct_groups);
         segs = max(1u, min(segs, (n_kb + 7) / 8));
-        uint32_t kbs = ((n_kb + segs - 1) / segs + KM_IT_KB - 1) / KM_IT_KB * KM_IT_KB;
+        uint32_t kbs = ((n_kb + segs - 1) / segs + 2 * KM_IT_KB - 1) / (2 * KM_IT_KB) * (2 * KM_IT_KB);
         kbs = min(kbs, kb_cap);
         segs = (n_kb + kbs - 1) / kbs;
         A.kb_per_seg = kbs;

@@ -103,7 +103,7 @@ def test_worst_case_magnitudes_stay_exact(slz, orc):
 
 
 @pytest.mark.parametrize("batch,kN,n,beta,l", [(1, 64, 10, 4, 3), (13, 128, 33, 3, 5), (8, 256, 255, 2, 8),
-                                               (37, 2048, 742, 3, 5), (3, 32, 300, 5, 2)])
+                                               (37, 2048, 742, 3, 5), (3, 32, 300, 5, 2), (5, 64, 20, 12, 5), (21, 16, 9, 4, 4)])
 def test_keyswitch_matches_oracle(slz, orc, batch, kN, n, beta, l):
     p = tiny(n=n, N=kN, k=1, ks_base_log=beta, ks_level=l)
     ksk = synth.raw_words(p, "raw_ksk", kN * l * (n + 1)).reshape(kN, l, n + 1)
