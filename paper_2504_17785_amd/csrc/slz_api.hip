@@ -64,6 +64,7 @@ extern "C" int slz_ctx_destroy(slz_ctx *ctx) {
     slz_fused_destroy(ctx);
     slz_bign_destroy(ctx);
     slz_ksm_destroy(ctx);
+    slz_lcm_destroy(ctx);
     slz_free_tables(ctx);
     if (ctx->acc) (void)hipFree(ctx->acc);
     if (ctx->dig) (void)hipFree(ctx->dig);

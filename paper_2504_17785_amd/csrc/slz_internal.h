@@ -57,6 +57,8 @@ struct slz_ctx {
     double *xhat;             // [max_batch][2][(k+1)l][N]
     double *outhat;           // [max_batch][2][k+1][N]
     void *ks_dig;             // digit bytes of the matrix-core keyswitch (allocated at its first call)
+    void *lc_dig;             // weight digit planes of the matrix-core linear combination (grown on demand)
+    size_t lc_dig_bytes;
     uint32_t fwd_reduce_mask; // bit s: fully reduce all values before forward stage s (0-based)
     uint32_t inv_reduce_mask; // same for the inverse stages
     double fwd_out_bound;     // bound (in units of p) of forward outputs
@@ -95,6 +97,10 @@ int slz_keyswitch_launch(slz_ctx *ctx, const uint64_t *lwe_in, const uint64_t *k
 int slz_ksm_supported(const slz_params *p);
 void slz_ksm_destroy(slz_ctx *ctx);
 int slz_ksm_launch(slz_ctx *ctx, const uint64_t *lwe_in, const uint64_t *ksk, uint64_t *lwe_out, uint32_t batch,
+                   hipStream_t s);
+// matrix-core linear combination (slz_lincomb_mfma.hip)
+void slz_lcm_destroy(slz_ctx *ctx);
+int slz_lcm_launch(slz_ctx *ctx, const uint64_t *cts, const int32_t *w, uint64_t *out, uint32_t G, uint32_t J, uint32_t O,
                    hipStream_t s);
 int slz_lincomb_launch(slz_ctx *ctx, const uint64_t *cts, const int32_t *w, uint64_t *out, uint32_t G, uint32_t J,
                        uint32_t O, hipStream_t s);

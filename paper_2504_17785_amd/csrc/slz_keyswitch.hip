@@ -148,6 +148,10 @@ k_lincomb(const uint64_t *__restrict__ cts, const int32_t *__restrict__ w, uint6
 int slz_lincomb_launch(slz_ctx *ctx, const uint64_t *cts, const int32_t *w, uint64_t *out, uint32_t G, uint32_t J, uint32_t O,
                        hipStream_t s) {
     const uint32_t width = ctx->prm.n + 1;
+    if (!ctx->force_generic) {      // int8 MFMA contraction; shapes it does not take fall through to the scalar kernel
+        int rc = slz_lcm_launch(ctx, cts, w, out, G, J, O, s);
+        if (rc != SLZ_E_UNSUPPORTED) return rc;
+    }
     hipLaunchKernelGGL(k_lincomb, dim3((width + KS_THREADS - 1) / KS_THREADS, (O + LC_OT - 1) / LC_OT, G), dim3(KS_THREADS), 0, s,
                        cts, w, out, J, O, width);
     SLZ_HIP(hipGetLastError());

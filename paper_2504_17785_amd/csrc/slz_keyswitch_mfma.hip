@@ -11,9 +11,7 @@
 // words at one level (kN must be a multiple of 32).
 #include "slz_internal.h"
 #include "slz_modarith.h"
-
-typedef int v16i __attribute__((ext_vector_type(16)));
-typedef int v4i __attribute__((ext_vector_type(4)));
+#include "slz_mfma_i8.h"
 
 #define KM_WAVES 8                      // waves per workgroup = 32-ciphertext tiles per workgroup
 #define KM_THREADS (64 * KM_WAVES)
@@ -75,18 +73,6 @@ struct ksm_args {
     uint32_t per_xcd;
 };
 
-// 4x4 byte transpose of four dwords: o[p] = byte p of a0, a1, a2, a3 (a0 in the low byte)
-__device__ __forceinline__ void ksm_tr4(uint32_t a0, uint32_t a1, uint32_t a2, uint32_t a3, uint32_t o[4]) {
-    uint32_t t01l = __builtin_amdgcn_perm(a1, a0, 0x05010400u);   // a0.b0 a1.b0 a0.b1 a1.b1
-    uint32_t t01h = __builtin_amdgcn_perm(a1, a0, 0x07030602u);   // a0.b2 a1.b2 a0.b3 a1.b3
-    uint32_t t23l = __builtin_amdgcn_perm(a3, a2, 0x05010400u);
-    uint32_t t23h = __builtin_amdgcn_perm(a3, a2, 0x07030602u);
-    o[0] = __builtin_amdgcn_perm(t23l, t01l, 0x05040100u);
-    o[1] = __builtin_amdgcn_perm(t23l, t01l, 0x07060302u);
-    o[2] = __builtin_amdgcn_perm(t23h, t01h, 0x05040100u);
-    o[3] = __builtin_amdgcn_perm(t23h, t01h, 0x07060302u);
-}
-
 __global__ void __launch_bounds__(KM_THREADS) __attribute__((amdgpu_waves_per_eu(2, 2)))
 k_ksm_main(ksm_args A) {
     __shared__ v4i lds[2 * KM_BUF_V4];                              // 64 KiB
@@ -147,24 +133,13 @@ k_ksm_main(ksm_args A) {
     auto body = [&](uint64_t (&kw)[8], bool &ok, v4i (&an)[KM_IT_KB], uint32_t it) {
         // recode to signed bytes, transpose 8 rows x 8 planes, park the plane operands in LDS
         {
-            uint32_t lo[8], hi[8];
+            uint64_t w[8], plane[8];
 #pragma unroll
-            for (int t = 0; t < 8; t++) {
-                uint64_t w = ok ? (kw[t] + 0x8080808080808080ull) ^ 0x8080808080808080ull : 0ull;
-                lo[t] = (uint32_t)w;
-                hi[t] = (uint32_t)(w >> 32);
-            }
-            uint32_t pl0[4], pl1[4], ph0[4], ph1[4];
-            ksm_tr4(lo[0], lo[1], lo[2], lo[3], pl0);               // planes 0..3, rows 0..3
-            ksm_tr4(lo[4], lo[5], lo[6], lo[7], pl1);               // planes 0..3, rows 4..7
-            ksm_tr4(hi[0], hi[1], hi[2], hi[3], ph0);               // planes 4..7, rows 0..3
-            ksm_tr4(hi[4], hi[5], hi[6], hi[7], ph1);
+            for (int t = 0; t < 8; t++) w[t] = ok ? slz_signed_bytes(kw[t]) : 0ull;
+            slz_byte_planes(w, plane);
             uint64_t *dst = reinterpret_cast<uint64_t *>(lds + buf * KM_BUF_V4) + lds_w;
 #pragma unroll
-            for (int p = 0; p < 4; p++) {
-                dst[(size_t)p * 64] = (uint64_t)pl0[p] | ((uint64_t)pl1[p] << 32);
-                dst[(size_t)(p + 4) * 64] = (uint64_t)ph0[p] | ((uint64_t)ph1[p] << 32);
-            }
+            for (int p = 0; p < 8; p++) dst[(size_t)p * 64] = plane[p];
         }
         load_key(kw, ok, it + 2 * KM_IT_KB);
         __syncthreads();

@@ -151,14 +151,40 @@ def test_matrix_core_keyswitch_extreme_bytes_and_digits(slz, orc):
     assert np.array_equal(got, orc.keyswitch_batch(p, cts, ksk))
 
 
-def test_lincomb_matches_oracle(slz, orc):
-    p = tiny(n=42)
-    G, J, O = 5, 37, 19
-    cts = synth.raw_words(p, "raw_ct", G * J * (p.n + 1)).reshape(G, J, p.n + 1)
-    w = (synth.uniform_below(p.seed, "weights", J * O, 27).astype(np.int64) - 13).astype(np.int32).reshape(J, O)
+def _lincomb_weights(p, J, O, kind):
+    raw = synth.words(p.seed, "weights", J * O).view(np.int64)
+    if kind == "small":          # residue-sized, as in the matmul gadget: one byte plane
+        return (raw % 13).astype(np.int32).reshape(J, O)
+    if kind == "int8":           # the whole signed-byte range, edges included
+        w = (raw % 256 - 128).astype(np.int32)
+        edge = np.array([-128, 127, 0, -1], dtype=np.int32)
+        w[:len(edge)] = edge[:len(w)]
+        return w.reshape(J, O)
+    if kind == "int16":          # two or three byte planes
+        return (raw % 65536 - 32768).astype(np.int32).reshape(J, O)
+    w = (raw >> 32).astype(np.int32)                      # full int32 range: five byte planes
+    edge = np.array([-2**31, 2**31 - 1, 0x7f7f7f7f, -0x7f7f7f80, 0x7fffff80, 128, -129, 0x00800000], dtype=np.int64).astype(np.int32)
+    w[:len(edge)] = edge[:len(w)]
+    return w.reshape(J, O)
+
+
+@pytest.mark.parametrize("G,J,O,n,kind", [(5, 37, 19, 42, "small"), (2, 784, 128, 742, "small"), (3, 100, 33, 70, "int8"),
+                                           (2, 65, 130, 31, "int16"), (2, 40, 257, 9, "int32"), (1, 1, 1, 5, "int32"),
+                                           (4, 32, 64, 63, "int32")])
+def test_lincomb_matches_oracle(slz, orc, G, J, O, n, kind):
+    # ragged output tiles, ragged word tiles, ragged row blocks, 2/4/8-wave workgroups, one to five weight byte planes
+    p = tiny(n=n)
+    cts = synth.raw_words(p, "raw_ct", G * J * (n + 1)).reshape(G, J, n + 1)
+    w = _lincomb_weights(p, J, O, kind)
+    want = orc.lwe_lincomb_batch(cts, w)
+    d_cts, d_w = slz.to_device_u64(cts), torch.from_numpy(w).cuda()
     ctx = slz.Context(p, 1)
-    got = slz.to_host_u64(ctx.lwe_lincomb_batch(slz.to_device_u64(cts), torch.from_numpy(w).cuda()))
-    assert np.array_equal(got, orc.lwe_lincomb_batch(cts, w))
+    assert np.array_equal(slz.to_host_u64(ctx.lwe_lincomb_batch(d_cts, d_w)), want)
+    # a second call on the same context with fewer byte planes must not see the first call's plane count
+    w2 = _lincomb_weights(p, J, O, "small")
+    assert np.array_equal(slz.to_host_u64(ctx.lwe_lincomb_batch(d_cts, torch.from_numpy(w2).cuda())), orc.lwe_lincomb_batch(cts, w2))
+    ctx.set_option(slz.SLZ_OPT_FORCE_GENERIC, 1)           # the scalar kernel
+    assert np.array_equal(slz.to_host_u64(ctx.lwe_lincomb_batch(d_cts, d_w)), want)
 
 
 def test_config1_full_pipeline_bit_exact_and_decrypts(slz, orc):
