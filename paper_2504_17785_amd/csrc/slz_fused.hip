@@ -54,8 +54,12 @@ struct fused_args {
 
 #include "slz_wave_ntt.h"
 
+// BETA > 0: gadget base 2^BETA fixed at compile time (constant shifts in the decomposition are worth about 1 % of the
+// kernel); BETA = 0: base taken from the arguments.
+template <int BETA>
 __global__ void __launch_bounds__(FUSED_THREADS) __attribute__((amdgpu_waves_per_eu(2, 2)))
 k_fused_blind_rotate_n2048(fused_args A) {
+    const uint32_t beta = BETA > 0 ? (uint32_t)BETA : A.beta;
     extern __shared__ double lds[];
     const uint32_t lane = threadIdx.x & 63u;
     const uint32_t w = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
@@ -123,8 +127,8 @@ k_fused_blind_rotate_n2048(fused_args A) {
                     const uint32_t neg = neg0 ^ (idx < r ? 1u : 0u);
                     const uint64_t a = Sh[(j >> 10) * (2u * TBUF) + (j & 1023u)];
                     const uint64_t lam = (neg ? (uint64_t)0 - a : a) - acc[e];
-                    uint64_t v = slz_round_top_bits(lam, A.beta);
-                    dg[e] = slz_next_digit(v, A.beta);
+                    uint64_t v = slz_round_top_bits(lam, beta);
+                    dg[e] = slz_next_digit(v, beta);
                     pd[64 * e + lane] = dg[e];
                 }
             }
@@ -278,7 +282,9 @@ int slz_fused_init(slz_ctx *ctx) {
     a = 0.5 + 1e-9;
     for (int s = 5; s < 11; s++) a += slz_mulmod_bound(a);
     if (a > 7.5 || slz_mulmod_bound(a) > 1.95) return SLZ_E_UNSUPPORTED;   // slz_d2i needs |r| < 2 p
-    SLZ_HIP(hipFuncSetAttribute((const void *)k_fused_blind_rotate_n2048, hipFuncAttributeMaxDynamicSharedMemorySize,
+    SLZ_HIP(hipFuncSetAttribute((const void *)k_fused_blind_rotate_n2048<23>, hipFuncAttributeMaxDynamicSharedMemorySize,
+                                4 * TBUF * sizeof(double)));
+    SLZ_HIP(hipFuncSetAttribute((const void *)k_fused_blind_rotate_n2048<0>, hipFuncAttributeMaxDynamicSharedMemorySize,
                                 4 * TBUF * sizeof(double)));
     return SLZ_OK;
 }
@@ -311,7 +317,10 @@ int slz_fused_blind_rotate(slz_ctx *ctx, const uint64_t *lwe_in, const uint64_t 
 #endif
     const uint32_t resident = 2u * 256u;               // two workgroups (68 KiB of LDS each) per compute unit
     const uint32_t grid = batch < resident ? batch : resident;
-    hipLaunchKernelGGL(k_fused_blind_rotate_n2048, dim3(grid), dim3(FUSED_THREADS), 4 * TBUF * sizeof(double), s, A);
+    if (A.beta == 23)       // the base of the N = 2048 parameter sets
+        hipLaunchKernelGGL(k_fused_blind_rotate_n2048<23>, dim3(grid), dim3(FUSED_THREADS), 4 * TBUF * sizeof(double), s, A);
+    else
+        hipLaunchKernelGGL(k_fused_blind_rotate_n2048<0>, dim3(grid), dim3(FUSED_THREADS), 4 * TBUF * sizeof(double), s, A);
     SLZ_HIP(hipGetLastError());
 #ifdef SLZ_PHASE_TIMING
     {
