@@ -154,6 +154,18 @@ def main():
         "roofline": {"bound": "alu", "kernel": "blind rotation (slz_pbs_batch)", "achieved": achieved,
                      "peak": PEAK_ALU_TINSTR, "unit": "Tinstr/s", "frac": achieved / PEAK_ALU_TINSTR, "traffic": traffic},
     }
+    # secondary kernels against their own bounds (whole entry point, helper kernels and launch gaps included)
+    kN = p.k * p.N
+    if p.ks_base_log <= 8 and kN % 32 == 0 and not args.generic:
+        ks_ops = 2.0 * batch * kN * p.ks_level * (p.n + 1) * 8          # int8 multiply-adds over the eight byte planes, x2
+        ks_pops = ks_ops / (ks_ms * 1e-3) / 1e15
+        result["keyswitch_roofline"] = {"bound": "mfma", "dtype": "int8", "achieved": ks_pops, "peak": 5.0, "unit": "POP/s",
+                                        "frac": ks_pops / 5.0}
+    if lin_ms is not None:
+        G, J, O = synth.CFG4_BATCH, synth.CFG4_IN, synth.CFG4_OUT
+        lin_bytes = 3.0 * G * (J + O) * (p.n + 1) * 8             # ciphertext words in, sums out (weights are negligible)
+        result["lincomb_roofline"] = {"bound": "hbm", "achieved": lin_bytes / (lin_ms * 1e-3) / 1e9, "peak": 8000.0,
+                                      "unit": "GB/s", "frac": lin_bytes / (lin_ms * 1e-3) / 8e12}
 
     # ---- CPU baseline: the oracle on a bounded sample of the same inputs (also a parity check) ----
     if not args.no_cpu_baseline:

@@ -1,0 +1,142 @@
+"""CPU oracle of the paper's Matmul^RNS (Algorithm "Matmul^RNS", Sec. "Low-bitwidth Matrix Multiplication").
+
+TEST INFRASTRUCTURE ONLY: imported by tests/ and by bench.py's cpu_baseline leg; the GPU library never imports it.
+
+Two layers, both written from the algorithm's three steps in the paper's order and notation:
+
+* `matmul_rns_clear`: the clear-integer clone (the paper validates its encrypted runs against such a clone,
+  Sec. "Evaluation").  Plain numpy integers.
+* `matmul_rns_encrypted`: the same steps on LWE ciphertexts, every table lookup (`mod`, the product of two encrypted
+  residues, the reduction of a block sum) being one programmable bootstrapping followed by one keyswitch of the CGGI
+  oracle in `tfhe_oracle.c`, and every sum a wrapping integer sum of ciphertext vectors.
+
+Readings of points the paper leaves open (listed again in the design notes):
+  R1  Signed inputs (the set I_8) are encoded in Z_t, t = 2^msg_bits >= 256, as the paper encodes signed values in a ring:
+      non-negative values in the lower half, negative ones in the upper half (v -> v + t).
+  R2  The product of two encrypted residues is a lookup on the packed value 16 x' + w' (both residues are below 16 since the
+      moduli are at most 4 bits wide); the paper names a two-input lookup and gives no packing.
+  R3  In step 3 the loop as printed sums slices of Y; it is read as summing the slices Y*[:, :, i:j, :] of the partial
+      products (the text: sub-sums of at most 15 summands, then summed modulo the base), and `Y <- Y + Y' mod m'` as
+      (Y + Y') mod m': Y + Y' <= 14 + 15 * 14 = 224 still fits 8 bits, so one lookup reduces it.
+"""
+from __future__ import annotations
+
+import math
+
+import numpy as np
+
+from . import keyswitch_batch, lut_encode, pbs_batch
+
+# Table "RNS bases used in Silenzio": number of moduli -> base (4-bit moduli, the most significant one even)
+RNS_BASES = {2: (15, 14), 3: (13, 15, 14), 4: (11, 13, 15, 14), 5: (7, 11, 13, 15, 8), 6: (5, 7, 9, 11, 13, 8)}
+BLOCK = 15      # summands per sub-sum (step 3)
+
+
+def rns_base_bitwidth(base) -> float:
+    """log2 of the number of values the base represents (the table's "Max. Bitwidth" column)."""
+    return math.log2(math.prod(base))
+
+
+def get_rns_base(bits: float):
+    """Smallest base of the table that represents `bits`-bit values (the paper's getRNSBase)."""
+    for k in sorted(RNS_BASES):
+        if rns_base_bitwidth(RNS_BASES[k]) >= bits:
+            return RNS_BASES[k]
+    raise ValueError("no base of the table holds %.2f bits" % bits)
+
+
+def signed_encode(x, M: int) -> np.ndarray:
+    """Signed value -> Z_M, negatives in the upper half."""
+    return np.mod(np.asarray(x, dtype=np.int64), M)
+
+
+def signed_decode(v, M: int) -> np.ndarray:
+    """Z_M -> signed value: the lower half (v <= (M-1)/2) is non-negative, the upper half is v - M."""
+    v = np.asarray(v, dtype=np.int64)
+    return np.where(2 * v <= M - 1, v, v - M)
+
+
+def crt_reconstruct(Y, m) -> np.ndarray:
+    """RNS tensor (k, ...) -> signed integers in the centred range of Z_{M_k}."""
+    m = [int(q) for q in m]
+    M = math.prod(m)
+    acc = np.zeros(np.asarray(Y).shape[1:], dtype=np.int64)
+    for i, q in enumerate(m):
+        Mi = M // q
+        acc = (acc + np.asarray(Y[i], dtype=np.int64) * (Mi * pow(Mi, -1, q) % M)) % M
+    return signed_decode(acc, M)
+
+
+def matmul_rns_clear(X, W, m) -> np.ndarray:
+    """Algorithm "Matmul^RNS" on clear integers.  X: a x b, W: b x c (signed), m: k moduli.  Returns Y: k x a x c residues."""
+    X = np.asarray(X, dtype=np.int64)
+    W = np.asarray(W, dtype=np.int64)
+    m = np.asarray(m, dtype=np.int64)
+    b = X.shape[1]
+    # Step 1: inputs to RNS representation
+    mp = m[:, None, None]
+    Xr = np.mod(X[None, :, :], mp)                                   # k x a x b
+    Wr = np.mod(W[None, :, :], mp)                                   # k x b x c
+    # Step 2: partial products
+    Ys = np.mod(Xr[:, :, :, None] * Wr[:, None, :, :], m[:, None, None, None])   # k x a x b x c
+    # Step 3: block-wise summation
+    n = min(BLOCK, b)
+    Y = np.mod(Ys[:, :, :n, :].sum(axis=2), mp)
+    i = n
+    while i < b:
+        j = min(i + n, b)
+        Yp = Ys[:, :, i:j, :].sum(axis=2)
+        assert int((Y + Yp).max()) < 256                             # the 8-bit bound the block size is chosen for
+        Y = np.mod(Y + Yp, mp)
+        i += n
+    return Y
+
+
+def lookup_tables(p, m):
+    """The three families of lookup tables over Z_t (t = 2^msg_bits >= 256), one table per modulus each:
+    reduce_signed[i][v] = signed(v) mod m_i;  product[i][u] = (u >> 4)(u & 15) mod m_i (u < 256);  reduce[i][v] = v mod m_i."""
+    t = 1 << p.msg_bits
+    if t < 256:
+        raise ValueError("Matmul^RNS needs an 8-bit message space")
+    v = np.arange(t, dtype=np.int64)
+    red_s = np.stack([np.mod(signed_decode(v, t), q) for q in m])
+    prod = np.stack([np.where(v < 256, np.mod((v >> 4) * (v & 15), q), 0) for q in m])
+    red = np.stack([np.mod(v, q) for q in m])
+    return red_s.astype(np.uint64), prod.astype(np.uint64), red.astype(np.uint64)
+
+
+def _lookup(p, cts, tables, idx, bsk, ksk) -> np.ndarray:
+    """One table lookup per ciphertext: programmable bootstrapping with table idx[c], then keyswitch back to the small key."""
+    flat = np.ascontiguousarray(cts.reshape(-1, p.n + 1))
+    big = pbs_batch(p, flat, lut_encode(p, tables), np.ascontiguousarray(idx.reshape(-1).astype(np.uint32)), bsk)
+    return keyswitch_batch(p, big, ksk).reshape(cts.shape)
+
+
+def matmul_rns_encrypted(p, x_cts, w_cts, m, bsk, ksk) -> np.ndarray:
+    """Algorithm "Matmul^RNS" on ciphertexts.  x_cts: a x b x (n+1) encryptions of signed 8-bit values (R1), w_cts: b x c x (n+1).
+    Returns k x a x c x (n+1) encryptions of the residues of X W."""
+    m = [int(q) for q in m]
+    k = len(m)
+    a, b = x_cts.shape[:2]
+    c = w_cts.shape[1]
+    red_s, prod, red = lookup_tables(p, m)
+    kk = np.arange(k, dtype=np.uint32)
+    # Step 1: X' = X mod m', W' = W mod m'
+    Xr = _lookup(p, np.broadcast_to(x_cts[None], (k, a, b, p.n + 1)), red_s, np.broadcast_to(kk[:, None, None], (k, a, b)), bsk, ksk)
+    Wr = _lookup(p, np.broadcast_to(w_cts[None], (k, b, c, p.n + 1)), red_s, np.broadcast_to(kk[:, None, None], (k, b, c)), bsk, ksk)
+    # Step 2: partial products, a lookup on 16 x' + w' (R2)
+    with np.errstate(over="ignore"):
+        packed = Xr[:, :, :, None, :] * np.uint64(16) + Wr[:, None, :, :, :]                     # k x a x b x c x (n+1)
+    Ys = _lookup(p, packed, prod, np.broadcast_to(kk[:, None, None, None], (k, a, b, c)), bsk, ksk)
+    # Step 3: block-wise summation (R3)
+    idx = np.broadcast_to(kk[:, None, None], (k, a, c))
+    n = min(BLOCK, b)
+    with np.errstate(over="ignore"):
+        Y = _lookup(p, Ys[:, :, :n, :, :].sum(axis=2, dtype=np.uint64), red, idx, bsk, ksk)
+        i = n
+        while i < b:
+            j = min(i + n, b)
+            Yp = Ys[:, :, i:j, :, :].sum(axis=2, dtype=np.uint64)
+            Y = _lookup(p, Y + Yp, red, idx, bsk, ksk)
+            i += n
+    return Y
