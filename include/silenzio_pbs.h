@@ -18,7 +18,9 @@
  *   - All device work is enqueued on the hipStream_t passed as `hip_stream` (a void*; NULL is
  *     the default stream) and is asynchronous: outputs are valid once the stream has been
  *     synchronised by the caller.  Inputs must stay alive and unmodified until then.
- *   - Input and output buffers must not overlap.  Device buffers must be 16-byte aligned.
+ *   - Input and output buffers must not overlap.  Keys, tables and prepared keys must be 16-byte aligned;
+ *     ciphertext arrays 8-byte aligned (their rows have an odd number of words, so any sub-batch of a
+ *     ciphertext array is a valid argument).
  *   - A context is bound to the device current at creation and is not thread-safe; separate
  *     contexts are independent.
  *

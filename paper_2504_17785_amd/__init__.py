@@ -16,6 +16,7 @@ _HERE = os.path.dirname(os.path.abspath(__file__))
 LIB_PATH = os.environ.get("SILENZIO_PBS_LIB") or os.path.join(_HERE, "libsilenzio_pbs.so")
 
 SLZ_OPT_FORCE_GENERIC = 1
+SLZ_OK, SLZ_E_INVALID_ARG, SLZ_E_UNSUPPORTED, SLZ_E_HIP, SLZ_E_NOMEM, SLZ_E_TOO_LARGE = 0, -1, -2, -3, -4, -5
 
 
 class SlzParams(ctypes.Structure):
@@ -33,7 +34,7 @@ _lib = None
 
 EXPORTS = ("slz_ctx_create", "slz_ctx_destroy", "slz_ctx_set_option", "slz_lut_encode", "slz_bsk_prepare",
            "slz_pbs_batch", "slz_blind_rotate_batch", "slz_keyswitch_batch", "slz_lwe_lincomb_batch",
-           "slz_pbs_path", "slz_strerror")
+           "slz_pbs_path", "slz_strerror", "slz_matmul_rns_luts", "slz_matmul_rns_workspace", "slz_matmul_rns")
 
 
 def lib():
@@ -60,6 +61,9 @@ def lib():
         L.slz_lwe_lincomb_batch.argtypes = [vp, vp, vp, vp, u32, u32, u32, vp]
         L.slz_pbs_path.argtypes = [vp]
         L.slz_pbs_path.restype = ctypes.c_char_p
+        L.slz_matmul_rns_luts.argtypes = [ctypes.POINTER(SlzParams), ctypes.POINTER(SlzMatmulRnsShape), vp]
+        L.slz_matmul_rns_workspace.argtypes = [vp, ctypes.POINTER(SlzMatmulRnsShape), ctypes.POINTER(sz)]
+        L.slz_matmul_rns.argtypes = [vp, ctypes.POINTER(SlzMatmulRnsShape), vp, vp, vp, vp, vp, vp, vp, sz, vp]
         L.slz_strerror.argtypes = [ctypes.c_int]
         L.slz_strerror.restype = ctypes.c_char_p
         for name in EXPORTS:
@@ -67,6 +71,28 @@ def lib():
                 getattr(L, name).restype = ctypes.c_int
         _lib = L
     return _lib
+
+
+class SlzMatmulRnsShape(ctypes.Structure):
+    """slz_matmul_rns_shape of include/silenzio_gadgets.h."""
+    _fields_ = [("k", ctypes.c_uint32), ("m", ctypes.c_uint32 * 8), ("a", ctypes.c_uint32), ("b", ctypes.c_uint32),
+                ("c", ctypes.c_uint32)]
+
+
+def make_matmul_rns_shape(m, a: int, b: int, c: int) -> SlzMatmulRnsShape:
+    m = [int(q) for q in m]
+    if not 1 <= len(m) <= 8:
+        raise ValueError("1 to 8 moduli")
+    return SlzMatmulRnsShape(len(m), (ctypes.c_uint32 * 8)(*m), a, b, c)
+
+
+def matmul_rns_luts(p, m, a: int, b: int, c: int) -> np.ndarray:
+    """slz_matmul_rns_luts: the 3k lookup polynomials of Matmul^RNS, u64 [3k][N] (host)."""
+    cp = make_params(p)
+    sh = make_matmul_rns_shape(m, a, b, c)
+    out = np.empty((3 * sh.k, p.N), dtype=np.uint64)
+    _check(lib().slz_matmul_rns_luts(ctypes.byref(cp), ctypes.byref(sh), out.ctypes.data), "slz_matmul_rns_luts")
+    return out
 
 
 def make_params(p) -> SlzParams:
@@ -192,6 +218,23 @@ class Context:
             out = torch.empty((batch, self.p.n + 1), dtype=torch.int64, device=lwe_in.device)
         _check(lib().slz_keyswitch_batch(self._h, _dev_u64(lwe_in, "lwe_in"), _dev_u64(ksk, "ksk"), _dev_u64(out, "out"),
                                          batch, _stream()), "slz_keyswitch_batch")
+        return out
+
+    def matmul_rns(self, x_cts, w_cts, m, luts, bsk_prepared, ksk, out=None):
+        """slz_matmul_rns: x_cts [a][b][n+1], w_cts [b][c][n+1] -> [k][a][c][n+1]; allocates the workspace the call needs."""
+        import torch
+        a, b = x_cts.shape[:2]
+        c = w_cts.shape[1]
+        sh = make_matmul_rns_shape(m, a, b, c)
+        need = ctypes.c_size_t(0)
+        _check(lib().slz_matmul_rns_workspace(self._h, ctypes.byref(sh), ctypes.byref(need)), "slz_matmul_rns_workspace")
+        ws = torch.empty(need.value, dtype=torch.uint8, device=x_cts.device)
+        if out is None:
+            out = torch.empty((sh.k, a, c, self.p.n + 1), dtype=torch.int64, device=x_cts.device)
+        _check(lib().slz_matmul_rns(self._h, ctypes.byref(sh), _dev_u64(x_cts, "x_cts"), _dev_u64(w_cts, "w_cts"),
+                                    _dev_u64(luts, "luts"), bsk_prepared.data_ptr(), _dev_u64(ksk, "ksk"),
+                                    _dev_u64(out, "out"), ws.data_ptr(), need.value, _stream()), "slz_matmul_rns")
+        torch.cuda.current_stream().synchronize()     # the workspace is released when this returns
         return out
 
     def lwe_lincomb_batch(self, cts, w, out=None):

@@ -15,6 +15,8 @@ static int check_params(const slz_params *p) {
 }
 
 static bool misaligned(const void *p) { return ((uintptr_t)p & 15u) != 0; }
+// ciphertext arrays: rows are n+1 (or kN+1) words, so only word alignment can hold for every row and every sub-batch
+static bool misaligned8(const void *p) { return ((uintptr_t)p & 7u) != 0; }
 
 extern "C" int slz_ctx_create(const slz_params *params, uint32_t max_batch, slz_ctx **out) {
     if (!out) return SLZ_E_INVALID_ARG;
@@ -143,7 +145,7 @@ static int blind_rotate_common(slz_ctx *ctx, const uint64_t *lwe_in, const uint6
     if (!acc_out && !lwe_out) return SLZ_E_INVALID_ARG;
     if (batch > ctx->max_batch) return SLZ_E_TOO_LARGE;
     if (n_steps > ctx->prm.n) return SLZ_E_INVALID_ARG;
-    if (misaligned(lwe_in) || misaligned(luts) || misaligned(bskp) || misaligned(acc_out) || misaligned(lwe_out) ||
+    if (misaligned8(lwe_in) || misaligned(luts) || misaligned(bskp) || misaligned(acc_out) || misaligned8(lwe_out) ||
         ((uintptr_t)lut_idx & 3u))
         return SLZ_E_INVALID_ARG;
     hipStream_t s = (hipStream_t)hip_stream;
@@ -173,7 +175,7 @@ extern "C" int slz_blind_rotate_batch(slz_ctx *ctx, const uint64_t *lwe_in_dev, 
 extern "C" int slz_keyswitch_batch(slz_ctx *ctx, const uint64_t *lwe_in_dev, const uint64_t *ksk_dev, uint64_t *lwe_out_dev,
                                    uint32_t batch, void *hip_stream) {
     if (!ctx || !lwe_in_dev || !ksk_dev || !lwe_out_dev || batch == 0) return SLZ_E_INVALID_ARG;
-    if (misaligned(lwe_in_dev) || misaligned(ksk_dev) || misaligned(lwe_out_dev)) return SLZ_E_INVALID_ARG;
+    if (misaligned8(lwe_in_dev) || misaligned(ksk_dev) || misaligned8(lwe_out_dev)) return SLZ_E_INVALID_ARG;
     return slz_keyswitch_launch(ctx, lwe_in_dev, ksk_dev, lwe_out_dev, batch, (hipStream_t)hip_stream);
 }
 
@@ -181,7 +183,7 @@ extern "C" int slz_lwe_lincomb_batch(slz_ctx *ctx, const uint64_t *cts_dev, cons
                                      uint32_t J, uint32_t O, void *hip_stream) {
     if (!ctx || !cts_dev || !w_dev || !out_dev || G == 0 || J == 0 || O == 0) return SLZ_E_INVALID_ARG;
     if (G > 65535) return SLZ_E_UNSUPPORTED;
-    if (misaligned(cts_dev) || misaligned(out_dev) || ((uintptr_t)w_dev & 3u)) return SLZ_E_INVALID_ARG;
+    if (misaligned8(cts_dev) || misaligned8(out_dev) || ((uintptr_t)w_dev & 3u)) return SLZ_E_INVALID_ARG;
     return slz_lincomb_launch(ctx, cts_dev, w_dev, out_dev, G, J, O, (hipStream_t)hip_stream);
 }
 

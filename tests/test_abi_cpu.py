@@ -15,9 +15,9 @@ ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
 
 def test_library_loads_and_exports_header_symbols():
     L = slz.lib()
-    header = open(os.path.join(ROOT, "include", "silenzio_pbs.h")).read()
+    header = "".join(open(os.path.join(ROOT, "include", h)).read() for h in sorted(os.listdir(os.path.join(ROOT, "include"))))
     declared = set(re.findall(r"\b(slz_[a-z_0-9]+)\s*\(", header))
-    declared -= {"slz_params", "slz_ctx"}
+    declared -= {"slz_params", "slz_ctx", "slz_matmul_rns_shape"}
     assert {"slz_pbs_batch", "slz_keyswitch_batch", "slz_lut_encode"} <= declared
     for name in sorted(declared):
         assert hasattr(L, name), name
@@ -69,3 +69,18 @@ def test_null_context_calls_are_errors_not_crashes():
     assert L.slz_bsk_prepare(None, None, None, ctypes.byref(need), None) == -1
     out = ctypes.c_void_p()
     assert L.slz_ctx_create(None, 1, ctypes.byref(out)) == -1
+
+
+def test_matmul_rns_luts_match_oracle_tables(orc):
+    from oracle import gadgets
+    p = synth.Params(name="t", n=4, k=1, N=2048, pbs_base_log=23, pbs_level=1, ks_base_log=4, ks_level=8, msg_bits=8,
+                     sigma_lwe=2.0 ** -40, sigma_bsk=2.0 ** -50, batch=1, n_luts=1, seed=1)
+    for m in gadgets.RNS_BASES.values():
+        want = orc.lut_encode(p, np.concatenate(gadgets.lookup_tables(p, m)))
+        assert np.array_equal(slz.matmul_rns_luts(p, m, 2, 3, 4), want)
+    with pytest.raises(slz.SlzError):
+        slz.matmul_rns_luts(p, (17, 3), 1, 1, 1)           # not a 4-bit modulus
+    with pytest.raises(slz.SlzError):
+        slz.matmul_rns_luts(p.with_(msg_bits=4), (7, 8), 1, 1, 1)
+    with pytest.raises(slz.SlzError):
+        slz.matmul_rns_luts(p, (7, 8), 0, 1, 1)

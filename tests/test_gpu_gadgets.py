@@ -1,0 +1,78 @@
+"""GPU parity of the Matmul^RNS gadget: slz_matmul_rns against the oracle's encrypted pipeline, bit for bit, and
+decryption against the clear-integer clone.  Toy (insecure) parameters with an 8-bit message space keep the oracle's
+lookups at 7e7 multiply-adds each; the N = 2048, l = 1 shape runs the fused blind-rotation kernel."""
+import numpy as np
+import pytest
+
+import synth
+from synth import Params
+
+pytestmark = pytest.mark.gpu
+
+torch = pytest.importorskip("torch")
+
+
+@pytest.fixture(scope="module")
+def slz():
+    if not torch.cuda.is_available():
+        pytest.fail("the gpu tests need a GPU: torch.cuda.is_available() is False")
+    import paper_2504_17785_amd as m
+    m.lib()
+    return m
+
+
+@pytest.fixture(scope="module")
+def toy(orc):
+    p = Params(name="gadget_toy", n=4, k=1, N=2048, pbs_base_log=23, pbs_level=1, ks_base_log=4, ks_level=8, msg_bits=8,
+               sigma_lwe=2.0 ** -40, sigma_bsk=2.0 ** -50, batch=1, n_luts=1, seed=0x6AD6E7)
+    return p, orc.Keys(p, synth)
+
+
+def _inputs(orc, gd, p, keys, a, b, c, offset):
+    X = (synth.uniform_below(p.seed, "lin_inputs", a * b, 256, offset).astype(np.int64) - 128).reshape(a, b)
+    W = (synth.uniform_below(p.seed, "weights", b * c, 256, offset).astype(np.int64) - 128).reshape(b, c)
+    X.flat[0], W.flat[0] = -128, -128
+    X.flat[-1], W.flat[-1] = 127, -1
+    x_cts = orc.encrypt_messages(p, synth, keys.lwe_sk, gd.signed_encode(X, 256).reshape(-1).astype(np.uint64), offset=offset)
+    w_cts = orc.encrypt_messages(p, synth, keys.lwe_sk, gd.signed_encode(W, 256).reshape(-1).astype(np.uint64), offset=offset + a * b)
+    return X, W, x_cts.reshape(a, b, p.n + 1), w_cts.reshape(b, c, p.n + 1)
+
+
+@pytest.mark.parametrize("a,b,c,m,max_batch", [(2, 3, 2, (15, 14), 64), (2, 17, 1, (13, 15, 14), 512), (1, 31, 2, (7, 11, 13, 15, 8), 37),
+                                                (3, 1, 1, (5, 7, 9, 11, 13, 8), 1)])
+def test_matmul_rns_matches_oracle_and_decrypts(slz, orc, toy, a, b, c, m, max_batch):
+    from oracle import gadgets as gd
+    p, keys = toy
+    X, W, x_cts, w_cts = _inputs(orc, gd, p, keys, a, b, c, offset=1000 * a + b)
+    ctx = slz.Context(p, max_batch)                       # lookups larger than max_batch go through in chunks
+    assert ctx.path == "fused_n2048"
+    d_bsk = ctx.bsk_prepare(slz.to_device_u64(keys.bsk))
+    d_luts = slz.to_device_u64(slz.matmul_rns_luts(p, m, a, b, c))
+    got = slz.to_host_u64(ctx.matmul_rns(slz.to_device_u64(x_cts), slz.to_device_u64(w_cts), m, d_luts, d_bsk, slz.to_device_u64(keys.ksk)))
+    want = gd.matmul_rns_encrypted(p, x_cts, w_cts, m, keys.bsk, keys.ksk)
+    assert np.array_equal(got, want)
+    dec, err = orc.decode(orc.lwe_phase(keys.lwe_sk, got.reshape(-1, p.n + 1)), p.msg_bits)
+    clear = gd.matmul_rns_clear(X, W, m)
+    assert np.array_equal(dec.reshape(clear.shape).astype(np.int64), clear)
+    for i, q in enumerate(m):
+        assert np.array_equal(clear[i], np.mod(X @ W, q))
+
+
+def test_matmul_rns_error_codes(slz, toy):
+    import ctypes
+    p, keys = toy
+    ctx = slz.Context(p, 8)
+    L = slz.lib()
+    sh = slz.make_matmul_rns_shape((15, 14), 2, 2, 2)
+    need = ctypes.c_size_t(0)
+    assert L.slz_matmul_rns_workspace(ctx._h, ctypes.byref(sh), ctypes.byref(need)) == 0 and need.value > 0
+    buf = torch.zeros(need.value + 4096, dtype=torch.uint8, device="cuda")
+    ptr = buf.data_ptr()
+    args = lambda ws, nbytes: (ctx._h, ctypes.byref(sh), ptr, ptr, ptr, ptr, ptr, ptr, ws, nbytes, None)
+    assert L.slz_matmul_rns(*args(ptr, need.value - 1)) == slz.SLZ_E_INVALID_ARG        # workspace too small
+    assert L.slz_matmul_rns(*args(ptr + 8, need.value)) == slz.SLZ_E_INVALID_ARG        # workspace not 256-byte aligned
+    assert L.slz_matmul_rns(*args(None, need.value)) == slz.SLZ_E_INVALID_ARG
+    bad = slz.make_matmul_rns_shape((15, 33), 2, 2, 2)
+    assert L.slz_matmul_rns_workspace(ctx._h, ctypes.byref(bad), ctypes.byref(need)) == slz.SLZ_E_INVALID_ARG
+    ctx4 = slz.Context(p.with_(msg_bits=4), 8)
+    assert L.slz_matmul_rns_workspace(ctx4._h, ctypes.byref(sh), ctypes.byref(need)) == slz.SLZ_E_INVALID_ARG
