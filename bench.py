@@ -35,6 +35,72 @@ def alu_model_ops_per_pbs(p) -> float:
     return float(p.n) * per_cmux
 
 
+def bench_matmul_rns(args):
+    """One step = one Matmul^RNS (the paper's Algorithm "Matmul^RNS") of an encrypted 8 x 28 by an encrypted 28 x 8 matrix
+    (the paper's batch of 8 and the first dense layer of its 28-8-2 network) over the moduli {7, 11, 13}: 7 104 table
+    lookups in three dependent rounds plus the leveled sums.  Key and ciphertext material is uniform random words."""
+    import torch
+    import synth
+    import paper_2504_17785_amd as slz
+
+    if args.gadget_params == "cfg3":
+        p, max_batch = synth.CONFIGS[3], 256
+    else:
+        p = synth.Params(name="gadget_toy", n=4, k=1, N=2048, pbs_base_log=23, pbs_level=1, ks_base_log=4, ks_level=8,
+                         msg_bits=8, sigma_lwe=2.0 ** -40, sigma_bsk=2.0 ** -50, batch=1, n_luts=1, seed=0x6AD6E7)
+        max_batch = 8192
+    a, b, c, m = 8, 28, 8, (7, 11, 13)
+    k = len(m)
+    nblk = (b + 14) // 15
+    lookups = k * (a * b + b * c) + k * a * b * c + k * a * c * nblk
+    torch.cuda.set_device(0)
+    ctx = slz.Context(p, max_batch)
+    R, C = (p.k + 1) * p.pbs_level, p.k + 1
+    bsk = synth.raw_words(p, "raw_bsk", p.n * R * C * p.N).reshape(p.n, p.k + 1, p.pbs_level, C, p.N)
+    ksk = synth.raw_words(p, "raw_ksk", p.k * p.N * p.ks_level * (p.n + 1)).reshape(p.k * p.N, p.ks_level, p.n + 1)
+    x_cts = synth.raw_words(p, "raw_ct", a * b * (p.n + 1)).reshape(a, b, p.n + 1)
+    w_cts = synth.raw_words(p, "raw_ct", b * c * (p.n + 1), a * b * (p.n + 1)).reshape(b, c, p.n + 1)
+    d_std = slz.to_device_u64(bsk)
+    d_bskp = ctx.bsk_prepare(d_std)
+    del d_std
+    d_ksk, d_x, d_w = slz.to_device_u64(ksk), slz.to_device_u64(x_cts), slz.to_device_u64(w_cts)
+    d_luts = slz.to_device_u64(slz.matmul_rns_luts(p, m, a, b, c))
+    d_y = torch.empty((k, a, c, p.n + 1), dtype=torch.int64, device="cuda")
+    for _ in range(args.warmup):
+        ctx.matmul_rns(d_x, d_w, m, d_luts, d_bskp, d_ksk, out=d_y)
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for _ in range(args.steps):
+        ctx.matmul_rns(d_x, d_w, m, d_luts, d_bskp, d_ksk, out=d_y)
+    torch.cuda.synchronize()
+    ms = (time.perf_counter() - t0) * 1e3 / args.steps
+    achieved = lookups * alu_model_ops_per_pbs(p) / (ms * 1e-3) / 1e12
+    result = {
+        "metric": "matmul_rns_lookups_per_s", "value": lookups / (ms * 1e-3), "unit": "PBS+KS/s",
+        "n_gpus": 1, "steps": args.steps, "warmup": args.warmup, "ms_per_step": ms,
+        "higher_is_better": True, "scaling": "weak", "vs_baseline": None, "dtype": "u64", "data": "synthetic",
+        "config": {"workload": "matmul_rns %dx%d by %dx%d over moduli %s at %s: %d lookups in %d dependent rounds" % (
+            a, b, b, c, list(m), p.name, lookups, 2 + nblk), "path": ctx.path},
+        "roofline": {"bound": "alu", "kernel": "blind rotation inside the lookups (whole gadget timed)", "achieved": achieved,
+                     "peak": PEAK_ALU_TINSTR, "unit": "Tinstr/s", "frac": achieved / PEAK_ALU_TINSTR, "traffic": None},
+    }
+    if not args.no_cpu_baseline and args.gadget_params == "toy":
+        # the oracle follows one output entry (row 0 of X, column 0 of W: every step of the algorithm, 1/64 of the work)
+        import oracle
+        from oracle import gadgets
+        t1 = time.perf_counter()
+        want = gadgets.matmul_rns_encrypted(p, x_cts[:1], w_cts[:, :1], m, bsk, ksk)
+        t2 = time.perf_counter()
+        sub = k * (b + b) + k * b + k * nblk
+        got = slz.to_host_u64(d_y)[:, :1, :1]
+        result["cpu_baseline"] = {"value": sub / (t2 - t1), "unit": "PBS+KS/s", "cores": min(oracle.num_threads(), k * b),
+                                  "kind": "oracle", "sample": "output entry (0, 0) of the product: %d of the %d lookups" % (sub, lookups),
+                                  "gpu_bit_exact_on_sample": bool(np.array_equal(got, want))}
+    else:
+        result["cpu_baseline"] = None       # one lookup at the 8-bit parameter set is 9e12 multiply-adds in the oracle
+    print(json.dumps(result))
+
+
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -46,10 +112,16 @@ def main():
     ap.add_argument("--generic", action="store_true", help="force the generic multi-kernel path")
     ap.add_argument("--calib-copy", action="store_true",
                     help="also run one plain device copy of 256 MiB (a known-size kernel to scale FETCH_SIZE/WRITE_SIZE by)")
+    ap.add_argument("--gadget", choices=["matmul_rns"], default=None,
+                    help="time a gadget built on the lookup primitive instead of the PBS + keyswitch step")
+    ap.add_argument("--gadget-params", choices=["cfg3", "toy"], default="cfg3",
+                    help="matmul_rns: the 8-bit parameter set of configuration 3, or the toy set the oracle can follow")
     args = ap.parse_args()
     if args.gpus != 1:
         print("bench.py measures one GPU only (this build has no multi-GPU path); run with --gpus 1", file=sys.stderr)
         sys.exit(2)
+    if args.gadget == "matmul_rns":
+        return bench_matmul_rns(args)
 
     import torch
     import synth
