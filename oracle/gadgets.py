@@ -140,3 +140,118 @@ def matmul_rns_encrypted(p, x_cts, w_cts, m, bsk, ksk) -> np.ndarray:
             Y = _lookup(p, Y + Yp, red, idx, bsk, ksk)
             i += n
     return Y
+
+
+# ---------------------------------------------------------------------------------------------------------------------
+# RNS-to-MRNS conversion (Algorithm "RNS2MRNS") and sign determination (Sec. "Sign Determination in RNS")
+#
+# Readings of points the paper leaves open:
+#   R4  Each update (y_j - y_{i-1}) * (m_{i-1}^-1 mod m_j) of the conversion is one lookup, taken on the difference moved
+#       into the non-negative range by the constant OFFSET = 16 (both operands are below 16): table v -> (v - 16) t mod m_j.
+#   R5  Sign_(n,z,p): the top mixed-radix digit decides the sign (negative iff y_k >= r_k / 2, which needs r_k even); the
+#       zero test is "sum of the mixed-radix digits == 0" as the paper states.  Both flags are combined in one lookup on
+#       sum + 128 [negative] (the digit sum of at most six 4-bit digits stays below 128): 0 -> z, 1..127 -> p, >= 128 -> n.
+OFFSET = 16
+
+
+def rns_encode(x, m) -> np.ndarray:
+    """Signed integers -> residues, shape (k, ...)."""
+    x = np.asarray(x, dtype=np.int64)
+    return np.stack([np.mod(x, int(q)) for q in m])
+
+
+def rns2mrns_clear(x, m) -> np.ndarray:
+    """Algorithm "RNS2MRNS" (Szabo-Tanaka): residues (k, ...) -> mixed-radix digits (k, ...) of the associated base."""
+    m = [int(q) for q in m]
+    k = len(m)
+    y = np.array(x, dtype=np.int64)
+    for i in range(1, k):
+        for j in range(i, k):
+            t = pow(m[i - 1], -1, m[j])
+            y[j] = np.mod((y[j] - y[i - 1]) * t, m[j])
+    return y
+
+
+def mrns_value(y, r) -> np.ndarray:
+    """x = y_1 + sum_{i >= 2} y_i prod_{j < i} r_j."""
+    acc = np.zeros(np.asarray(y).shape[1:], dtype=np.int64)
+    w = 1
+    for i, q in enumerate(r):
+        acc = acc + np.asarray(y[i], dtype=np.int64) * w
+        w *= int(q)
+    return acc
+
+
+def sign_rns_clear(x, m, n: int, z: int, p: int) -> np.ndarray:
+    """Sign_(n,z,p)^RNS on residues (k, ...): n for negative values (upper half of Z_M), z for zero, p for positive ones."""
+    m = [int(q) for q in m]
+    if m[-1] % 2:
+        raise ValueError("the most significant modulus must be even")
+    y = rns2mrns_clear(x, m)
+    neg = y[-1] >= m[-1] // 2
+    digit_sum = y.sum(axis=0)
+    return np.where(neg, n, np.where(digit_sum == 0, z, p)).astype(np.int64)
+
+
+def rns2mrns_tables(p, m):
+    """Lookup tables of the conversion, one per pair i < j in the order (0,1), (0,2), .., (1,2), ..: v -> (v - 16) t_ij mod m_j."""
+    t = 1 << p.msg_bits
+    if t < 256:
+        raise ValueError("the RNS gadgets need an 8-bit message space")
+    v = np.arange(t, dtype=np.int64)
+    m = [int(q) for q in m]
+    tabs = []
+    for i in range(len(m) - 1):
+        for j in range(i + 1, len(m)):
+            tabs.append(np.mod((v - OFFSET) * pow(m[i], -1, m[j]), m[j]))
+    return np.stack(tabs).astype(np.uint64)
+
+
+def pair_index(k: int, i: int, j: int) -> int:
+    """Position of the pair i < j in rns2mrns_tables."""
+    return i * k - i * (i + 1) // 2 + (j - i - 1)
+
+
+def sign_tables(p, m, n: int, z: int, pos: int):
+    """The two extra tables of the sign gadget: top digit -> [digit >= r_k / 2], and sum + 128 [negative] -> n / z / p (signed
+    results encoded in Z_t with negatives in the upper half)."""
+    t = 1 << p.msg_bits
+    v = np.arange(t, dtype=np.int64)
+    top = (v >= int(m[-1]) // 2).astype(np.int64)
+    top[int(m[-1]):] = 0                                            # not reachable: a digit is below its radix
+    sel = np.where(v == 0, z, np.where(v < 128, pos, n))
+    return np.stack([top, signed_encode(sel, t)]).astype(np.uint64)
+
+
+def _add_const(p, cts, c: int) -> np.ndarray:
+    """Adds the clear constant c to every ciphertext (c Delta on the body)."""
+    out = np.array(cts, dtype=np.uint64)
+    with np.errstate(over="ignore"):
+        out[..., -1] += np.uint64((c << (63 - p.msg_bits)) & 0xFFFFFFFFFFFFFFFF)
+    return out
+
+
+def rns2mrns_encrypted(p, x_cts, m, bsk, ksk) -> np.ndarray:
+    """Algorithm "RNS2MRNS" on ciphertexts.  x_cts: k x count x (n+1) encryptions of residues.  Returns the digits, same shape."""
+    m = [int(q) for q in m]
+    k = len(m)
+    tabs = rns2mrns_tables(p, m)
+    y = np.array(x_cts, dtype=np.uint64)
+    count = y.shape[1]
+    for i in range(1, k):
+        with np.errstate(over="ignore"):
+            diff = _add_const(p, y[i:] - y[i - 1][None], OFFSET)                       # (k - i) x count x (n+1)
+        idx = np.repeat(np.array([pair_index(k, i - 1, j) for j in range(i, k)], dtype=np.uint32), count).reshape(k - i, count)
+        y[i:] = _lookup(p, diff, tabs, idx, bsk, ksk)
+    return y
+
+
+def sign_rns_encrypted(p, x_cts, m, n: int, z: int, pos: int, bsk, ksk) -> np.ndarray:
+    """Sign_(n,z,p)^RNS on ciphertexts: k x count x (n+1) -> count x (n+1)."""
+    y = rns2mrns_encrypted(p, x_cts, m, bsk, ksk)
+    st = sign_tables(p, m, n, z, pos)
+    count = y.shape[1]
+    neg = _lookup(p, y[-1], st[:1], np.zeros(count, dtype=np.uint32), bsk, ksk)
+    with np.errstate(over="ignore"):
+        packed = y.sum(axis=0, dtype=np.uint64) + neg * np.uint64(128)
+    return _lookup(p, packed, st[1:], np.zeros(count, dtype=np.uint32), bsk, ksk)

@@ -141,3 +141,75 @@ def test_encrypted_pipeline_decrypts_to_the_clear_clone(orc, gd):
     assert np.array_equal(got.reshape(want.shape).astype(np.int64), want)
     assert np.array_equal(gd.crt_reconstruct(want, m), gd.signed_decode(np.mod(X @ W, 13 * 15 * 14), 13 * 15 * 14))
     assert float(np.abs(err).max()) < 2.0 ** -12           # far from the 2^-10 decision boundary
+
+
+# ---- RNS-to-MRNS conversion and sign determination -------------------------------------------------------------------
+def test_rns2mrns_reproduces_the_printed_example(gd):
+    rows = {r.split("|")[0].strip(): [int(v) for v in r.split("|")[1].split()] for r in _rows("rns_to_mrns_example.txt")}
+    m = rows["moduli"]
+    x = rows["value"][0]
+    assert [x % q for q in m] == rows["rns"]
+    y = gd.rns2mrns_clear(np.array(rows["rns"]).reshape(3, 1), m)
+    assert y[:, 0].tolist() == rows["mrns"]
+    assert int(gd.mrns_value(y, m)[0]) == x == rows["mrns"][0] + rows["mrns"][1] * 5 + rows["mrns"][2] * 35
+    # the printed intermediate rows: subtract the finished digit, multiply by the inverse of its modulus
+    r = rows["rns"]
+    s1 = [r[0], (r[1] - r[0]) % 7, (r[2] - r[0]) % 8]
+    assert s1 == rows["after_subtract_1"]
+    m1 = [s1[0], s1[1] * pow(5, -1, 7) % 7, s1[2] * pow(5, -1, 8) % 8]
+    assert m1 == rows["after_multiply_1"]
+    s2 = [m1[0], m1[1], (m1[2] - m1[1]) % 8]
+    assert s2 == rows["after_subtract_2"]
+    assert [s2[0], s2[1], s2[2] * pow(7, -1, 8) % 8] == rows["after_multiply_2"]
+
+
+def test_rns2mrns_and_sign_exhaustively_over_every_base_of_the_table(gd):
+    for k, m in gd.RNS_BASES.items():
+        M = math.prod(m)
+        x = np.arange(M, dtype=np.int64)
+        res = gd.rns_encode(x, m)
+        y = gd.rns2mrns_clear(res, m)
+        assert all(int(y[i].max()) < m[i] and int(y[i].min()) >= 0 for i in range(k))
+        assert np.array_equal(gd.mrns_value(y, m), x)                       # the digits are the number
+        s = gd.sign_rns_clear(res, m, -1, 0, 1)
+        assert np.array_equal(s, np.sign(gd.signed_decode(x, M)))           # true sign of the signed value
+        assert np.array_equal(gd.sign_rns_clear(res, m, -1, 1, 1), np.where(gd.signed_decode(x, M) < 0, -1, 1))
+
+
+def test_sign_needs_an_even_top_modulus(gd):
+    with pytest.raises(ValueError):
+        gd.sign_rns_clear(np.zeros((2, 1), dtype=np.int64), (14, 15), -1, 0, 1)
+
+
+def test_rns_gadget_tables(gd):
+    p = Params(name="t", n=4, k=1, N=2048, pbs_base_log=23, pbs_level=1, ks_base_log=4, ks_level=8, msg_bits=8,
+               sigma_lwe=2.0 ** -40, sigma_bsk=2.0 ** -50, batch=1, n_luts=1, seed=99)
+    m = (7, 11, 13, 15, 8)
+    tabs = gd.rns2mrns_tables(p, m)
+    assert tabs.shape == (10, 256)
+    for i in range(4):
+        for j in range(i + 1, 5):
+            row = tabs[gd.pair_index(5, i, j)]
+            for a in range(m[j]):
+                for b in range(m[i]):
+                    assert int(row[a - b + gd.OFFSET]) == ((a - b) * pow(m[i], -1, m[j])) % m[j]
+    st = gd.sign_tables(p, m, -1, 0, 1)
+    assert st[0, :8].tolist() == [0, 0, 0, 0, 1, 1, 1, 1]
+    assert int(st[1, 0]) == 0 and int(st[1, 1]) == 1 and int(st[1, 127]) == 1 and int(st[1, 128]) == 255 and int(st[1, 218]) == 255
+
+
+def test_encrypted_rns2mrns_and_sign_decrypt_to_the_clear_clone(orc, gd):
+    p = Params(name="gadget_toy", n=4, k=1, N=2048, pbs_base_log=23, pbs_level=1, ks_base_log=4, ks_level=8, msg_bits=8,
+               sigma_lwe=2.0 ** -40, sigma_bsk=2.0 ** -50, batch=1, n_luts=1, seed=0x6AD6E7)
+    keys = orc.Keys(p, synth)
+    m = (13, 15, 14)
+    M = math.prod(m)
+    vals = np.array([0, 1, -1, 99, -99, M // 2 - 1, -(M // 2), 7, -1364, 1363, 2, -2], dtype=np.int64)
+    res = gd.rns_encode(vals, m)                                            # 3 x 12
+    cts = orc.encrypt_messages(p, synth, keys.lwe_sk, res.reshape(-1).astype(np.uint64)).reshape(3, len(vals), p.n + 1)
+    y = gd.rns2mrns_encrypted(p, cts, m, keys.bsk, keys.ksk)
+    got, _ = orc.decode(orc.lwe_phase(keys.lwe_sk, y.reshape(-1, p.n + 1)), p.msg_bits)
+    assert np.array_equal(got.reshape(3, -1).astype(np.int64), gd.rns2mrns_clear(res, m))
+    s = gd.sign_rns_encrypted(p, cts, m, -1, 0, 1, keys.bsk, keys.ksk)
+    got, _ = orc.decode(orc.lwe_phase(keys.lwe_sk, s), p.msg_bits)
+    assert np.array_equal(gd.signed_decode(got.astype(np.int64), 256), np.sign(vals))
