@@ -49,6 +49,43 @@ int slz_matmul_rns(slz_ctx *ctx, const slz_matmul_rns_shape *shape, const uint64
                    const uint64_t *luts_dev, const void *bsk_prepared_dev, const uint64_t *ksk_dev, uint64_t *y_dev,
                    void *workspace_dev, size_t workspace_bytes, void *hip_stream);
 
+/* ---- RNS-to-MRNS conversion (the paper's Algorithm "RNS2MRNS") and sign determination (Sec. "Sign Determination in
+ * RNS") on encrypted residues ---------------------------------------------------------------------------------------
+ * A number x of Z_M, M = m_1 .. m_k, is given as k ciphertexts of its residues x_i = x mod m_i (all in the context's
+ * message space, msg_bits >= 8).  The conversion returns the digits y_i of the associated mixed-radix system
+ * (x = y_1 + y_2 m_1 + y_3 m_1 m_2 + ..): for i = 2..k, every later digit j >= i is replaced by
+ * (y_j - y_{i-1}) (m_{i-1}^-1 mod m_j) mod m_j, one lookup per (i, j) on the difference moved up by the constant 16;
+ * k - 1 dependent rounds, k (k - 1) / 2 lookups per number.
+ * Sign_(n,z,p): n for negative x (upper half of Z_M; the top modulus must be even), z for zero, p for positive x.  After
+ * the conversion: one lookup on the top digit (y_k >= m_k / 2), then one on (sum of the digits) + 128 [negative]. */
+typedef struct {
+    uint32_t k;                          /* number of moduli, 2..SLZ_MATMUL_RNS_MAX_K */
+    uint32_t m[SLZ_MATMUL_RNS_MAX_K];    /* pairwise coprime moduli in [2, 16] */
+    uint32_t count;                      /* numbers converted per call */
+} slz_rns_shape;
+
+/* Host, pure.  luts_out [k (k-1) / 2 + 2][N] host words: the conversion tables in the order (1,2), (1,3), .., (2,3), ..
+ * (table v -> (v - 16) (m_i^-1 mod m_j) mod m_j), then the top-digit table and the final table of the sign gadget for
+ * the results neg, zero, pos (each in [-128, 127], encoded with negatives in the upper half of the message space).
+ * SLZ_E_INVALID_ARG for a bad shape (moduli not coprime included) or msg_bits < 8. */
+int slz_rns_luts(const slz_params *params, const slz_rns_shape *shape, int32_t neg, int32_t zero, int32_t pos,
+                 uint64_t *luts_out);
+
+/* Bytes of device workspace slz_rns2mrns / slz_sign_rns need for this shape on this context. */
+int slz_rns_workspace(const slz_ctx *ctx, const slz_rns_shape *shape, size_t *bytes);
+
+/* x_dev [k][count][n+1] residues -> y_dev [k][count][n+1] mixed-radix digits.  luts_dev: the polynomials of slz_rns_luts
+ * on the device.  Workspace and error conventions as for slz_matmul_rns. */
+int slz_rns2mrns(slz_ctx *ctx, const slz_rns_shape *shape, const uint64_t *x_dev, const uint64_t *luts_dev,
+                 const void *bsk_prepared_dev, const uint64_t *ksk_dev, uint64_t *y_dev, void *workspace_dev,
+                 size_t workspace_bytes, void *hip_stream);
+
+/* x_dev [k][count][n+1] residues -> s_dev [count][n+1] encryptions of neg / zero / pos (the values given to slz_rns_luts).
+ * SLZ_E_INVALID_ARG also when the top modulus is odd. */
+int slz_sign_rns(slz_ctx *ctx, const slz_rns_shape *shape, const uint64_t *x_dev, const uint64_t *luts_dev,
+                 const void *bsk_prepared_dev, const uint64_t *ksk_dev, uint64_t *s_dev, void *workspace_dev,
+                 size_t workspace_bytes, void *hip_stream);
+
 #ifdef __cplusplus
 }
 #endif

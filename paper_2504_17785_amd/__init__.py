@@ -34,7 +34,8 @@ _lib = None
 
 EXPORTS = ("slz_ctx_create", "slz_ctx_destroy", "slz_ctx_set_option", "slz_lut_encode", "slz_bsk_prepare",
            "slz_pbs_batch", "slz_blind_rotate_batch", "slz_keyswitch_batch", "slz_lwe_lincomb_batch",
-           "slz_pbs_path", "slz_strerror", "slz_matmul_rns_luts", "slz_matmul_rns_workspace", "slz_matmul_rns")
+           "slz_pbs_path", "slz_strerror", "slz_matmul_rns_luts", "slz_matmul_rns_workspace", "slz_matmul_rns",
+           "slz_rns_luts", "slz_rns_workspace", "slz_rns2mrns", "slz_sign_rns")
 
 
 def lib():
@@ -64,6 +65,11 @@ def lib():
         L.slz_matmul_rns_luts.argtypes = [ctypes.POINTER(SlzParams), ctypes.POINTER(SlzMatmulRnsShape), vp]
         L.slz_matmul_rns_workspace.argtypes = [vp, ctypes.POINTER(SlzMatmulRnsShape), ctypes.POINTER(sz)]
         L.slz_matmul_rns.argtypes = [vp, ctypes.POINTER(SlzMatmulRnsShape), vp, vp, vp, vp, vp, vp, vp, sz, vp]
+        i32 = ctypes.c_int32
+        L.slz_rns_luts.argtypes = [ctypes.POINTER(SlzParams), ctypes.POINTER(SlzRnsShape), i32, i32, i32, vp]
+        L.slz_rns_workspace.argtypes = [vp, ctypes.POINTER(SlzRnsShape), ctypes.POINTER(sz)]
+        L.slz_rns2mrns.argtypes = [vp, ctypes.POINTER(SlzRnsShape), vp, vp, vp, vp, vp, vp, sz, vp]
+        L.slz_sign_rns.argtypes = [vp, ctypes.POINTER(SlzRnsShape), vp, vp, vp, vp, vp, vp, sz, vp]
         L.slz_strerror.argtypes = [ctypes.c_int]
         L.slz_strerror.restype = ctypes.c_char_p
         for name in EXPORTS:
@@ -92,6 +98,27 @@ def matmul_rns_luts(p, m, a: int, b: int, c: int) -> np.ndarray:
     sh = make_matmul_rns_shape(m, a, b, c)
     out = np.empty((3 * sh.k, p.N), dtype=np.uint64)
     _check(lib().slz_matmul_rns_luts(ctypes.byref(cp), ctypes.byref(sh), out.ctypes.data), "slz_matmul_rns_luts")
+    return out
+
+
+class SlzRnsShape(ctypes.Structure):
+    """slz_rns_shape of include/silenzio_gadgets.h."""
+    _fields_ = [("k", ctypes.c_uint32), ("m", ctypes.c_uint32 * 8), ("count", ctypes.c_uint32)]
+
+
+def make_rns_shape(m, count: int) -> SlzRnsShape:
+    m = [int(q) for q in m]
+    if not 1 <= len(m) <= 8:
+        raise ValueError("1 to 8 moduli")
+    return SlzRnsShape(len(m), (ctypes.c_uint32 * 8)(*m), count)
+
+
+def rns_luts(p, m, neg: int = -1, zero: int = 0, pos: int = 1) -> np.ndarray:
+    """slz_rns_luts: conversion tables of RNS2MRNS plus the two tables of Sign_(neg,zero,pos), u64 [k(k-1)/2 + 2][N] (host)."""
+    cp = make_params(p)
+    sh = make_rns_shape(m, 1)
+    out = np.empty((sh.k * (sh.k - 1) // 2 + 2, p.N), dtype=np.uint64)
+    _check(lib().slz_rns_luts(ctypes.byref(cp), ctypes.byref(sh), neg, zero, pos, out.ctypes.data), "slz_rns_luts")
     return out
 
 
@@ -236,6 +263,31 @@ class Context:
                                     _dev_u64(out, "out"), ws.data_ptr(), need.value, _stream()), "slz_matmul_rns")
         torch.cuda.current_stream().synchronize()     # the workspace is released when this returns
         return out
+
+    def _rns_call(self, fn, name, x_cts, m, luts, bsk_prepared, ksk, out):
+        import torch
+        sh = make_rns_shape(m, x_cts.shape[1])
+        need = ctypes.c_size_t(0)
+        _check(lib().slz_rns_workspace(self._h, ctypes.byref(sh), ctypes.byref(need)), "slz_rns_workspace")
+        ws = torch.empty(need.value, dtype=torch.uint8, device=x_cts.device)
+        _check(fn(self._h, ctypes.byref(sh), _dev_u64(x_cts, "x_cts"), _dev_u64(luts, "luts"), bsk_prepared.data_ptr(),
+                  _dev_u64(ksk, "ksk"), _dev_u64(out, "out"), ws.data_ptr(), need.value, _stream()), name)
+        torch.cuda.current_stream().synchronize()     # the workspace is released when this returns
+        return out
+
+    def rns2mrns(self, x_cts, m, luts, bsk_prepared, ksk, out=None):
+        """slz_rns2mrns: residues [k][count][n+1] -> mixed-radix digits [k][count][n+1]."""
+        import torch
+        if out is None:
+            out = torch.empty_like(x_cts)
+        return self._rns_call(lib().slz_rns2mrns, "slz_rns2mrns", x_cts, m, luts, bsk_prepared, ksk, out)
+
+    def sign_rns(self, x_cts, m, luts, bsk_prepared, ksk, out=None):
+        """slz_sign_rns: residues [k][count][n+1] -> [count][n+1] encryptions of the neg / zero / pos values of the tables."""
+        import torch
+        if out is None:
+            out = torch.empty((x_cts.shape[1], self.p.n + 1), dtype=torch.int64, device=x_cts.device)
+        return self._rns_call(lib().slz_sign_rns, "slz_sign_rns", x_cts, m, luts, bsk_prepared, ksk, out)
 
     def lwe_lincomb_batch(self, cts, w, out=None):
         import torch

@@ -76,3 +76,47 @@ def test_matmul_rns_error_codes(slz, toy):
     assert L.slz_matmul_rns_workspace(ctx._h, ctypes.byref(bad), ctypes.byref(need)) == slz.SLZ_E_INVALID_ARG
     ctx4 = slz.Context(p.with_(msg_bits=4), 8)
     assert L.slz_matmul_rns_workspace(ctx4._h, ctypes.byref(sh), ctypes.byref(need)) == slz.SLZ_E_INVALID_ARG
+
+
+@pytest.mark.parametrize("m,max_batch", [((5, 7, 8), 64), ((13, 15, 14), 7), ((7, 11, 13, 15, 8), 256), ((15, 14), 1)])
+def test_rns2mrns_and_sign_match_oracle_and_decrypt(slz, orc, toy, m, max_batch):
+    import math
+    from oracle import gadgets as gd
+    p, keys = toy
+    M = math.prod(m)
+    vals = np.array([0, 1, -1, 99 % (M // 2), -(99 % (M // 2)), (M - 1) // 2, -(M // 2), 2, -2, 7, -7], dtype=np.int64)
+    res = gd.rns_encode(vals, m)
+    cts = orc.encrypt_messages(p, synth, keys.lwe_sk, res.reshape(-1).astype(np.uint64), offset=5000).reshape(len(m), len(vals), p.n + 1)
+    ctx = slz.Context(p, max_batch)
+    d_bsk = ctx.bsk_prepare(slz.to_device_u64(keys.bsk))
+    d_ksk = slz.to_device_u64(keys.ksk)
+    d_cts = slz.to_device_u64(cts)
+    nzp = (-1, 0, 1)
+    d_luts = slz.to_device_u64(slz.rns_luts(p, m, *nzp))
+    # conversion: bit for bit against the oracle pipeline, and the digits are the number
+    y = slz.to_host_u64(ctx.rns2mrns(d_cts, m, d_luts, d_bsk, d_ksk))
+    assert np.array_equal(y, gd.rns2mrns_encrypted(p, cts, m, keys.bsk, keys.ksk))
+    dec, _ = orc.decode(orc.lwe_phase(keys.lwe_sk, y.reshape(-1, p.n + 1)), p.msg_bits)
+    digits = dec.reshape(len(m), -1).astype(np.int64)
+    assert np.array_equal(digits, gd.rns2mrns_clear(res, m))
+    assert np.array_equal(gd.mrns_value(digits, m), np.mod(vals, M))
+    if m[-1] % 2 == 0:
+        s = slz.to_host_u64(ctx.sign_rns(d_cts, m, d_luts, d_bsk, d_ksk))
+        assert np.array_equal(s, gd.sign_rns_encrypted(p, cts, m, *nzp, keys.bsk, keys.ksk))
+        dec, _ = orc.decode(orc.lwe_phase(keys.lwe_sk, s), p.msg_bits)
+        assert np.array_equal(gd.signed_decode(dec.astype(np.int64), 256), np.sign(vals))
+
+
+def test_sign_rns_rejects_an_odd_top_modulus(slz, toy):
+    import ctypes
+    p, keys = toy
+    ctx = slz.Context(p, 8)
+    L = slz.lib()
+    sh = slz.make_rns_shape((14, 15), 4)
+    need = ctypes.c_size_t(0)
+    assert L.slz_rns_workspace(ctx._h, ctypes.byref(sh), ctypes.byref(need)) == 0
+    buf = torch.zeros(need.value, dtype=torch.uint8, device="cuda")
+    ptr = buf.data_ptr()
+    assert L.slz_sign_rns(ctx._h, ctypes.byref(sh), ptr, ptr, ptr, ptr, ptr, ptr, need.value, None) == slz.SLZ_E_INVALID_ARG
+    bad = slz.make_rns_shape((6, 15), 4)
+    assert L.slz_rns_workspace(ctx._h, ctypes.byref(bad), ctypes.byref(need)) == slz.SLZ_E_INVALID_ARG
