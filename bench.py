@@ -101,6 +101,70 @@ def bench_matmul_rns(args):
     print(json.dumps(result))
 
 
+def bench_sign_rns(args):
+    """One step = Sign_(-1,0,1)^RNS (RNS-to-MRNS conversion, top-digit lookup, final lookup) of --batch numbers (default 64:
+    the 8 x 8 outputs of the product above) given as residues modulo {13, 15, 14}: 5 lookups per number in 4 dependent
+    rounds.  Key and ciphertext material is uniform random words."""
+    import torch
+    import synth
+    import paper_2504_17785_amd as slz
+
+    if args.gadget_params == "cfg3":
+        p, max_batch = synth.CONFIGS[3], 256
+    else:
+        p = synth.Params(name="gadget_toy", n=4, k=1, N=2048, pbs_base_log=23, pbs_level=1, ks_base_log=4, ks_level=8,
+                         msg_bits=8, sigma_lwe=2.0 ** -40, sigma_bsk=2.0 ** -50, batch=1, n_luts=1, seed=0x6AD6E7)
+        max_batch = 8192
+    m = (13, 15, 14)
+    k = len(m)
+    count = args.batch or 64
+    lookups = count * (k * (k - 1) // 2 + 2)
+    torch.cuda.set_device(0)
+    ctx = slz.Context(p, max_batch)
+    R, C = (p.k + 1) * p.pbs_level, p.k + 1
+    bsk = synth.raw_words(p, "raw_bsk", p.n * R * C * p.N).reshape(p.n, p.k + 1, p.pbs_level, C, p.N)
+    ksk = synth.raw_words(p, "raw_ksk", p.k * p.N * p.ks_level * (p.n + 1)).reshape(p.k * p.N, p.ks_level, p.n + 1)
+    x_cts = synth.raw_words(p, "raw_ct", k * count * (p.n + 1)).reshape(k, count, p.n + 1)
+    d_std = slz.to_device_u64(bsk)
+    d_bskp = ctx.bsk_prepare(d_std)
+    del d_std
+    d_ksk, d_x = slz.to_device_u64(ksk), slz.to_device_u64(x_cts)
+    d_luts = slz.to_device_u64(slz.rns_luts(p, m, -1, 0, 1))
+    d_s = torch.empty((count, p.n + 1), dtype=torch.int64, device="cuda")
+    for _ in range(args.warmup):
+        ctx.sign_rns(d_x, m, d_luts, d_bskp, d_ksk, out=d_s)
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for _ in range(args.steps):
+        ctx.sign_rns(d_x, m, d_luts, d_bskp, d_ksk, out=d_s)
+    torch.cuda.synchronize()
+    ms = (time.perf_counter() - t0) * 1e3 / args.steps
+    achieved = lookups * alu_model_ops_per_pbs(p) / (ms * 1e-3) / 1e12
+    result = {
+        "metric": "sign_rns_lookups_per_s", "value": lookups / (ms * 1e-3), "unit": "PBS+KS/s",
+        "n_gpus": 1, "steps": args.steps, "warmup": args.warmup, "ms_per_step": ms,
+        "higher_is_better": True, "scaling": "weak", "vs_baseline": None, "dtype": "u64", "data": "synthetic",
+        "config": {"workload": "sign_rns of %d numbers over moduli %s at %s: %d lookups in %d dependent rounds" % (
+            count, list(m), p.name, lookups, k + 1), "path": ctx.path},
+        "roofline": {"bound": "alu", "kernel": "blind rotation inside the lookups (whole gadget timed)", "achieved": achieved,
+                     "peak": PEAK_ALU_TINSTR, "unit": "Tinstr/s", "frac": achieved / PEAK_ALU_TINSTR, "traffic": None},
+    }
+    if not args.no_cpu_baseline and args.gadget_params == "toy":
+        import oracle
+        from oracle import gadgets
+        sub = min(count, 16)
+        t1 = time.perf_counter()
+        want = gadgets.sign_rns_encrypted(p, x_cts[:, :sub], m, -1, 0, 1, bsk, ksk)
+        t2 = time.perf_counter()
+        result["cpu_baseline"] = {"value": sub * (k * (k - 1) // 2 + 2) / (t2 - t1), "unit": "PBS+KS/s",
+                                  "cores": min(oracle.num_threads(), (k - 1) * sub), "kind": "oracle",
+                                  "sample": "the first %d of the %d numbers" % (sub, count),
+                                  "gpu_bit_exact_on_sample": bool(np.array_equal(slz.to_host_u64(d_s)[:sub], want))}
+    else:
+        result["cpu_baseline"] = None       # one lookup at the 8-bit parameter set is 9e12 multiply-adds in the oracle
+    print(json.dumps(result))
+
+
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -112,7 +176,7 @@ def main():
     ap.add_argument("--generic", action="store_true", help="force the generic multi-kernel path")
     ap.add_argument("--calib-copy", action="store_true",
                     help="also run one plain device copy of 256 MiB (a known-size kernel to scale FETCH_SIZE/WRITE_SIZE by)")
-    ap.add_argument("--gadget", choices=["matmul_rns"], default=None,
+    ap.add_argument("--gadget", choices=["matmul_rns", "sign_rns"], default=None,
                     help="time a gadget built on the lookup primitive instead of the PBS + keyswitch step")
     ap.add_argument("--gadget-params", choices=["cfg3", "toy"], default="cfg3",
                     help="matmul_rns: the 8-bit parameter set of configuration 3, or the toy set the oracle can follow")
@@ -122,6 +186,8 @@ def main():
         sys.exit(2)
     if args.gadget == "matmul_rns":
         return bench_matmul_rns(args)
+    if args.gadget == "sign_rns":
+        return bench_sign_rns(args)
 
     import torch
     import synth
