@@ -255,3 +255,157 @@ def sign_rns_encrypted(p, x_cts, m, n: int, z: int, pos: int, bsk, ksk) -> np.nd
     with np.errstate(over="ignore"):
         packed = y.sum(axis=0, dtype=np.uint64) + neg * np.uint64(128)
     return _lookup(p, packed, st[1:], np.zeros(count, dtype=np.uint32), bsk, ksk)
+
+
+# ---------------------------------------------------------------------------------------------------------------------
+# Shift2MSBs^+ and Shift2MSBs^+- (Algorithms "Shift2MSBs^+" and "Shift2MSBs^+-"): approximate block scaling of an RNS tensor
+# to its gamma most significant bits, viewing the mixed-radix digits as w-bit chunks of a binary number.
+#
+# Readings of points the paper leaves open:
+#   R6  Step 2's lookup ceil(log2(x + 1)) + i w is the 1-indexed position of the digit's highest set bit; a zero digit has no
+#       set bit and contributes 0 (the step's title; the formula as printed would give i w and force a shift for every
+#       input with two or more moduli).
+#   R7  The maximum over the tensor is a binary tree of pairwise maxima, max(a, b) = b + ReLU(a - b), one lookup per pair on
+#       a - b + 32 (positions are at most 6 * 4 = 24); level by level, element 2j with element 2j + 1, an odd last element
+#       passing through.  The paper uses Concrete's max as a black box.
+#   R8  Steps 3 and 4: per digit position one lookup turns maxBit into a shift code (lshift for digitShift >= 0, else
+#       8 + min(rshift, w): a right shift of w or more clears a w-bit digit), and one two-input lookup per digit on
+#       16 code + digit applies it.
+#   R9  Shift2MSBs^+-: the sign is taken as the flag [x < 0] (Sign_(1,0,0)); s X mod m is a two-input lookup on
+#       16 flag + residue, and s Y^+ one on 128 flag + Y^+ (Y^+ < 2^(Gamma-1) <= 128), its result signed in Z_t.
+MAX_OFFSET = 32
+
+
+def bit_position(x) -> np.ndarray:
+    """1-indexed position of the highest set bit, 0 for 0 (= ceil(log2(x + 1)))."""
+    x = np.asarray(x, dtype=np.int64)
+    out = np.zeros_like(x)
+    for b in range(1, 40):
+        out = np.where(x >= (1 << (b - 1)), b, out)
+    return out
+
+
+def shift_code(max_bit, i: int, w: int, gamma: int) -> np.ndarray:
+    """Step 3 for digit position i as one number: lshift if digitShift >= 0, else 8 + min(rshift, w)."""
+    max_bit = np.asarray(max_bit, dtype=np.int64)
+    any_shift = (max_bit > w).astype(np.int64)
+    digit_shift = (gamma - (max_bit - w * i)) * any_shift
+    lshift = np.minimum(np.maximum(digit_shift, 0), gamma - 1)
+    rshift = np.maximum(-digit_shift, 0)
+    return np.where(digit_shift >= 0, lshift, 8 + np.minimum(rshift, w))
+
+
+def apply_shift_code(code, x) -> np.ndarray:
+    code = np.asarray(code, dtype=np.int64)
+    x = np.asarray(x, dtype=np.int64)
+    return np.where(code < 8, x << np.minimum(code, 7), x >> np.maximum(code - 8, 0))
+
+
+def shift2msbs_plus_digits_clear(Xd, w: int, gamma: int):
+    """Steps 2-6 of "Shift2MSBs^+" on mixed-radix digits Xd (k, ...).  Returns Y, shift and (maxBit, lshift, rshift)."""
+    Xd = np.asarray(Xd, dtype=np.int64)
+    k = Xd.shape[0]
+    # Step 2: position of the highest set bit
+    max_bit = 0
+    for i in range(k):
+        u = np.where(Xd[i] > 0, bit_position(Xd[i]) + i * w, 0)
+        max_bit = max(int(u.max()), max_bit)
+    # Step 3: amount of shift per digit
+    any_shift = int(max_bit > w)
+    max_bw = np.array([w * i for i in range(k)], dtype=np.int64)
+    digit_shift = (gamma - (max_bit - max_bw)) * any_shift
+    lshift = np.minimum(np.maximum(digit_shift, 0), gamma - 1)
+    rshift = np.maximum(-digit_shift, 0)
+    # Step 4: shift, Step 5: sum over the digits
+    shp = (k,) + (1,) * (Xd.ndim - 1)
+    Ys = (Xd << lshift.reshape(shp)) >> rshift.reshape(shp)
+    Y = Ys.sum(axis=0)
+    # Step 6
+    return Y, max_bit - gamma, (max_bit, lshift, rshift)
+
+
+def shift2msbs_plus_clear(X, m, w: int, gamma: int):
+    """"Shift2MSBs^+" on residues X (k, ...) of non-negative numbers."""
+    Y, shift, _ = shift2msbs_plus_digits_clear(rns2mrns_clear(X, m), w, gamma)
+    return Y, shift
+
+
+def shift2msbs_pm_clear(X, m, w: int, Gamma: int):
+    """"Shift2MSBs^+-" on residues X (k, ...) of signed numbers (negatives in the upper half of Z_M)."""
+    m = [int(q) for q in m]
+    s = sign_rns_clear(X, m, -1, 1, 1)
+    Xp = np.stack([np.mod(s * np.asarray(X[i], dtype=np.int64), q) for i, q in enumerate(m)])
+    Yp, shift = shift2msbs_plus_clear(Xp, m, w, Gamma - 1)
+    return s * Yp, shift
+
+
+def shift_tables(p, m, w: int, gamma: int):
+    """Tables of Shift2MSBs^+ over Z_t: [0, k) digit -> bit position + i w (R6); [k] a - b + 32 -> ReLU(a - b) (R7);
+    [k+1, 2k+1) maxBit -> shift code of digit i (R8); [2k+1] 16 code + digit -> shifted digit (R8)."""
+    t = 1 << p.msg_bits
+    if t < 256:
+        raise ValueError("the RNS gadgets need an 8-bit message space")
+    k = len(m)
+    v = np.arange(t, dtype=np.int64)
+    pos = [np.where((v > 0) & (v < 16), bit_position(v) + i * w, 0) for i in range(k)]
+    relu = [np.maximum(v - MAX_OFFSET, 0) * (v < 2 * MAX_OFFSET)]
+    code = [np.where(v <= k * w, shift_code(v, i, w, gamma), 0) for i in range(k)]
+    app = [np.where(v < 256, apply_shift_code(v >> 4, v & 15) % t, 0)]
+    return np.stack(pos + relu + code + app).astype(np.uint64)
+
+
+def pm_tables(p, m):
+    """Extra tables of Shift2MSBs^+-: [0, k) 16 flag + residue -> |x| mod m_i; [k] 128 flag + y -> s y, signed in Z_t (R9)."""
+    t = 1 << p.msg_bits
+    v = np.arange(t, dtype=np.int64)
+    ab = [np.where(v < 16, v % int(q), np.where(v < 32, (-(v - 16)) % int(q), 0)) for q in m]
+    sg = [np.where(v < 128, v, signed_encode(-(v - 128), t))]
+    return np.stack(ab + sg).astype(np.uint64)
+
+
+def _max_tree(p, vals, relu_table, bsk, ksk) -> np.ndarray:
+    """Maximum of the ciphertexts vals (n, n+1 words) by levels of pairwise maxima (R7).  Returns one ciphertext."""
+    cur = np.array(vals, dtype=np.uint64)
+    while cur.shape[0] > 1:
+        h = cur.shape[0] // 2
+        a, b = cur[0:2 * h:2], cur[1:2 * h:2]
+        with np.errstate(over="ignore"):
+            d = _lookup(p, _add_const(p, a - b, MAX_OFFSET), relu_table, np.zeros(h, dtype=np.uint32), bsk, ksk)
+            nxt = b + d
+        cur = np.concatenate([nxt, cur[2 * h:]]) if cur.shape[0] % 2 else nxt
+    return cur[0]
+
+
+def shift2msbs_plus_encrypted(p, x_cts, m, w: int, gamma: int, bsk, ksk):
+    """"Shift2MSBs^+" on ciphertexts: residues k x count x (n+1) -> (Y: count x (n+1), shift: (n+1,), signed in Z_t)."""
+    m = [int(q) for q in m]
+    k = len(m)
+    st = shift_tables(p, m, w, gamma)
+    y = rns2mrns_encrypted(p, x_cts, m, bsk, ksk)                                   # Step 1
+    count = y.shape[1]
+    idx = np.repeat(np.arange(k, dtype=np.uint32), count).reshape(k, count)
+    u = _lookup(p, y, st[:k], idx, bsk, ksk)                                        # Step 2
+    max_bit = _max_tree(p, u.reshape(k * count, p.n + 1), st[k:k + 1], bsk, ksk)
+    codes = _lookup(p, np.broadcast_to(max_bit, (k, p.n + 1)), st[k + 1:2 * k + 1], np.arange(k, dtype=np.uint32), bsk, ksk)   # Step 3
+    with np.errstate(over="ignore"):
+        packed = codes[:, None, :] * np.uint64(16) + y                              # Step 4
+        ys = _lookup(p, packed, st[2 * k + 1:], np.zeros((k, count), dtype=np.uint32), bsk, ksk)
+        Y = ys.sum(axis=0, dtype=np.uint64)                                         # Step 5
+    shift = _add_const(p, max_bit, -gamma)                                          # Step 6
+    return Y, shift
+
+
+def shift2msbs_pm_encrypted(p, x_cts, m, w: int, Gamma: int, bsk, ksk):
+    """"Shift2MSBs^+-" on ciphertexts: residues k x count x (n+1) of signed numbers -> (Y signed in Z_t, shift)."""
+    m = [int(q) for q in m]
+    k = len(m)
+    count = x_cts.shape[1]
+    flag = sign_rns_encrypted(p, x_cts, m, 1, 0, 0, bsk, ksk)                       # [x < 0]
+    pt = pm_tables(p, m)
+    idx = np.repeat(np.arange(k, dtype=np.uint32), count).reshape(k, count)
+    with np.errstate(over="ignore"):
+        xp = _lookup(p, flag[None] * np.uint64(16) + x_cts, pt[:k], idx, bsk, ksk)  # |x| in RNS
+    Yp, shift = shift2msbs_plus_encrypted(p, xp, m, w, Gamma - 1, bsk, ksk)
+    with np.errstate(over="ignore"):
+        Y = _lookup(p, flag * np.uint64(128) + Yp, pt[k:], np.zeros(count, dtype=np.uint32), bsk, ksk)
+    return Y, shift

@@ -213,3 +213,89 @@ def test_encrypted_rns2mrns_and_sign_decrypt_to_the_clear_clone(orc, gd):
     s = gd.sign_rns_encrypted(p, cts, m, -1, 0, 1, keys.bsk, keys.ksk)
     got, _ = orc.decode(orc.lwe_phase(keys.lwe_sk, s), p.msg_bits)
     assert np.array_equal(gd.signed_decode(got.astype(np.int64), 256), np.sign(vals))
+
+
+# ---- Shift2MSBs ---------------------------------------------------------------------------------------------------------
+def test_shift2msbs_plus_reproduces_the_printed_example(gd):
+    rows = {r.split("|")[0].strip(): [int(v) for v in r.split("|")[1].split()] for r in _rows("shift2msbs_example.txt")}
+    Xd = np.array([rows["digits_0"], rows["digits_1"], rows["digits_2"]]).T.reshape(3, 1, 3)      # k x a x b
+    Y, shift, (max_bit, lshift, rshift) = gd.shift2msbs_plus_digits_clear(Xd, rows["w"][0], rows["gamma"][0])
+    assert max_bit == rows["max_bit"][0]
+    assert lshift.tolist() == rows["lshift"] and rshift.tolist() == rows["rshift"]
+    assert Y.reshape(-1).tolist() == rows["y"] and shift == rows["shift"][0]
+    # the same through the single-number shift code the encrypted pipeline uses
+    for i in range(3):
+        code = gd.shift_code(max_bit, i, 4, 5)
+        assert np.array_equal(gd.apply_shift_code(code, Xd[i]), (Xd[i] << lshift[i]) >> rshift[i])
+
+
+def test_shift2msbs_properties(gd):
+    m, w = (13, 15, 14), 4
+    M = math.prod(m)
+    for gamma in (5, 7):
+        x = synth.uniform_below(11 + gamma, "misc", 64, M // 2).astype(np.int64)
+        Y, shift = gd.shift2msbs_plus_clear(gd.rns_encode(x, m), m, w, gamma)
+        assert int(Y.max()) < (1 << gamma) and int(Y.min()) >= 0
+        d = gd.rns2mrns_clear(gd.rns_encode(x, m), m)
+        top = max(int(np.where(d[i] > 0, gd.bit_position(d[i]) + 4 * i, 0).max()) for i in range(3))
+        assert shift == top - gamma
+        # the largest element keeps its leading bit at position gamma
+        assert int(Y.max()) >= (1 << (gamma - 1))
+    # small inputs (highest bit within the first digit) are not shifted at all
+    x = np.array([0, 1, 5, 12], dtype=np.int64)
+    Y, shift = gd.shift2msbs_plus_clear(gd.rns_encode(x, m), m, w, 7)
+    assert Y.tolist() == x.tolist() and shift == 4 - 7
+    # signed variant: odd symmetry, and the sign of every non-zero output
+    x = np.concatenate([synth.uniform_below(5, "misc", 40, M // 2).astype(np.int64), [0, 1, -1, M // 2 - 1, -(M // 2)]])
+    Yp, s1 = gd.shift2msbs_pm_clear(gd.rns_encode(x, m), m, w, 8)
+    Yn, s2 = gd.shift2msbs_pm_clear(gd.rns_encode(-x[:-1], m), m, w, 8)
+    assert np.array_equal(Yp[:-1], -Yn) and int(np.abs(Yp).max()) < 128
+    assert np.all(np.sign(Yp[Yp != 0]) == np.sign(x[Yp != 0]))
+
+
+def test_shift_tables(gd):
+    p = Params(name="t", n=4, k=1, N=2048, pbs_base_log=23, pbs_level=1, ks_base_log=4, ks_level=8, msg_bits=8,
+               sigma_lwe=2.0 ** -40, sigma_bsk=2.0 ** -50, batch=1, n_luts=1, seed=99)
+    m, w, gamma = (13, 15, 14), 4, 5
+    st = gd.shift_tables(p, m, w, gamma)
+    assert st.shape == (2 * 3 + 2, 256)
+    assert st[0, :16].tolist() == [0, 1, 2, 2, 3, 3, 3, 3, 4, 4, 4, 4, 4, 4, 4, 4]
+    assert st[2, :16].tolist() == [0] + [v + 8 for v in [1, 2, 2, 3, 3, 3, 3, 4, 4, 4, 4, 4, 4, 4, 4]]
+    for a in range(25):
+        for b in range(25):
+            assert int(st[3, a - b + gd.MAX_OFFSET]) == max(a - b, 0)
+    # codes at the printed example's maxBit = 10: lshift 3 for the top digit, rshift 1 and 5 (clamped to 4) below
+    assert [int(st[4 + i, 10]) for i in range(3)] == [8 + 4, 8 + 1, 3]
+    assert int(st[7, 16 * 3 + 3]) == 24 and int(st[7, 16 * 9 + 12]) == 6 and int(st[7, 16 * 12 + 6]) == 0
+    pt = gd.pm_tables(p, m)
+    for i, q in enumerate(m):
+        assert [int(pt[i, 16 + x]) for x in range(q)] == [(-x) % q for x in range(q)]
+        assert [int(pt[i, x]) for x in range(q)] == list(range(q))
+    assert int(pt[3, 5]) == 5 and int(pt[3, 128 + 5]) == 251 and int(pt[3, 128]) == 0
+
+
+def test_encrypted_shift2msbs_decrypts_to_the_clear_clone(orc, gd):
+    p = Params(name="gadget_toy", n=4, k=1, N=2048, pbs_base_log=23, pbs_level=1, ks_base_log=4, ks_level=8, msg_bits=8,
+               sigma_lwe=2.0 ** -40, sigma_bsk=2.0 ** -50, batch=1, n_luts=1, seed=0x6AD6E7)
+    keys = orc.Keys(p, synth)
+    m, w = (13, 15, 14), 4
+    # the printed example's three inputs (from their digits) plus two more
+    vals = np.array([0 + 2 * 13 + 3 * 195, 2 + 12 * 13 + 1 * 195, 6 + 1 * 13, 1000, 3], dtype=np.int64)
+    res = gd.rns_encode(vals, m)
+    cts = orc.encrypt_messages(p, synth, keys.lwe_sk, res.reshape(-1).astype(np.uint64), offset=777).reshape(3, len(vals), p.n + 1)
+    Y, shift = gd.shift2msbs_plus_encrypted(p, cts, m, w, 5, keys.bsk, keys.ksk)
+    got, _ = orc.decode(orc.lwe_phase(keys.lwe_sk, Y), p.msg_bits)
+    want, want_shift = gd.shift2msbs_plus_clear(res, m, w, 5)
+    assert np.array_equal(got.astype(np.int64), want)
+    sh, _ = orc.decode(orc.lwe_phase(keys.lwe_sk, shift[None]), p.msg_bits)
+    assert int(gd.signed_decode(sh.astype(np.int64), 256)[0]) == want_shift
+    # signed variant
+    svals = np.array([vals[0], -vals[1], vals[2], -1000, 0, -3], dtype=np.int64)
+    sres = gd.rns_encode(svals, m)
+    scts = orc.encrypt_messages(p, synth, keys.lwe_sk, sres.reshape(-1).astype(np.uint64), offset=999).reshape(3, len(svals), p.n + 1)
+    Y, shift = gd.shift2msbs_pm_encrypted(p, scts, m, w, 6, keys.bsk, keys.ksk)
+    got, _ = orc.decode(orc.lwe_phase(keys.lwe_sk, Y), p.msg_bits)
+    want, want_shift = gd.shift2msbs_pm_clear(sres, m, w, 6)
+    assert np.array_equal(gd.signed_decode(got.astype(np.int64), 256), want)
+    sh, _ = orc.decode(orc.lwe_phase(keys.lwe_sk, shift[None]), p.msg_bits)
+    assert int(gd.signed_decode(sh.astype(np.int64), 256)[0]) == want_shift
