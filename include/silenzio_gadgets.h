@@ -86,6 +86,39 @@ int slz_sign_rns(slz_ctx *ctx, const slz_rns_shape *shape, const uint64_t *x_dev
                  const void *bsk_prepared_dev, const uint64_t *ksk_dev, uint64_t *s_dev, void *workspace_dev,
                  size_t workspace_bytes, void *hip_stream);
 
+/* ---- Shift2MSBs^+ and Shift2MSBs^+- (the paper's Algorithms of those names): approximate block scaling ---------------
+ * The whole tensor (count numbers given as encrypted residues) is scaled down so that its largest element keeps its
+ * gamma most significant bits, viewing the mixed-radix digits as w-bit chunks of a binary number:
+ *   1. RNS-to-MRNS conversion;  2. per digit a lookup of the 1-indexed position of its highest set bit (0 for a zero
+ *   digit) + i w, then the maximum over all digits of all numbers (binary tree of max(a, b) = b + ReLU(a - b), one lookup
+ *   per pair and level);  3. per digit position a lookup maxBit -> shift code;  4. per digit a two-input lookup on
+ *   16 code + digit applying the left or right shift;  5. the sum of the shifted digits;  6. shift = maxBit - gamma.
+ * Shift2MSBs^+- handles signed numbers (negatives in the upper half of Z_M; even top modulus): flag [x < 0] by the sign
+ * gadget, |x| per residue by a two-input lookup on 16 flag + residue, Shift2MSBs^+ with gamma, and the sign put back by
+ * a lookup on 128 flag + Y^+.  Outputs: y_dev [count][n+1] (for +-: signed, negatives in the upper half of the message
+ * space) and shift_dev [n+1], one ciphertext of maxBit - gamma (signed the same way). */
+typedef struct {
+    uint32_t k;                          /* number of moduli, 2..6 */
+    uint32_t m[SLZ_MATMUL_RNS_MAX_K];    /* pairwise coprime moduli in [2, 16] */
+    uint32_t count;                      /* numbers in the tensor */
+    uint32_t w;                          /* digit bitwidth; must be 4 */
+    uint32_t gamma;                      /* unsigned output bitwidth, 1..7 (for the signed variant: Gamma - 1) */
+} slz_shift_shape;
+
+/* Host, pure.  luts_out [k (k-1) / 2 + 3k + 5][N]: the tables of slz_rns_luts for (neg, zero, pos) = (1, 0, 0), then k bit-position
+ * tables, the ReLU table of the maximum, k shift-code tables, the shift-application table, k absolute-value tables and
+ * the sign-reapplication table. */
+int slz_shift2msbs_luts(const slz_params *params, const slz_shift_shape *shape, uint64_t *luts_out);
+int slz_shift2msbs_workspace(const slz_ctx *ctx, const slz_shift_shape *shape, size_t *bytes);
+/* x_dev [k][count][n+1] residues of non-negative numbers.  Conventions as for slz_matmul_rns. */
+int slz_shift2msbs_plus(slz_ctx *ctx, const slz_shift_shape *shape, const uint64_t *x_dev, const uint64_t *luts_dev,
+                        const void *bsk_prepared_dev, const uint64_t *ksk_dev, uint64_t *y_dev, uint64_t *shift_dev,
+                        void *workspace_dev, size_t workspace_bytes, void *hip_stream);
+/* x_dev [k][count][n+1] residues of signed numbers.  SLZ_E_INVALID_ARG also when the top modulus is odd. */
+int slz_shift2msbs_pm(slz_ctx *ctx, const slz_shift_shape *shape, const uint64_t *x_dev, const uint64_t *luts_dev,
+                      const void *bsk_prepared_dev, const uint64_t *ksk_dev, uint64_t *y_dev, uint64_t *shift_dev,
+                      void *workspace_dev, size_t workspace_bytes, void *hip_stream);
+
 #ifdef __cplusplus
 }
 #endif

@@ -35,7 +35,8 @@ _lib = None
 EXPORTS = ("slz_ctx_create", "slz_ctx_destroy", "slz_ctx_set_option", "slz_lut_encode", "slz_bsk_prepare",
            "slz_pbs_batch", "slz_blind_rotate_batch", "slz_keyswitch_batch", "slz_lwe_lincomb_batch",
            "slz_pbs_path", "slz_strerror", "slz_matmul_rns_luts", "slz_matmul_rns_workspace", "slz_matmul_rns",
-           "slz_rns_luts", "slz_rns_workspace", "slz_rns2mrns", "slz_sign_rns")
+           "slz_rns_luts", "slz_rns_workspace", "slz_rns2mrns", "slz_sign_rns",
+           "slz_shift2msbs_luts", "slz_shift2msbs_workspace", "slz_shift2msbs_plus", "slz_shift2msbs_pm")
 
 
 def lib():
@@ -70,6 +71,10 @@ def lib():
         L.slz_rns_workspace.argtypes = [vp, ctypes.POINTER(SlzRnsShape), ctypes.POINTER(sz)]
         L.slz_rns2mrns.argtypes = [vp, ctypes.POINTER(SlzRnsShape), vp, vp, vp, vp, vp, vp, sz, vp]
         L.slz_sign_rns.argtypes = [vp, ctypes.POINTER(SlzRnsShape), vp, vp, vp, vp, vp, vp, sz, vp]
+        L.slz_shift2msbs_luts.argtypes = [ctypes.POINTER(SlzParams), ctypes.POINTER(SlzShiftShape), vp]
+        L.slz_shift2msbs_workspace.argtypes = [vp, ctypes.POINTER(SlzShiftShape), ctypes.POINTER(sz)]
+        L.slz_shift2msbs_plus.argtypes = [vp, ctypes.POINTER(SlzShiftShape), vp, vp, vp, vp, vp, vp, vp, sz, vp]
+        L.slz_shift2msbs_pm.argtypes = [vp, ctypes.POINTER(SlzShiftShape), vp, vp, vp, vp, vp, vp, vp, sz, vp]
         L.slz_strerror.argtypes = [ctypes.c_int]
         L.slz_strerror.restype = ctypes.c_char_p
         for name in EXPORTS:
@@ -119,6 +124,28 @@ def rns_luts(p, m, neg: int = -1, zero: int = 0, pos: int = 1) -> np.ndarray:
     sh = make_rns_shape(m, 1)
     out = np.empty((sh.k * (sh.k - 1) // 2 + 2, p.N), dtype=np.uint64)
     _check(lib().slz_rns_luts(ctypes.byref(cp), ctypes.byref(sh), neg, zero, pos, out.ctypes.data), "slz_rns_luts")
+    return out
+
+
+class SlzShiftShape(ctypes.Structure):
+    """slz_shift_shape of include/silenzio_gadgets.h."""
+    _fields_ = [("k", ctypes.c_uint32), ("m", ctypes.c_uint32 * 8), ("count", ctypes.c_uint32), ("w", ctypes.c_uint32),
+                ("gamma", ctypes.c_uint32)]
+
+
+def make_shift_shape(m, count: int, w: int, gamma: int) -> SlzShiftShape:
+    m = [int(q) for q in m]
+    if not 1 <= len(m) <= 8:
+        raise ValueError("1 to 8 moduli")
+    return SlzShiftShape(len(m), (ctypes.c_uint32 * 8)(*m), count, w, gamma)
+
+
+def shift2msbs_luts(p, m, w: int, gamma: int) -> np.ndarray:
+    """slz_shift2msbs_luts: every table of Shift2MSBs^+ / ^+- for unsigned output bitwidth gamma, u64 [k(k-1)/2 + 3k + 5][N] (host)."""
+    cp = make_params(p)
+    sh = make_shift_shape(m, 1, w, gamma)
+    out = np.empty((sh.k * (sh.k - 1) // 2 + 3 * sh.k + 5, p.N), dtype=np.uint64)
+    _check(lib().slz_shift2msbs_luts(ctypes.byref(cp), ctypes.byref(sh), out.ctypes.data), "slz_shift2msbs_luts")
     return out
 
 
@@ -288,6 +315,24 @@ class Context:
         if out is None:
             out = torch.empty((x_cts.shape[1], self.p.n + 1), dtype=torch.int64, device=x_cts.device)
         return self._rns_call(lib().slz_sign_rns, "slz_sign_rns", x_cts, m, luts, bsk_prepared, ksk, out)
+
+    def shift2msbs(self, x_cts, m, w: int, gamma: int, luts, bsk_prepared, ksk, signed: bool = False):
+        """slz_shift2msbs_plus / slz_shift2msbs_pm: residues [k][count][n+1] -> (Y [count][n+1], shift [n+1]); gamma is the
+        unsigned output bitwidth (for signed inputs: Gamma - 1)."""
+        import torch
+        count = x_cts.shape[1]
+        sh = make_shift_shape(m, count, w, gamma)
+        need = ctypes.c_size_t(0)
+        _check(lib().slz_shift2msbs_workspace(self._h, ctypes.byref(sh), ctypes.byref(need)), "slz_shift2msbs_workspace")
+        ws = torch.empty(need.value, dtype=torch.uint8, device=x_cts.device)
+        y = torch.empty((count, self.p.n + 1), dtype=torch.int64, device=x_cts.device)
+        shift = torch.empty((self.p.n + 1,), dtype=torch.int64, device=x_cts.device)
+        fn = lib().slz_shift2msbs_pm if signed else lib().slz_shift2msbs_plus
+        _check(fn(self._h, ctypes.byref(sh), _dev_u64(x_cts, "x_cts"), _dev_u64(luts, "luts"), bsk_prepared.data_ptr(),
+                  _dev_u64(ksk, "ksk"), _dev_u64(y, "y"), _dev_u64(shift, "shift"), ws.data_ptr(), need.value, _stream()),
+               "slz_shift2msbs")
+        torch.cuda.current_stream().synchronize()     # the workspace is released when this returns
+        return y, shift
 
     def lwe_lincomb_batch(self, cts, w, out=None):
         import torch

@@ -215,9 +215,8 @@ static uint32_t inv_mod(uint32_t a, uint32_t q) {
     return 0;       // q == 1 cannot happen (moduli are at least 2)
 }
 
-extern "C" int slz_rns_luts(const slz_params *p, const slz_rns_shape *sh, int32_t neg, int32_t zero, int32_t pos, uint64_t *luts_out) {
-    if (!luts_out || !rns_shape_ok(p, sh)) return SLZ_E_INVALID_ARG;
-    if (neg < -128 || neg > 127 || zero < -128 || zero > 127 || pos < -128 || pos > 127) return SLZ_E_INVALID_ARG;
+// conversion tables and the two sign tables, appended to tab
+static void rns_tables(const slz_params *p, const slz_rns_shape *sh, int32_t neg, int32_t zero, int32_t pos, std::vector<uint64_t> &out) {
     const uint64_t t = 1ull << p->msg_bits;
     const uint32_t k = sh->k, n_conv = k * (k - 1) / 2;
     std::vector<uint64_t> tab((size_t)(n_conv + 2) * t);
@@ -237,7 +236,15 @@ extern "C" int slz_rns_luts(const slz_params *p, const slz_rns_shape *sh, int32_
         const int64_t r = v == 0 ? zero : (v < 128 ? pos : neg);
         sel[v] = (uint64_t)((r + (int64_t)t) % (int64_t)t);
     }
-    return slz_lut_encode(p, tab.data(), n_conv + 2, luts_out);
+    out.insert(out.end(), tab.begin(), tab.end());
+}
+
+extern "C" int slz_rns_luts(const slz_params *p, const slz_rns_shape *sh, int32_t neg, int32_t zero, int32_t pos, uint64_t *luts_out) {
+    if (!luts_out || !rns_shape_ok(p, sh)) return SLZ_E_INVALID_ARG;
+    if (neg < -128 || neg > 127 || zero < -128 || zero > 127 || pos < -128 || pos > 127) return SLZ_E_INVALID_ARG;
+    std::vector<uint64_t> tab;
+    rns_tables(p, sh, neg, zero, pos, tab);
+    return slz_lut_encode(p, tab.data(), sh->k * (sh->k - 1) / 2 + 2, luts_out);
 }
 
 struct rns_plan {
@@ -345,14 +352,10 @@ extern "C" int slz_rns2mrns(slz_ctx *ctx, const slz_rns_shape *sh, const uint64_
     return SLZ_OK;
 }
 
-extern "C" int slz_sign_rns(slz_ctx *ctx, const slz_rns_shape *sh, const uint64_t *x, const uint64_t *luts, const void *bskp,
-                            const uint64_t *ksk, uint64_t *out, void *workspace, size_t workspace_bytes, void *hip_stream) {
-    if (!rns_args_ok(ctx, sh, x, luts, bskp, ksk, out, workspace)) return SLZ_E_INVALID_ARG;
-    if (sh->m[sh->k - 1] % 2) return SLZ_E_INVALID_ARG;
-    const rns_plan P = make_rns_plan(ctx, sh);
-    if (workspace_bytes < P.total) return SLZ_E_INVALID_ARG;
+// sign of count numbers: residues x -> out; uses the plan's y, neg, tmp, big, idx buffers
+static int sign_rns_run(slz_ctx *ctx, const slz_rns_shape *sh, const rns_plan &P, const uint64_t *x, const uint64_t *luts, const void *bskp,
+                        const uint64_t *ksk, uint64_t *out, char *ws, void *hip_stream) {
     hipStream_t s = (hipStream_t)hip_stream;
-    char *ws = (char *)workspace;
     uint64_t *y = (uint64_t *)(ws + P.o_y), *neg = (uint64_t *)(ws + P.o_neg), *tmp = (uint64_t *)(ws + P.o_tmp);
     uint64_t *big = (uint64_t *)(ws + P.o_big);
     const uint32_t k = sh->k, n1 = (uint32_t)P.n1, n_conv = k * (k - 1) / 2;
@@ -365,7 +368,271 @@ extern "C" int slz_sign_rns(slz_ctx *ctx, const slz_rns_shape *sh, const uint64_
                   hip_stream);
     if (rc != SLZ_OK) return rc;
     hipLaunchKernelGGL(k_rns_sign_pack, ew_grid(count * n1), dim3(MR_THREADS), 0, s, y, neg, tmp, k, count, n1);
-    rc = lookup_n(ctx, P.chunk, P.n1, tmp, luts + (size_t)(n_conv + 1) * N, nullptr, 1, bskp, ksk, big, out, count, hip_stream);
+    return lookup_n(ctx, P.chunk, P.n1, tmp, luts + (size_t)(n_conv + 1) * N, nullptr, 1, bskp, ksk, big, out, count, hip_stream);
+}
+
+extern "C" int slz_sign_rns(slz_ctx *ctx, const slz_rns_shape *sh, const uint64_t *x, const uint64_t *luts, const void *bskp,
+                            const uint64_t *ksk, uint64_t *out, void *workspace, size_t workspace_bytes, void *hip_stream) {
+    if (!rns_args_ok(ctx, sh, x, luts, bskp, ksk, out, workspace)) return SLZ_E_INVALID_ARG;
+    if (sh->m[sh->k - 1] % 2) return SLZ_E_INVALID_ARG;
+    const rns_plan P = make_rns_plan(ctx, sh);
+    if (workspace_bytes < P.total) return SLZ_E_INVALID_ARG;
+    int rc = sign_rns_run(ctx, sh, P, x, luts, bskp, ksk, out, (char *)workspace, hip_stream);
+    if (rc != SLZ_OK) return rc;
+    SLZ_HIP(hipGetLastError());
+    return SLZ_OK;
+}
+
+// ---- Shift2MSBs^+ and Shift2MSBs^+- ----------------------------------------------------------------------------------
+#define MAX_OFFSET 32u      // moves a difference of two bit positions (each at most 24) into the non-negative range
+
+static bool shift_shape_ok(const slz_params *p, const slz_shift_shape *sh, slz_rns_shape *rs) {
+    if (!p || !sh) return false;
+    rs->k = sh->k; rs->count = sh->count;
+    for (int i = 0; i < SLZ_MATMUL_RNS_MAX_K; i++) rs->m[i] = sh->m[i];
+    if (!rns_shape_ok(p, rs)) return false;
+    if (sh->w != 4 || sh->gamma < 1 || sh->gamma > 7 || sh->k > 6) return false;      // 4-bit digits; outputs and positions fit the tables
+    return true;
+}
+
+static uint32_t bit_position(uint64_t x) { uint32_t b = 0; while (x) { b++; x >>= 1; } return b; }
+
+static uint64_t shift_code(uint64_t max_bit, uint32_t i, uint32_t w, uint32_t gamma) {
+    const int64_t any_shift = max_bit > w ? 1 : 0;
+    const int64_t digit_shift = ((int64_t)gamma - ((int64_t)max_bit - (int64_t)(w * i))) * any_shift;
+    if (digit_shift >= 0) return (uint64_t)(digit_shift < (int64_t)gamma - 1 ? digit_shift : (int64_t)gamma - 1);
+    const int64_t r = -digit_shift;
+    return 8 + (uint64_t)(r < (int64_t)w ? r : (int64_t)w);
+}
+
+// table counts: conversion + sign (k (k-1) / 2 + 2), shift (2k + 2), signed variant (k + 1)
+static uint32_t shift_n_luts(uint32_t k) { return k * (k - 1) / 2 + 2 + 2 * k + 2 + k + 1; }
+
+extern "C" int slz_shift2msbs_luts(const slz_params *p, const slz_shift_shape *sh, uint64_t *luts_out) {
+    slz_rns_shape rs;
+    if (!luts_out || !shift_shape_ok(p, sh, &rs)) return SLZ_E_INVALID_ARG;
+    const uint64_t t = 1ull << p->msg_bits;
+    const uint32_t k = sh->k, w = sh->w, gamma = sh->gamma;
+    std::vector<uint64_t> tab;
+    rns_tables(p, &rs, 1, 0, 0, tab);                          // the sign as the flag [x < 0]
+    std::vector<uint64_t> row(t);
+    for (uint32_t i = 0; i < k; i++) {                          // digit -> 1-indexed position of its highest set bit (+ i w), 0 for 0
+        for (uint64_t v = 0; v < t; v++) row[v] = (v > 0 && v < 16) ? bit_position(v) + i * w : 0;
+        tab.insert(tab.end(), row.begin(), row.end());
+    }
+    for (uint64_t v = 0; v < t; v++) row[v] = (v < 2 * MAX_OFFSET && v > MAX_OFFSET) ? v - MAX_OFFSET : 0;     // a - b + 32 -> ReLU(a - b)
+    tab.insert(tab.end(), row.begin(), row.end());
+    for (uint32_t i = 0; i < k; i++) {                          // maxBit -> shift code of digit i
+        for (uint64_t v = 0; v < t; v++) row[v] = v <= (uint64_t)k * w ? shift_code(v, i, w, gamma) : 0;
+        tab.insert(tab.end(), row.begin(), row.end());
+    }
+    for (uint64_t v = 0; v < t; v++) {                          // 16 code + digit -> shifted digit
+        uint64_t r = 0;
+        if (v < 256) {
+            const uint64_t code = v >> 4, x = v & 15;
+            r = code < 8 ? x << (code < 7 ? code : 7) : x >> (code - 8);
+        }
+        row[v] = r % t;
+    }
+    tab.insert(tab.end(), row.begin(), row.end());
+    for (uint32_t i = 0; i < k; i++) {                          // 16 flag + residue -> |x| mod m_i
+        const uint64_t q = sh->m[i];
+        for (uint64_t v = 0; v < t; v++) row[v] = v < 16 ? v % q : (v < 32 ? (q - (v - 16) % q) % q : 0);
+        tab.insert(tab.end(), row.begin(), row.end());
+    }
+    for (uint64_t v = 0; v < t; v++) row[v] = v < 128 ? v : (t - (v - 128)) % t;      // 128 flag + y -> s y, signed in Z_t
+    tab.insert(tab.end(), row.begin(), row.end());
+    return slz_lut_encode(p, tab.data(), shift_n_luts(k), luts_out);
+}
+
+struct shift_plan {
+    rns_plan R;             // buffers of the conversion and the sign
+    size_t o_u, o_u2, o_maxbit, o_codes, o_ys, o_xp, o_yp, o_flag, total;
+};
+
+static shift_plan make_shift_plan(const slz_ctx *ctx, const slz_rns_shape *rs) {
+    shift_plan S;
+    S.R = make_rns_plan(ctx, rs);
+    const size_t n1 = S.R.n1, all = S.R.total_cts;
+    size_t o = S.R.total;
+    S.o_u = o;      o += up256(all * n1 * 8);                   // bit positions; levels of the maximum tree alternate u / u2
+    S.o_u2 = o;     o += up256(all * n1 * 8);
+    S.o_maxbit = o; o += up256(n1 * 8);
+    S.o_codes = o;  o += up256((size_t)rs->k * n1 * 8);
+    S.o_ys = o;     o += up256(all * n1 * 8);                   // shifted digits
+    S.o_xp = o;     o += up256(all * n1 * 8);                   // |x| in RNS (signed variant)
+    S.o_yp = o;     o += up256((size_t)rs->count * n1 * 8);     // Y^+ (signed variant)
+    S.o_flag = o;   o += up256((size_t)rs->count * n1 * 8);     // [x < 0] (signed variant)
+    S.total = o;
+    return S;
+}
+
+extern "C" int slz_shift2msbs_workspace(const slz_ctx *ctx, const slz_shift_shape *sh, size_t *bytes) {
+    slz_rns_shape rs;
+    if (!ctx || !bytes || !shift_shape_ok(&ctx->prm, sh, &rs)) return SLZ_E_INVALID_ARG;
+    *bytes = make_shift_plan(ctx, &rs).total;
+    return SLZ_OK;
+}
+
+// idx[i * count + e] = i
+__global__ void k_sh_row_index(uint32_t *idx, uint32_t k, size_t count) {
+    const size_t gid = (size_t)blockIdx.x * blockDim.x + threadIdx.x;
+    if (gid < (size_t)k * count) idx[gid] = (uint32_t)(gid / count);
+}
+
+// tmp[j][.] = cur[2j][.] - cur[2j+1][.] + 32 (on the body), j < h
+__global__ void __launch_bounds__(MR_THREADS)
+k_sh_pair_diff(const uint64_t *__restrict__ cur, uint64_t *__restrict__ tmp, size_t h, uint32_t n1, uint64_t offset_body) {
+    const size_t total = h * n1;
+    for (size_t gid = (size_t)blockIdx.x * MR_THREADS + threadIdx.x; gid < total; gid += (size_t)gridDim.x * MR_THREADS) {
+        const uint32_t word = (uint32_t)(gid % n1);
+        const size_t j = gid / n1;
+        uint64_t v = cur[(2 * j) * n1 + word] - cur[(2 * j + 1) * n1 + word];
+        if (word == n1 - 1) v += offset_body;
+        tmp[gid] = v;
+    }
+}
+
+// nxt[j] = cur[2j+1] + d[j] for j < h; an odd last element of cur passes through as nxt[h]
+__global__ void __launch_bounds__(MR_THREADS)
+k_sh_pair_max(const uint64_t *__restrict__ cur, const uint64_t *__restrict__ d, uint64_t *__restrict__ nxt, size_t h, size_t n_cur, uint32_t n1) {
+    const size_t n_next = h + (n_cur & 1);
+    const size_t total = n_next * n1;
+    for (size_t gid = (size_t)blockIdx.x * MR_THREADS + threadIdx.x; gid < total; gid += (size_t)gridDim.x * MR_THREADS) {
+        const uint32_t word = (uint32_t)(gid % n1);
+        const size_t j = gid / n1;
+        nxt[gid] = j < h ? cur[(2 * j + 1) * n1 + word] + d[gid] : cur[(n_cur - 1) * n1 + word];
+    }
+}
+
+// tmp[i][.] = src[.] for i < k;  idx[i] = i
+__global__ void k_sh_broadcast(const uint64_t *__restrict__ src, uint64_t *__restrict__ tmp, uint32_t *__restrict__ idx, uint32_t k, uint32_t n1) {
+    const uint32_t gid = blockIdx.x * blockDim.x + threadIdx.x;
+    if (gid < k * n1) tmp[gid] = src[gid % n1];
+    if (gid < k) idx[gid] = gid;
+}
+
+// tmp[i][e][.] = mul * a[i or 0][.] (a per row when a_per_row, else per element e) + b[i][e][.]
+// mode 0: a = codes[i] (one ciphertext per row);  mode 1: a = flag[e] (one per element)
+__global__ void __launch_bounds__(MR_THREADS)
+k_sh_pack(const uint64_t *__restrict__ a, const uint64_t *__restrict__ b, uint64_t *__restrict__ tmp, uint32_t k, size_t count, uint32_t n1,
+          uint64_t mul, int mode) {
+    const size_t total = (size_t)k * count * n1;
+    for (size_t gid = (size_t)blockIdx.x * MR_THREADS + threadIdx.x; gid < total; gid += (size_t)gridDim.x * MR_THREADS) {
+        const uint32_t word = (uint32_t)(gid % n1);
+        const size_t ct = gid / n1;
+        const size_t e = ct % count, i = ct / count;
+        const uint64_t av = mode == 0 ? a[i * n1 + word] : a[e * n1 + word];
+        tmp[gid] = mul * av + b[gid];
+    }
+}
+
+// Y[e][.] = sum_i ys[i][e][.];  shift[.] = maxbit[.] - gamma (on the body)
+__global__ void __launch_bounds__(MR_THREADS)
+k_sh_sum(const uint64_t *__restrict__ ys, const uint64_t *__restrict__ maxbit, uint64_t *__restrict__ Y, uint64_t *__restrict__ shift, uint32_t k,
+         size_t count, uint32_t n1, uint64_t gamma_body) {
+    const size_t total = count * n1;
+    for (size_t gid = (size_t)blockIdx.x * MR_THREADS + threadIdx.x; gid < total; gid += (size_t)gridDim.x * MR_THREADS) {
+        uint64_t v = 0;
+        for (uint32_t i = 0; i < k; i++) v += ys[(size_t)i * total + gid];
+        Y[gid] = v;
+        if (gid < n1) shift[gid] = maxbit[gid] - (gid == n1 - 1 ? gamma_body : 0);
+    }
+}
+
+// Shift2MSBs^+ of the residues in x (device, k x count) -> Y, shift
+static int shift_plus_run(slz_ctx *ctx, const slz_shift_shape *sh, const slz_rns_shape *rs, const shift_plan &S, const uint64_t *x,
+                          const uint64_t *luts, const void *bskp, const uint64_t *ksk, uint64_t *Y, uint64_t *shift, char *ws, void *hip_stream) {
+    hipStream_t s = (hipStream_t)hip_stream;
+    const rns_plan &P = S.R;
+    const uint32_t k = rs->k, n1 = (uint32_t)P.n1, n_conv = k * (k - 1) / 2;
+    const size_t count = rs->count, all = P.total_cts, N = ctx->prm.N;
+    uint32_t *idx = (uint32_t *)(ws + P.o_idx);
+    uint64_t *big = (uint64_t *)(ws + P.o_big), *tmp = (uint64_t *)(ws + P.o_tmp), *y = (uint64_t *)(ws + P.o_y);
+    uint64_t *u = (uint64_t *)(ws + S.o_u), *u2 = (uint64_t *)(ws + S.o_u2), *maxbit = (uint64_t *)(ws + S.o_maxbit);
+    uint64_t *codes = (uint64_t *)(ws + S.o_codes), *ys = (uint64_t *)(ws + S.o_ys);
+    const uint64_t *t_pos = luts + (size_t)(n_conv + 2) * N, *t_relu = t_pos + (size_t)k * N, *t_code = t_relu + N, *t_apply = t_code + (size_t)k * N;
+    const uint32_t delta_shift = 63 - ctx->prm.msg_bits;
+    // Step 1: digits
+    SLZ_HIP(hipMemcpyAsync(y, x, all * n1 * 8, hipMemcpyDeviceToDevice, s));
+    int rc = rns2mrns_inplace(ctx, rs, P, y, luts, bskp, ksk, ws, hip_stream);
+    if (rc != SLZ_OK) return rc;
+    // Step 2: position of the highest set bit of every digit, then the maximum over everything
+    hipLaunchKernelGGL(k_sh_row_index, dim3((unsigned)((all + 255) / 256)), dim3(256), 0, s, idx, k, count);
+    rc = lookup_n(ctx, P.chunk, P.n1, y, t_pos, idx, k, bskp, ksk, big, u, all, hip_stream);
+    if (rc != SLZ_OK) return rc;
+    uint64_t *cur = u, *nxt = u2;
+    for (size_t n_cur = all; n_cur > 1;) {
+        const size_t h = n_cur / 2;
+        hipLaunchKernelGGL(k_sh_pair_diff, ew_grid(h * n1), dim3(MR_THREADS), 0, s, cur, tmp, h, n1, (uint64_t)MAX_OFFSET << delta_shift);
+        rc = lookup_n(ctx, P.chunk, P.n1, tmp, t_relu, nullptr, 1, bskp, ksk, big, ys, h, hip_stream);      // ys is free until step 4
+        if (rc != SLZ_OK) return rc;
+        hipLaunchKernelGGL(k_sh_pair_max, ew_grid((h + 1) * n1), dim3(MR_THREADS), 0, s, cur, ys, nxt, h, n_cur, n1);
+        uint64_t *sw = cur; cur = nxt; nxt = sw;
+        n_cur = h + (n_cur & 1);
+    }
+    SLZ_HIP(hipMemcpyAsync(maxbit, cur, (size_t)n1 * 8, hipMemcpyDeviceToDevice, s));
+    // Step 3: shift code per digit position
+    hipLaunchKernelGGL(k_sh_broadcast, dim3((k * n1 + 255) / 256), dim3(256), 0, s, maxbit, tmp, idx, k, n1);
+    rc = lookup_n(ctx, P.chunk, P.n1, tmp, t_code, idx, k, bskp, ksk, big, codes, k, hip_stream);
+    if (rc != SLZ_OK) return rc;
+    // Step 4: apply the shifts
+    hipLaunchKernelGGL(k_sh_pack, ew_grid(all * n1), dim3(MR_THREADS), 0, s, codes, y, tmp, k, count, n1, (uint64_t)16, 0);
+    rc = lookup_n(ctx, P.chunk, P.n1, tmp, t_apply, nullptr, 1, bskp, ksk, big, ys, all, hip_stream);
+    if (rc != SLZ_OK) return rc;
+    // Step 5: sum over the digits, Step 6: shift = maxBit - gamma
+    hipLaunchKernelGGL(k_sh_sum, ew_grid(count * n1 > n1 ? count * n1 : n1), dim3(MR_THREADS), 0, s, ys, maxbit, Y, shift, k, count, n1,
+                       (uint64_t)sh->gamma << delta_shift);
+    return SLZ_OK;
+}
+
+static int shift_args_ok(slz_ctx *ctx, const slz_shift_shape *sh, slz_rns_shape *rs, const void *x, const void *luts, const void *bskp,
+                         const void *ksk, const void *y, const void *shift, const void *ws) {
+    if (!ctx || !x || !luts || !bskp || !ksk || !y || !shift || !ws || !shift_shape_ok(&ctx->prm, sh, rs)) return 0;
+    return !(((uintptr_t)ws & 255u) || ((uintptr_t)x & 7u) || ((uintptr_t)y & 7u) || ((uintptr_t)shift & 7u) || ((uintptr_t)luts & 15u));
+}
+
+extern "C" int slz_shift2msbs_plus(slz_ctx *ctx, const slz_shift_shape *sh, const uint64_t *x, const uint64_t *luts, const void *bskp,
+                                   const uint64_t *ksk, uint64_t *y, uint64_t *shift, void *workspace, size_t workspace_bytes, void *hip_stream) {
+    slz_rns_shape rs;
+    if (!shift_args_ok(ctx, sh, &rs, x, luts, bskp, ksk, y, shift, workspace)) return SLZ_E_INVALID_ARG;
+    const shift_plan S = make_shift_plan(ctx, &rs);
+    if (workspace_bytes < S.total) return SLZ_E_INVALID_ARG;
+    int rc = shift_plus_run(ctx, sh, &rs, S, x, luts, bskp, ksk, y, shift, (char *)workspace, hip_stream);
+    if (rc != SLZ_OK) return rc;
+    SLZ_HIP(hipGetLastError());
+    return SLZ_OK;
+}
+
+extern "C" int slz_shift2msbs_pm(slz_ctx *ctx, const slz_shift_shape *sh, const uint64_t *x, const uint64_t *luts, const void *bskp,
+                                 const uint64_t *ksk, uint64_t *y, uint64_t *shift, void *workspace, size_t workspace_bytes, void *hip_stream) {
+    slz_rns_shape rs;
+    if (!shift_args_ok(ctx, sh, &rs, x, luts, bskp, ksk, y, shift, workspace)) return SLZ_E_INVALID_ARG;
+    if (rs.m[rs.k - 1] % 2) return SLZ_E_INVALID_ARG;
+    const shift_plan S = make_shift_plan(ctx, &rs);
+    if (workspace_bytes < S.total) return SLZ_E_INVALID_ARG;
+    hipStream_t s = (hipStream_t)hip_stream;
+    char *ws = (char *)workspace;
+    const rns_plan &P = S.R;
+    const uint32_t k = rs.k, n1 = (uint32_t)P.n1, n_conv = k * (k - 1) / 2;
+    const size_t count = rs.count, all = P.total_cts, N = ctx->prm.N;
+    uint32_t *idx = (uint32_t *)(ws + P.o_idx);
+    uint64_t *big = (uint64_t *)(ws + P.o_big), *tmp = (uint64_t *)(ws + P.o_tmp);
+    uint64_t *xp = (uint64_t *)(ws + S.o_xp), *yp = (uint64_t *)(ws + S.o_yp), *flag = (uint64_t *)(ws + S.o_flag);
+    const uint64_t *t_abs = luts + (size_t)(n_conv + 2 + 2 * k + 2) * N, *t_sign = t_abs + (size_t)k * N;
+    // s = [x < 0] through the sign gadget
+    int rc = sign_rns_run(ctx, &rs, P, x, luts, bskp, ksk, flag, ws, hip_stream);
+    if (rc != SLZ_OK) return rc;
+    // X^+ = s X mod m: a two-input lookup on 16 flag + residue
+    hipLaunchKernelGGL(k_sh_pack, ew_grid(all * n1), dim3(MR_THREADS), 0, s, flag, x, tmp, k, count, n1, (uint64_t)16, 1);
+    hipLaunchKernelGGL(k_sh_row_index, dim3((unsigned)((all + 255) / 256)), dim3(256), 0, s, idx, k, count);
+    rc = lookup_n(ctx, P.chunk, P.n1, tmp, t_abs, idx, k, bskp, ksk, big, xp, all, hip_stream);
+    if (rc != SLZ_OK) return rc;
+    rc = shift_plus_run(ctx, sh, &rs, S, xp, luts, bskp, ksk, yp, shift, ws, hip_stream);
+    if (rc != SLZ_OK) return rc;
+    // Y = s Y^+: a two-input lookup on 128 flag + Y^+
+    hipLaunchKernelGGL(k_sh_pack, ew_grid(count * n1), dim3(MR_THREADS), 0, s, flag, yp, tmp, 1u, count, n1, (uint64_t)128, 1);
+    rc = lookup_n(ctx, P.chunk, P.n1, tmp, t_sign, nullptr, 1, bskp, ksk, big, y, count, hip_stream);
     if (rc != SLZ_OK) return rc;
     SLZ_HIP(hipGetLastError());
     return SLZ_OK;

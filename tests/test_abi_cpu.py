@@ -17,7 +17,7 @@ def test_library_loads_and_exports_header_symbols():
     L = slz.lib()
     header = "".join(open(os.path.join(ROOT, "include", h)).read() for h in sorted(os.listdir(os.path.join(ROOT, "include"))))
     declared = set(re.findall(r"\b(slz_[a-z_0-9]+)\s*\(", header))
-    declared -= {"slz_params", "slz_ctx", "slz_matmul_rns_shape", "slz_rns_shape"}
+    declared -= {"slz_params", "slz_ctx", "slz_matmul_rns_shape", "slz_rns_shape", "slz_shift_shape"}
     assert {"slz_pbs_batch", "slz_keyswitch_batch", "slz_lut_encode"} <= declared
     for name in sorted(declared):
         assert hasattr(L, name), name
@@ -100,3 +100,18 @@ def test_rns_luts_match_oracle_tables(orc):
         slz.rns_luts(p, (15, 14), 200, 0, 1)               # result out of the signed byte range
     with pytest.raises(slz.SlzError):
         slz.rns_luts(p.with_(msg_bits=5), (15, 14))
+
+
+def test_shift2msbs_luts_match_oracle_tables(orc):
+    from oracle import gadgets
+    p = synth.Params(name="t", n=4, k=1, N=2048, pbs_base_log=23, pbs_level=1, ks_base_log=4, ks_level=8, msg_bits=8,
+                     sigma_lwe=2.0 ** -40, sigma_bsk=2.0 ** -50, batch=1, n_luts=1, seed=1)
+    for m in gadgets.RNS_BASES.values():
+        for gamma in (1, 5, 7):
+            want = orc.lut_encode(p, np.concatenate([gadgets.rns2mrns_tables(p, m), gadgets.sign_tables(p, m, 1, 0, 0),
+                                                     gadgets.shift_tables(p, m, 4, gamma), gadgets.pm_tables(p, m)]))
+            assert np.array_equal(slz.shift2msbs_luts(p, m, 4, gamma), want)
+    with pytest.raises(slz.SlzError):
+        slz.shift2msbs_luts(p, (15, 14), 5, 5)            # only 4-bit digits
+    with pytest.raises(slz.SlzError):
+        slz.shift2msbs_luts(p, (15, 14), 4, 8)            # the output must fit 7 bits

@@ -120,3 +120,39 @@ def test_sign_rns_rejects_an_odd_top_modulus(slz, toy):
     assert L.slz_sign_rns(ctx._h, ctypes.byref(sh), ptr, ptr, ptr, ptr, ptr, ptr, need.value, None) == slz.SLZ_E_INVALID_ARG
     bad = slz.make_rns_shape((6, 15), 4)
     assert L.slz_rns_workspace(ctx._h, ctypes.byref(bad), ctypes.byref(need)) == slz.SLZ_E_INVALID_ARG
+
+
+@pytest.mark.parametrize("m,gamma,max_batch", [((13, 15, 14), 5, 64), ((15, 14), 7, 5), ((7, 11, 13, 15, 8), 6, 256)])
+def test_shift2msbs_matches_oracle_and_decrypts(slz, orc, toy, m, gamma, max_batch):
+    import math
+    from oracle import gadgets as gd
+    p, keys = toy
+    M, w = math.prod(m), 4
+    # non-negative inputs: the printed example's three numbers (reduced into the base's positive range) and edge cases
+    vals = np.array([2 * 13 + 3 * 195, 2 + 12 * 13 + 195, 6 + 13, 1000, 3, 0, (M - 1) // 2], dtype=np.int64) % (M // 2)
+    ctx = slz.Context(p, max_batch)
+    d_bsk = ctx.bsk_prepare(slz.to_device_u64(keys.bsk))
+    d_ksk = slz.to_device_u64(keys.ksk)
+    d_luts = slz.to_device_u64(slz.shift2msbs_luts(p, m, w, gamma))
+
+    def run(values, signed):
+        res = gd.rns_encode(values, m)
+        cts = orc.encrypt_messages(p, synth, keys.lwe_sk, res.reshape(-1).astype(np.uint64), offset=31337).reshape(len(m), len(values), p.n + 1)
+        y, shift = ctx.shift2msbs(slz.to_device_u64(cts), m, w, gamma, d_luts, d_bsk, d_ksk, signed=signed)
+        y, shift = slz.to_host_u64(y), slz.to_host_u64(shift)
+        if signed:
+            want_y, want_shift = gd.shift2msbs_pm_encrypted(p, cts, m, w, gamma + 1, keys.bsk, keys.ksk)
+            clear_y, clear_shift = gd.shift2msbs_pm_clear(res, m, w, gamma + 1)
+        else:
+            want_y, want_shift = gd.shift2msbs_plus_encrypted(p, cts, m, w, gamma, keys.bsk, keys.ksk)
+            clear_y, clear_shift = gd.shift2msbs_plus_clear(res, m, w, gamma)
+        assert np.array_equal(y, want_y) and np.array_equal(shift, want_shift)          # bit for bit
+        dec, _ = orc.decode(orc.lwe_phase(keys.lwe_sk, y), p.msg_bits)
+        assert np.array_equal(gd.signed_decode(dec.astype(np.int64), 256), clear_y)
+        dec, _ = orc.decode(orc.lwe_phase(keys.lwe_sk, shift[None]), p.msg_bits)
+        assert int(gd.signed_decode(dec.astype(np.int64), 256)[0]) == clear_shift
+
+    run(vals, signed=False)
+    if m[-1] % 2 == 0:
+        svals = vals * np.array([1, -1, 1, -1, -1, 1, -1])
+        run(svals, signed=True)
