@@ -118,7 +118,16 @@ def bench_sign_rns(args):
     m = (13, 15, 14)
     k = len(m)
     count = args.batch or 64
-    lookups = count * (k * (k - 1) // 2 + 2)
+    shift = args.gadget == "shift2msbs"      # Shift2MSBs^+- to Gamma = 8 signed bits (gamma = 7, w = 4) instead of the sign alone
+    conv = count * k * (k - 1) // 2
+    if shift:
+        # sign, |x|, then Shift2MSBs^+: conversion, bit positions, maximum tree (one lookup per pair), codes, shifts; sign back
+        lookups = (conv + 2 * count) + k * count + (conv + k * count + (k * count - 1) + k + k * count) + count
+        tree = (k * count - 1).bit_length()
+        rounds = (k - 1 + 2) + 1 + (k - 1 + 1 + tree + 1 + 1) + 1
+    else:
+        lookups = conv + 2 * count
+        rounds = k + 1
     torch.cuda.set_device(0)
     ctx = slz.Context(p, max_batch)
     R, C = (p.k + 1) * p.pbs_level, p.k + 1
@@ -129,37 +138,52 @@ def bench_sign_rns(args):
     d_bskp = ctx.bsk_prepare(d_std)
     del d_std
     d_ksk, d_x = slz.to_device_u64(ksk), slz.to_device_u64(x_cts)
-    d_luts = slz.to_device_u64(slz.rns_luts(p, m, -1, 0, 1))
+    d_luts = slz.to_device_u64(slz.shift2msbs_luts(p, m, 4, 7) if shift else slz.rns_luts(p, m, -1, 0, 1))
     d_s = torch.empty((count, p.n + 1), dtype=torch.int64, device="cuda")
+
+    def run():
+        if shift:
+            return ctx.shift2msbs(d_x, m, 4, 7, d_luts, d_bskp, d_ksk, signed=True)
+        return ctx.sign_rns(d_x, m, d_luts, d_bskp, d_ksk, out=d_s), None
+
     for _ in range(args.warmup):
-        ctx.sign_rns(d_x, m, d_luts, d_bskp, d_ksk, out=d_s)
+        run()
     torch.cuda.synchronize()
     t0 = time.perf_counter()
     for _ in range(args.steps):
-        ctx.sign_rns(d_x, m, d_luts, d_bskp, d_ksk, out=d_s)
+        d_s, d_shift = run()
     torch.cuda.synchronize()
     ms = (time.perf_counter() - t0) * 1e3 / args.steps
     achieved = lookups * alu_model_ops_per_pbs(p) / (ms * 1e-3) / 1e12
     result = {
-        "metric": "sign_rns_lookups_per_s", "value": lookups / (ms * 1e-3), "unit": "PBS+KS/s",
+        "metric": "%s_lookups_per_s" % args.gadget, "value": lookups / (ms * 1e-3), "unit": "PBS+KS/s",
         "n_gpus": 1, "steps": args.steps, "warmup": args.warmup, "ms_per_step": ms,
         "higher_is_better": True, "scaling": "weak", "vs_baseline": None, "dtype": "u64", "data": "synthetic",
-        "config": {"workload": "sign_rns of %d numbers over moduli %s at %s: %d lookups in %d dependent rounds" % (
-            count, list(m), p.name, lookups, k + 1), "path": ctx.path},
+        "config": {"workload": "%s of %d numbers over moduli %s at %s: %d lookups in %d dependent rounds" % (
+            args.gadget, count, list(m), p.name, lookups, rounds), "path": ctx.path},
         "roofline": {"bound": "alu", "kernel": "blind rotation inside the lookups (whole gadget timed)", "achieved": achieved,
                      "peak": PEAK_ALU_TINSTR, "unit": "Tinstr/s", "frac": achieved / PEAK_ALU_TINSTR, "traffic": None},
     }
     if not args.no_cpu_baseline and args.gadget_params == "toy":
         import oracle
         from oracle import gadgets
-        sub = min(count, 16)
-        t1 = time.perf_counter()
-        want = gadgets.sign_rns_encrypted(p, x_cts[:, :sub], m, -1, 0, 1, bsk, ksk)
-        t2 = time.perf_counter()
-        result["cpu_baseline"] = {"value": sub * (k * (k - 1) // 2 + 2) / (t2 - t1), "unit": "PBS+KS/s",
-                                  "cores": min(oracle.num_threads(), (k - 1) * sub), "kind": "oracle",
-                                  "sample": "the first %d of the %d numbers" % (sub, count),
-                                  "gpu_bit_exact_on_sample": bool(np.array_equal(slz.to_host_u64(d_s)[:sub], want))}
+        if shift:       # the maximum couples all numbers: the oracle follows the whole tensor
+            t1 = time.perf_counter()
+            want, want_shift = gadgets.shift2msbs_pm_encrypted(p, x_cts, m, 4, 8, bsk, ksk)
+            t2 = time.perf_counter()
+            result["cpu_baseline"] = {"value": lookups / (t2 - t1), "unit": "PBS+KS/s", "cores": oracle.num_threads(), "kind": "oracle",
+                                      "sample": "the whole tensor of %d numbers" % count,
+                                      "gpu_bit_exact_on_sample": bool(np.array_equal(slz.to_host_u64(d_s), want)
+                                                                      and np.array_equal(slz.to_host_u64(d_shift), want_shift))}
+        else:
+            sub = min(count, 16)
+            t1 = time.perf_counter()
+            want = gadgets.sign_rns_encrypted(p, x_cts[:, :sub], m, -1, 0, 1, bsk, ksk)
+            t2 = time.perf_counter()
+            result["cpu_baseline"] = {"value": sub * (k * (k - 1) // 2 + 2) / (t2 - t1), "unit": "PBS+KS/s",
+                                      "cores": min(oracle.num_threads(), (k - 1) * sub), "kind": "oracle",
+                                      "sample": "the first %d of the %d numbers" % (sub, count),
+                                      "gpu_bit_exact_on_sample": bool(np.array_equal(slz.to_host_u64(d_s)[:sub], want))}
     else:
         result["cpu_baseline"] = None       # one lookup at the 8-bit parameter set is 9e12 multiply-adds in the oracle
     print(json.dumps(result))
@@ -176,7 +200,7 @@ def main():
     ap.add_argument("--generic", action="store_true", help="force the generic multi-kernel path")
     ap.add_argument("--calib-copy", action="store_true",
                     help="also run one plain device copy of 256 MiB (a known-size kernel to scale FETCH_SIZE/WRITE_SIZE by)")
-    ap.add_argument("--gadget", choices=["matmul_rns", "sign_rns"], default=None,
+    ap.add_argument("--gadget", choices=["matmul_rns", "sign_rns", "shift2msbs"], default=None,
                     help="time a gadget built on the lookup primitive instead of the PBS + keyswitch step")
     ap.add_argument("--gadget-params", choices=["cfg3", "toy"], default="cfg3",
                     help="matmul_rns: the 8-bit parameter set of configuration 3, or the toy set the oracle can follow")
@@ -186,7 +210,7 @@ def main():
         sys.exit(2)
     if args.gadget == "matmul_rns":
         return bench_matmul_rns(args)
-    if args.gadget == "sign_rns":
+    if args.gadget in ("sign_rns", "shift2msbs"):
         return bench_sign_rns(args)
 
     import torch
