@@ -24,7 +24,7 @@ PEAK_ALU_TINSTR = 256 * 4 * 16 * 2.4e9 / 1e12      # 256 CUs x 4 SIMD16 x 2.4 GH
 
 
 def alu_model_ops_per_pbs(p) -> float:
-    """Algorithmic VALU lane-instructions of one PBS (the op table is in the design doc):
+    """Algorithmic VALU lane-instructions of one PBS, from this op table:
     8 per butterfly (6 modular multiply + add + sub), 7 per pointwise multiply-accumulate, 3 per inverse
     post-scaling beyond the butterflies' share (6-instruction modular multiply per coefficient), 12 per
     decomposed coefficient (rotate, subtract, round, digit, convert) and 20 per CRT-lifted coefficient."""

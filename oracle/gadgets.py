@@ -10,7 +10,7 @@ Two layers, both written from the algorithm's three steps in the paper's order a
   residues, the reduction of a block sum) being one programmable bootstrapping followed by one keyswitch of the CGGI
   oracle in `tfhe_oracle.c`, and every sum a wrapping integer sum of ciphertext vectors.
 
-Readings of points the paper leaves open (listed again in the design notes):
+Readings of points the paper leaves open:
   R1  Signed inputs (the set I_8) are encoded in Z_t, t = 2^msg_bits >= 256, as the paper encodes signed values in a ring:
       non-negative values in the lower half, negative ones in the upper half (v -> v + t).
   R2  The product of two encrypted residues is a lookup on the packed value 16 x' + w' (both residues are below 16 since the

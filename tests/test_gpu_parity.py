@@ -233,7 +233,10 @@ def test_error_codes(slz):
     x = torch.zeros(64, dtype=torch.int64, device="cuda")
     assert L.slz_pbs_batch(ctx._h, x.data_ptr(), x.data_ptr(), None, 1, x.data_ptr(), x.data_ptr(), 5, None) == -5
     assert L.slz_pbs_batch(ctx._h, x.data_ptr(), x.data_ptr(), None, 1, x.data_ptr(), x.data_ptr(), 0, None) == -1
-    assert L.slz_pbs_batch(ctx._h, x.data_ptr() + 8, x.data_ptr(), None, 1, x.data_ptr(), x.data_ptr(), 1, None) == -1
+    # ciphertext arrays need word alignment (any sub-batch of an array is a valid argument), tables and keys 16 bytes
+    assert L.slz_pbs_batch(ctx._h, x.data_ptr() + 4, x.data_ptr(), None, 1, x.data_ptr(), x.data_ptr(), 1, None) == -1
+    assert L.slz_pbs_batch(ctx._h, x.data_ptr(), x.data_ptr() + 8, None, 1, x.data_ptr(), x.data_ptr(), 1, None) == -1
+    assert L.slz_pbs_batch(ctx._h, x.data_ptr(), x.data_ptr(), None, 1, x.data_ptr() + 8, x.data_ptr(), 1, None) == -1
     assert L.slz_blind_rotate_batch(ctx._h, x.data_ptr(), x.data_ptr(), None, 1, x.data_ptr(), p.n + 1, x.data_ptr(), 1, None) == -1
     need = ctypes.c_size_t(0)
     assert L.slz_bsk_prepare(ctx._h, None, None, ctypes.byref(need), None) == 0
