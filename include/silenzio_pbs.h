@@ -70,6 +70,9 @@ typedef struct slz_ctx slz_ctx;   /* opaque: parameter copy, twiddle tables, scr
 #define SLZ_OPT_FORCE_GENERIC 1   /* value != 0: always use the multi-kernel global-memory blind rotation and the
                                      scalar-ALU keyswitch (the kernels every shape has; for cross-checks) */
 
+#define SLZ_OPT_LARGE_N_BLOCK 2   /* value 1024 or 2048: block size of the row pass of the large-N path (default: 1024
+                                     when N = 1024 G', G' <= 32, else 2048); SLZ_E_INVALID_ARG if this N cannot use it */
+
 /* Creates a context on the current device.  Allocates transform tables and scratch sized for
  * `max_batch` ciphertexts.  Fails with SLZ_E_UNSUPPORTED when the exactness bound
  * 4 * (k+1) * l * N * 2^(beta-1) * 2^63 <= p1 * p2 (the two ~2^50 transform primes) does not hold. */

@@ -16,6 +16,7 @@ _HERE = os.path.dirname(os.path.abspath(__file__))
 LIB_PATH = os.environ.get("SILENZIO_PBS_LIB") or os.path.join(_HERE, "libsilenzio_pbs.so")
 
 SLZ_OPT_FORCE_GENERIC = 1
+SLZ_OPT_LARGE_N_BLOCK = 2
 SLZ_OK, SLZ_E_INVALID_ARG, SLZ_E_UNSUPPORTED, SLZ_E_HIP, SLZ_E_NOMEM, SLZ_E_TOO_LARGE = 0, -1, -2, -3, -4, -5
 
 

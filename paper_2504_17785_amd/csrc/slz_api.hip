@@ -79,6 +79,12 @@ extern "C" int slz_ctx_destroy(slz_ctx *ctx) {
 extern "C" int slz_ctx_set_option(slz_ctx *ctx, int option, int value) {
     if (!ctx) return SLZ_E_INVALID_ARG;
     if (option == SLZ_OPT_FORCE_GENERIC) { ctx->force_generic = value != 0; return SLZ_OK; }
+    if (option == SLZ_OPT_LARGE_N_BLOCK) {
+        if (!ctx->has_bign) return SLZ_E_INVALID_ARG;
+        if (value == 1024 && ctx->has_bign16) { ctx->bign_block = 1024; return SLZ_OK; }
+        if (value == 2048 && ctx->bign_rowA) { ctx->bign_block = 2048; return SLZ_OK; }
+        return SLZ_E_INVALID_ARG;
+    }
     return SLZ_E_INVALID_ARG;
 }
 

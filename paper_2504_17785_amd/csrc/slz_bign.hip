@@ -37,20 +37,21 @@ struct bign_args {
 };
 
 // ---- P1 ------------------------------------------------------------------------------------------
-template <int G>
+// BS: block size of the row pass (2048 or 1024); G = N / BS rows of BS columns
+template <int G, int BS>
 __global__ void __launch_bounds__(256)
 k_big_cols_fwd(bign_args A) {
-    const uint32_t c = blockIdx.x * 256 + threadIdx.x;          // column, < 2048
+    const uint32_t c = blockIdx.x * 256 + threadIdx.x;          // column, < BS
     const uint32_t comp = blockIdx.y, b = blockIdx.z;
     const uint32_t N = A.N, R = 2 * A.l;
-    uint32_t logN2 = 12;                                         // log2(2N) = 12 + log2 G
-    for (uint32_t g = G; g > 1; g >>= 1) logN2++;
+    uint32_t logN2 = 1;                                          // log2(2N)
+    for (uint32_t g = N; g > 1; g >>= 1) logN2++;
     const uint32_t at = slz_modswitch(A.lwe_in[(size_t)b * (A.n + 1) + A.step], logN2);
     const uint64_t *poly = A.acc + ((size_t)b * 2 + comp) * N;
     uint64_t lam[G];
 #pragma unroll
     for (int i = 0; i < G; i++) {
-        const uint32_t idx = 2048u * i + c;
+        const uint32_t idx = (uint32_t)BS * i + c;
         lam[i] = slz_rot_coeff([&](uint32_t j) { return poly[j]; }, idx, at, N) - poly[idx];
         lam[i] = slz_round_top_bits(lam[i], A.beta * A.l);
     }
@@ -64,7 +65,7 @@ k_big_cols_fwd(bign_args A) {
             double y[G];
 #pragma unroll
             for (int i = 0; i < G; i++) y[i] = d[i];
-            // stages with strides N/2 .. 2048: pairs of rows, twiddle by block of rows (uniform)
+            // stages with strides N/2 .. BS: pairs of rows, twiddle by block of rows (uniform)
 #pragma unroll
             for (int half = G / 2, blocks = 1; half >= 1; half >>= 1, blocks <<= 1) {
 #pragma unroll
@@ -76,7 +77,7 @@ k_big_cols_fwd(bign_args A) {
             }
             double *dst = A.X + (((size_t)b * 2 + q) * R + (comp * A.l + lev)) * N + c;
 #pragma unroll
-            for (int i = 0; i < G; i++) dst[2048u * i] = slz_reduce(y[i], m);
+            for (int i = 0; i < G; i++) dst[(uint32_t)BS * i] = slz_reduce(y[i], m);
         }
     }
 }
@@ -178,8 +179,126 @@ k_big_rows(bign_args A, uint32_t G, uint32_t n_tasks, int xcd_aware) {
     }
 }
 
+// ---- P2 with 1024-blocks -------------------------------------------------------------------------
+// One wave per (ciphertext, prime, 1024-block), 16 coefficients per lane: the accumulators of both components, the block
+// and the tables fit 256 registers, so two waves share a SIMD and cover each other's memory latency (the 2048-block
+// kernel above needs more than 256 and runs one wave per SIMD, 43 % of it waiting for memory).
+__global__ void __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(2, 2)))
+k_big_rows16(bign_args A, uint32_t G, uint32_t n_tasks, int xcd_aware) {
+    extern __shared__ double lds[];
+    const uint32_t lane = threadIdx.x & 63u;
+    const uint32_t wv = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
+    uint32_t task = blockIdx.x * 4 + wv;
+    if (xcd_aware) {                                             // as above: an XCD keeps to its 1/8 of the (prime, block) pairs
+        const uint32_t cpx = 2 * G / 8;
+        const uint32_t xcd = blockIdx.x & 7u, v = (blockIdx.x >> 3) * 4 + wv;
+        task = (v / cpx) * 2 * G + xcd * cpx + v % cpx;
+    }
+    if (task >= n_tasks) return;                                 // whole wave leaves; no workgroup barriers below
+    double *T = lds + wv * (TBUF16 + 1024u);
+    double *twA = T + TBUF16, *twB = twA + 64;                  // this block's forward tables, staged in LDS
+    const uint32_t row = task % G, q = (task / G) & 1u, b = task / (2 * G);
+    const uint32_t N = A.N, R = 2 * A.l;
+    const slz_mod m = A.mod[q];
+    const bign_tabs tb = A.tab[q];
+    {
+        const double *gA = tb.rowA + (size_t)row * 64, *gB = tb.rowB + (size_t)row * 15 * 64;
+        twA[lane] = gA[lane];
+#pragma unroll
+        for (int k = 0; k < 15; k++) twB[64 * k + lane] = gB[64 * k + lane];
+        wave_sync();
+    }
+    // spectrum index of x[i] is 1024 row + 16 lane + i, stored at position (idx % 32) (N/32) + idx / 32 of the prepared
+    // polynomial: register i of lane l sits at i (N/32) + [16 (l & 1) (N/32) + 32 row + l / 2]
+    const uint32_t stride = N / 32;
+    const uint32_t key_lane_off = (16u * (lane & 1u) * stride + (lane >> 1)) * 8u;
+    double o0[16], o1[16];
+    double xn[16];                                               // the next GGSW row's block, requested one row ahead
+    {
+        const double *src = A.X + (((size_t)b * 2 + q) * R + 0) * N + 1024u * row;
+#pragma unroll
+        for (int e = 0; e < 16; e++) xn[e] = ldl(src + 64 * e, lane * 8u);
+    }
+    for (uint32_t r = 0; r < R; r++) {
+        int z;
+        asm volatile("s_mov_b32 %0, 0" : "=s"(z));              // tables are reloaded per GGSW row (they would spill if hoisted)
+        double x[16];
+#pragma unroll
+        for (int e = 0; e < 16; e++) x[e] = xn[e];
+        // the key words of this row and then the next row's block are requested here (vector memory completes in issue
+        // order) and arrive while the transform runs
+        const double *k0 = A.bskp_step + (((size_t)q * R + r) * 2 + 0) * N + 32u * row + z;
+        const double *k1 = k0 + N;
+        double kk0[16], kk1[16];
+#pragma unroll
+        for (int i = 0; i < 16; i++) { kk0[i] = ldl(k0 + (size_t)i * stride, key_lane_off); kk1[i] = ldl(k1 + (size_t)i * stride, key_lane_off); }
+        {
+            const double *nxt = A.X + (((size_t)b * 2 + q) * R + (r + 1 < R ? r + 1 : r)) * N + 1024u * row + z;
+#pragma unroll
+            for (int e = 0; e < 16; e++) xn[e] = ldl(nxt + 64 * e, lane * 8u);
+        }
+        SCHED_FENCE();
+        fwd16(x, T, twA, twB, m, lane, z);
+        SCHED_FENCE();
+#pragma unroll
+        for (int g = 0; g < 4; g++) {
+            double r0[4], r1[4];
+            const double x4[4] = {x[4 * g], x[4 * g + 1], x[4 * g + 2], x[4 * g + 3]};
+            const double ka[4] = {kk0[4 * g], kk0[4 * g + 1], kk0[4 * g + 2], kk0[4 * g + 3]};
+            const double kb[4] = {kk1[4 * g], kk1[4 * g + 1], kk1[4 * g + 2], kk1[4 * g + 3]};
+            mulmod_k<4>(r0, x4, ka, m);
+            mulmod_k<4>(r1, x4, kb, m);
+#pragma unroll
+            for (int u = 0; u < 4; u++) {
+                o0[4 * g + u] = (r == 0) ? r0[u] : o0[4 * g + u] + r0[u];
+                o1[4 * g + u] = (r == 0) ? r1[u] : o1[4 * g + u] + r1[u];
+            }
+        }
+        if ((r & 3u) == 3u && r + 1 < R) {                       // more than four rows: keep the running sums below 8 p
+#pragma unroll
+            for (int g = 0; g < 4; g++) {
+                double a4[4], b4[4];
+                const double xa[4] = {o0[4 * g], o0[4 * g + 1], o0[4 * g + 2], o0[4 * g + 3]};
+                const double xb[4] = {o1[4 * g], o1[4 * g + 1], o1[4 * g + 2], o1[4 * g + 3]};
+                reduce_k<4>(a4, xa, m);
+                reduce_k<4>(b4, xb, m);
+#pragma unroll
+                for (int u = 0; u < 4; u++) { o0[4 * g + u] = a4[u]; o1[4 * g + u] = b4[u]; }
+            }
+        }
+        wave_sync();
+    }
+    // inverse: first 10 stages inside the block, reduce, hand the block to the column pass
+    for (int comp = 0; comp < 2; comp++) {
+        int z;
+        asm volatile("s_mov_b32 %0, 0" : "=s"(z));
+        double x[16];
+#pragma unroll
+        for (int g = 0; g < 2; g++) {
+            double r8[8], x8[8];
+#pragma unroll
+            for (int u = 0; u < 8; u++) x8[u] = comp ? o1[8 * g + u] : o0[8 * g + u];
+            reduce_k<8>(r8, x8, m);
+#pragma unroll
+            for (int u = 0; u < 8; u++) x[8 * g + u] = r8[u];
+        }
+        inv16(x, T, tb.inv, tb.inv, m, lane, z);
+        double *dst = A.Y + (((size_t)b * 2 + q) * 2 + comp) * N + 1024u * row;
+#pragma unroll
+        for (int g = 0; g < 2; g++) {
+            double r8[8], x8[8];
+#pragma unroll
+            for (int u = 0; u < 8; u++) x8[u] = x[8 * g + u];
+            reduce_k<8>(r8, x8, m);
+#pragma unroll
+            for (int u = 0; u < 8; u++) dst[64 * (8 * g + u) + lane] = r8[u];
+        }
+        wave_sync();
+    }
+}
+
 // ---- P3 ------------------------------------------------------------------------------------------
-template <int G>
+template <int G, int BS>
 __global__ void __launch_bounds__(256)
 k_big_cols_inv(bign_args A) {
     const uint32_t c = blockIdx.x * 256 + threadIdx.x;
@@ -192,23 +311,23 @@ k_big_cols_inv(bign_args A) {
         const double *tw = A.tab[q].inv, *post = A.tab[q].post;
         double y[G];
 #pragma unroll
-        for (int i = 0; i < G; i++) y[i] = src[2048u * i];
-        // stages with half-size t = 2048 * half: pairs of rows i, i + half; twiddle inv[t + 2048 (i mod half) + c]
+        for (int i = 0; i < G; i++) y[i] = src[(uint32_t)BS * i];
+        // stages with half-size t = BS * half: pairs of rows i, i + half; twiddle inv[t + BS (i mod half) + c]
 #pragma unroll
         for (int half = 1; half < G; half <<= 1) {
 #pragma unroll
             for (int j = 0; j < half; j++) {
-                const double w = tw[2048u * half + 2048u * j + c];
+                const double w = tw[(uint32_t)BS * half + (uint32_t)BS * j + c];
 #pragma unroll
                 for (int blk = 0; blk < G / (2 * half); blk++) bfly(y[blk * 2 * half + j], y[blk * 2 * half + j + half], w, m);
             }
         }
 #pragma unroll
-        for (int i = 0; i < G; i++) res[q][i] = slz_mulmod(y[i], post[2048u * i + c], m);
+        for (int i = 0; i < G; i++) res[q][i] = slz_mulmod(y[i], post[(uint32_t)BS * i + c], m);
     }
     uint64_t *poly = A.acc + ((size_t)b * 2 + comp) * N + c;
 #pragma unroll
-    for (int i = 0; i < G; i++) poly[2048u * i] += slz_crt64(res[0][i], res[1][i], A.mod[1], A.p1inv_mod_p2);
+    for (int i = 0; i < G; i++) poly[(uint32_t)BS * i] += slz_crt64(res[0][i], res[1][i], A.mod[1], A.p1inv_mod_p2);
 }
 
 // ---- host ------------------------------------------------------------------------------------------
@@ -216,32 +335,27 @@ k_big_cols_inv(bign_args A) {
 int slz_bign_supported(const slz_params *p) {
     if (p->k != 1 || p->pbs_level > BIG_MAX_L) return 0;
     for (uint32_t G = 2; G <= 32; G <<= 1)
-        if (p->N == 2048u * G) return 1;
+        if (p->N == 2048u * G || p->N == 1024u * G) return 1;
     return 0;
 }
 
-int slz_bign_init(slz_ctx *ctx) {
-    const uint32_t N = ctx->prm.N, G = N / 2048;
-    // worst-case bounds (units of p): column stages start from digits, rows from reduced values
-    double a = 1e-6;
-    for (uint32_t g = G; g > 1; g >>= 1) a += slz_mulmod_bound(a);
-    if (a > 7.5) return SLZ_E_UNSUPPORTED;
-    a = 0.5 + 1e-9;
-    for (int s = 0; s < 6; s++) a += slz_mulmod_bound(a);        // block stages 1..6, then the reduction inside fused_fwd
-    if (a > 7.5) return SLZ_E_UNSUPPORTED;
-    a = 0.5 + 1e-9;
-    for (int s = 0; s < 5; s++) a += slz_mulmod_bound(a);
-    // sums over the GGSW rows are reduced after every fourth row
-    if (0.5 + 4.0 * slz_mulmod_bound(a) > 7.5) return SLZ_E_UNSUPPORTED;
-    a = 0.5 + 1e-9;
-    for (uint32_t g = G; g > 1; g >>= 1) a += slz_mulmod_bound(a);
-    if (slz_mulmod_bound(a) > 1.95) return SLZ_E_UNSUPPORTED;
-    std::vector<double> nat(N), rowA((size_t)2 * G * 64), rowB((size_t)2 * G * 31 * 64);
+static bool block_fits(uint32_t N, uint32_t BS) {
+    const uint32_t G = N / BS;
+    return N % BS == 0 && G >= 2 && G <= 32 && (G & (G - 1)) == 0;
+}
+
+// block-specific forward tables for blocks of BS = 64 * E coefficients (E = 32 or 16 per lane)
+static int build_row_tables(slz_ctx *ctx, uint32_t BS, double **dA, double **dB) {
+    const uint32_t N = ctx->prm.N, G = N / BS, E = BS / 64;
+    int late = 0;                                   // stages done after the transposition: log2 E
+    for (uint32_t e = E; e > 1; e >>= 1) late++;
+    const uint32_t nB = E - 1;                      // per-lane twiddles of those stages
+    std::vector<double> nat(N), rowA((size_t)2 * G * 64), rowB((size_t)2 * G * nB * 64);
     for (int q = 0; q < 2; q++) {
         SLZ_HIP(hipMemcpy(nat.data(), ctx->tab[q].fwd, (size_t)N * sizeof(double), hipMemcpyDeviceToHost));
         for (uint32_t row = 0; row < G; row++) {
-            // the 2048-block `row` continues the transform with sub-block counts m' = 1, 2, ..., 1024; its sub-block blk
-            // at that stage is block (G + row) * m' + blk ... i.e. table entry fwd[(G + row) * m' + blk]
+            // block `row` continues the transform with sub-block counts m' = 1, 2, ..., BS / 2; its sub-block blk at that
+            // stage is block (G + row) m' + blk of the whole transform: table entry fwd[(G + row) m' + blk]
             double *ra = &rowA[((size_t)q * G + row) * 64];
             ra[0] = 1.0;
             for (uint32_t x = 1; x < 64; x++) {
@@ -250,42 +364,94 @@ int slz_bign_init(slz_ctx *ctx) {
                 ra[x] = nat[(size_t)(G + row) * mp + (x - mp)];
             }
             int kk = 0;
-            for (int s = 0; s < 5; s++) {
-                const uint32_t t = 16u >> s, mp = FN / (2 * t);
+            for (int s = 0; s < late; s++) {
+                const uint32_t t = (E / 2) >> s, mp = BS / (2 * t);
                 for (uint32_t blk = 0; blk < (1u << s); blk++, kk++)
                     for (uint32_t l = 0; l < 64; l++)
-                        rowB[(((size_t)q * G + row) * 31 + kk) * 64 + l] = nat[(size_t)(G + row) * mp + (32 * l) / (2 * t) + blk];
+                        rowB[(((size_t)q * G + row) * nB + kk) * 64 + l] = nat[(size_t)(G + row) * mp + (E * l) / (2 * t) + blk];
             }
         }
     }
-    SLZ_HIP(hipMalloc((void **)&ctx->bign_rowA, rowA.size() * sizeof(double)));
-    SLZ_HIP(hipMalloc((void **)&ctx->bign_rowB, rowB.size() * sizeof(double)));
-    SLZ_HIP(hipMemcpy(ctx->bign_rowA, rowA.data(), rowA.size() * sizeof(double), hipMemcpyHostToDevice));
-    SLZ_HIP(hipMemcpy(ctx->bign_rowB, rowB.data(), rowB.size() * sizeof(double), hipMemcpyHostToDevice));
-    SLZ_HIP(hipFuncSetAttribute((const void *)k_big_rows, hipFuncAttributeMaxDynamicSharedMemorySize, 4 * TBUF * sizeof(double)));
+    SLZ_HIP(hipMalloc((void **)dA, rowA.size() * sizeof(double)));
+    SLZ_HIP(hipMalloc((void **)dB, rowB.size() * sizeof(double)));
+    SLZ_HIP(hipMemcpy(*dA, rowA.data(), rowA.size() * sizeof(double), hipMemcpyHostToDevice));
+    SLZ_HIP(hipMemcpy(*dB, rowB.data(), rowB.size() * sizeof(double), hipMemcpyHostToDevice));
     return SLZ_OK;
+}
+
+// worst-case bounds (units of p) of one block size: column stages start from digits, rows from reduced values
+static bool bounds_ok(uint32_t N, uint32_t BS) {
+    const uint32_t G = N / BS;
+    double a = 1e-6;
+    for (uint32_t g = G; g > 1; g >>= 1) a += slz_mulmod_bound(a);
+    if (a > 7.5) return false;
+    a = 0.5 + 1e-9;
+    for (int s = 0; s < 6; s++) a += slz_mulmod_bound(a);        // block stages 1..6, then the reduction inside the wave transform
+    if (a > 7.5) return false;
+    a = 0.5 + 1e-9;
+    for (int s = 0; s < (BS == 2048 ? 5 : 4); s++) a += slz_mulmod_bound(a);
+    // sums over the GGSW rows are reduced after every fourth row
+    if (0.5 + 4.0 * slz_mulmod_bound(a) > 7.5) return false;
+    a = 0.5 + 1e-9;
+    for (uint32_t g = G; g > 1; g >>= 1) a += slz_mulmod_bound(a);
+    return slz_mulmod_bound(a) <= 1.95;
+}
+
+int slz_bign_init(slz_ctx *ctx) {
+    const uint32_t N = ctx->prm.N;
+    ctx->has_bign16 = 0;
+    ctx->bign_block = 0;
+    bool any = false;
+    if (block_fits(N, 2048) && bounds_ok(N, 2048)) {
+        int rc = build_row_tables(ctx, 2048, &ctx->bign_rowA, &ctx->bign_rowB);
+        if (rc != SLZ_OK) return rc;
+        SLZ_HIP(hipFuncSetAttribute((const void *)k_big_rows, hipFuncAttributeMaxDynamicSharedMemorySize, 4 * TBUF * sizeof(double)));
+        ctx->bign_block = 2048;
+        any = true;
+    }
+    if (block_fits(N, 1024) && bounds_ok(N, 1024)) {
+        int rc = build_row_tables(ctx, 1024, &ctx->bign16_rowA, &ctx->bign16_rowB);
+        if (rc != SLZ_OK) return rc;
+        SLZ_HIP(hipFuncSetAttribute((const void *)k_big_rows16, hipFuncAttributeMaxDynamicSharedMemorySize, 4 * (TBUF16 + 1024) * sizeof(double)));
+        ctx->has_bign16 = 1;
+        ctx->bign_block = 1024;                                  // preferred: two waves per SIMD in the row pass
+        any = true;
+    }
+    return any ? SLZ_OK : SLZ_E_UNSUPPORTED;
 }
 
 void slz_bign_destroy(slz_ctx *ctx) {
     if (ctx->bign_rowA) (void)hipFree(ctx->bign_rowA);
     if (ctx->bign_rowB) (void)hipFree(ctx->bign_rowB);
-    ctx->bign_rowA = ctx->bign_rowB = nullptr;
+    if (ctx->bign16_rowA) (void)hipFree(ctx->bign16_rowA);
+    if (ctx->bign16_rowB) (void)hipFree(ctx->bign16_rowB);
+    ctx->bign_rowA = ctx->bign_rowB = ctx->bign16_rowA = ctx->bign16_rowB = nullptr;
 }
 
-template <int G>
+template <int G, int BS>
 static void launch_cols(bool fwd, const bign_args &A, uint32_t batch, hipStream_t s) {
-    dim3 grid(2048 / 256, 2, batch);
-    if (fwd) hipLaunchKernelGGL(k_big_cols_fwd<G>, grid, dim3(256), 0, s, A);
-    else hipLaunchKernelGGL(k_big_cols_inv<G>, grid, dim3(256), 0, s, A);
+    dim3 grid(BS / 256, 2, batch);
+    if (fwd) hipLaunchKernelGGL((k_big_cols_fwd<G, BS>), grid, dim3(256), 0, s, A);
+    else hipLaunchKernelGGL((k_big_cols_inv<G, BS>), grid, dim3(256), 0, s, A);
 }
 
-static void launch_cols_any(bool fwd, uint32_t G, const bign_args &A, uint32_t batch, hipStream_t s) {
-    switch (G) {
-        case 2: launch_cols<2>(fwd, A, batch, s); break;
-        case 4: launch_cols<4>(fwd, A, batch, s); break;
-        case 8: launch_cols<8>(fwd, A, batch, s); break;
-        case 16: launch_cols<16>(fwd, A, batch, s); break;
-        default: launch_cols<32>(fwd, A, batch, s); break;
+static void launch_cols_any(bool fwd, uint32_t G, uint32_t BS, const bign_args &A, uint32_t batch, hipStream_t s) {
+    if (BS == 2048) {
+        switch (G) {
+            case 2: launch_cols<2, 2048>(fwd, A, batch, s); break;
+            case 4: launch_cols<4, 2048>(fwd, A, batch, s); break;
+            case 8: launch_cols<8, 2048>(fwd, A, batch, s); break;
+            case 16: launch_cols<16, 2048>(fwd, A, batch, s); break;
+            default: launch_cols<32, 2048>(fwd, A, batch, s); break;
+        }
+    } else {
+        switch (G) {
+            case 2: launch_cols<2, 1024>(fwd, A, batch, s); break;
+            case 4: launch_cols<4, 1024>(fwd, A, batch, s); break;
+            case 8: launch_cols<8, 1024>(fwd, A, batch, s); break;
+            case 16: launch_cols<16, 1024>(fwd, A, batch, s); break;
+            default: launch_cols<32, 1024>(fwd, A, batch, s); break;
+        }
     }
 }
 
@@ -293,14 +459,15 @@ static void launch_cols_any(bool fwd, uint32_t G, const bign_args &A, uint32_t b
 int slz_bign_cmux_steps(slz_ctx *ctx, const uint64_t *lwe_in, const double *bskp, uint32_t n_steps, uint64_t *acc,
                         uint32_t batch, hipStream_t s) {
     const slz_params &p = ctx->prm;
-    const uint32_t N = p.N, G = N / 2048, R = 2 * p.pbs_level;
+    const uint32_t N = p.N, BS = (uint32_t)ctx->bign_block, G = N / BS, R = 2 * p.pbs_level;
     uint32_t logG = 0;
     while ((1u << logG) < G) logG++;
     // Ciphertexts go through all steps in chunks whose workspace (X, Y, accumulators: (2R + 4 + 2) N doubles each) stays
     // in the 256 MB Infinity Cache; the key (read once per chunk and step) streams from HBM.
     const size_t per_ct = (size_t)(2 * R + 4 + 2) * N * 8;
     uint32_t chunk = (uint32_t)((size_t)224 * 1024 * 1024 / per_ct);
-    const uint32_t fill = 1024u / (2 * G) ? 1024u / (2 * G) : 1;      // ciphertexts whose row tasks fill the chip once (4 waves per CU)
+    const uint32_t slots = BS == 2048 ? 1024u : 2048u;              // resident row-pass waves: one or two per SIMD
+    const uint32_t fill = slots / (2 * G) ? slots / (2 * G) : 1;     // ciphertexts whose row tasks fill the chip once
     chunk = chunk / fill * fill;
     if (chunk < fill) chunk = fill;
     if (chunk > batch) chunk = batch;
@@ -314,8 +481,8 @@ int slz_bign_cmux_steps(slz_ctx *ctx, const uint64_t *lwe_in, const double *bskp
         A.n = p.n; A.N = N; A.logG = logG; A.beta = p.pbs_base_log; A.l = p.pbs_level; A.batch = nb;
         for (int q = 0; q < 2; q++) {
             A.tab[q].fwd = ctx->tab[q].fwd;
-            A.tab[q].rowA = ctx->bign_rowA + (size_t)q * G * 64;
-            A.tab[q].rowB = ctx->bign_rowB + (size_t)q * G * 31 * 64;
+            A.tab[q].rowA = (BS == 2048 ? ctx->bign_rowA : ctx->bign16_rowA) + (size_t)q * G * 64;
+            A.tab[q].rowB = BS == 2048 ? ctx->bign_rowB + (size_t)q * G * 31 * 64 : ctx->bign16_rowB + (size_t)q * G * 15 * 64;
             A.tab[q].inv = ctx->tab[q].inv;
             A.tab[q].post = ctx->tab[q].post;
             A.mod[q] = ctx->mod[q];
@@ -325,11 +492,14 @@ int slz_bign_cmux_steps(slz_ctx *ctx, const uint64_t *lwe_in, const double *bskp
         for (uint32_t step = 0; step < n_steps; step++) {
             A.step = step;
             A.bskp_step = bskp + (size_t)step * 2 * R * 2 * N;
-            launch_cols_any(true, G, A, nb, s);
+            launch_cols_any(true, G, BS, A, nb, s);
             // the XCD-aware order needs the task count to split evenly over 8 XCDs x 4 waves x (2G/8) combinations
             const int xcd_aware = (2 * G) % 8 == 0 && n_tasks % 32 == 0 && (n_tasks / 8) % (2 * G / 8) == 0;
-            hipLaunchKernelGGL(k_big_rows, dim3((n_tasks + 3) / 4), dim3(256), 4 * TBUF * sizeof(double), s, A, G, n_tasks, xcd_aware);
-            launch_cols_any(false, G, A, nb, s);
+            if (BS == 2048)
+                hipLaunchKernelGGL(k_big_rows, dim3((n_tasks + 3) / 4), dim3(256), 4 * TBUF * sizeof(double), s, A, G, n_tasks, xcd_aware);
+            else
+                hipLaunchKernelGGL(k_big_rows16, dim3((n_tasks + 3) / 4), dim3(256), 4 * (TBUF16 + 1024) * sizeof(double), s, A, G, n_tasks, xcd_aware);
+            launch_cols_any(false, G, BS, A, nb, s);
         }
     }
     SLZ_HIP(hipGetLastError());

@@ -51,6 +51,10 @@ struct slz_ctx {
     int has_bign;             // large-N three-pass path available (N = 2048 G, k = 1)
     double *bign_rowA;        // [2][G][64] block-specific lane-uniform forward twiddles
     double *bign_rowB;        // [2][G][31][64] block-specific per-lane forward twiddles
+    int has_bign16;           // large-N path with 1024-blocks available (N = 1024 G', G' = 2..32, k = 1)
+    int bign_block;           // block size the large-N path uses: 1024 or 2048
+    double *bign16_rowA;      // [2][G'][64] as bign_rowA for 1024-blocks
+    double *bign16_rowB;      // [2][G'][15][64] per-lane twiddles of the last four forward stages of a 1024-block
     // scratch for the generic path, sized for max_batch
     uint64_t *acc;            // [max_batch][k+1][N]
     double *dig;              // [max_batch][(k+1)l][N]

@@ -282,3 +282,169 @@ __device__ __forceinline__ void fused_inv(double (&x)[32], double *T, const doub
     }
 }
 
+
+// ---- 1024-point wave transforms: 16 coefficients per lane ---------------------------------------------------------------
+// Half the registers of the 2048-point version, so that a kernel holding accumulators besides the transform fits two
+// waves per SIMD.  Ten stages: four over the register index, one across the two half-waves (v_permlane32_swap), one
+// across the 16-lane rows (v_permlane16_swap), one LDS transposition, four more over the register index.
+//   layout A: x[e] = coefficient 64 e + lane;                          layout B: x[i] = position 16 lane + i.
+//   lane = 32 hh + 16 v + j.  After the two swap stages a lane's register 2 mm + u holds 64 (2 mm + hh) + 32 v + 16 u + j.
+#define TBUF16 1152u          // doubles per wave buffer: 1024 + 2 pad doubles per 16 (16-byte reads at a 144-byte lane stride)
+
+// a <- rows (a0, b0, a2, b2), b <- rows (a1, b1, a3, b3) of the four 16-lane rows of a and b
+__device__ __forceinline__ void swap16(double &a, double &b) {
+    uint32_t alo = (uint32_t)__double2loint(a), ahi = (uint32_t)__double2hiint(a);
+    uint32_t blo = (uint32_t)__double2loint(b), bhi = (uint32_t)__double2hiint(b);
+    auto lo = __builtin_amdgcn_permlane16_swap(alo, blo, false, false);
+    auto hi = __builtin_amdgcn_permlane16_swap(ahi, bhi, false, false);
+    a = __hiloint2double((int)hi[0], (int)lo[0]);
+    b = __hiloint2double((int)hi[1], (int)lo[1]);
+}
+
+// Forward.  In: layout A, |x| tiny (digits after the column stages, reduced).  Out: layout B, |x| <= 3.7 p.
+// twA: lane-uniform twiddles of this block, entry (sub-blocks m') + blk for m' = 1 .. 32 (64 doubles);
+// twB_tab: [15][64] per-lane twiddles of the last four stages.  Bounds: six stages 0.5 -> 4.81 p, reduction, four more -> 3.63 p.
+__device__ __forceinline__ void fwd16(double (&x)[16], double *T, const double *twA, const double *twB_tab, slz_mod m, uint32_t lane,
+                                      int z) {
+    const uint32_t hh = lane >> 5, v = (lane >> 4) & 1u, j = lane & 15u;
+    // twA and twB_tab are expected in LDS (the kernel stages its block's tables there once): their reads do not queue
+    // behind the kernel's global loads and need no registers until the stage that uses them
+#pragma unroll
+    for (int s = 0; s < 4; s++) {
+        const int half = 8 >> s;
+#pragma unroll
+        for (int g = 0; g < 2; g++) {
+#define FA16_I(b) (((b) / half) * 2 * half + (b) % half)
+#define FA16_W(b) twA[(1 << s) + (b) / half + z]
+            BF4(FA16_I(4 * g), FA16_I(4 * g) + half, FA16_W(4 * g), FA16_I(4 * g + 1), FA16_I(4 * g + 1) + half, FA16_W(4 * g + 1),
+                FA16_I(4 * g + 2), FA16_I(4 * g + 2) + half, FA16_W(4 * g + 2), FA16_I(4 * g + 3), FA16_I(4 * g + 3) + half, FA16_W(4 * g + 3));
+        }
+    }
+#pragma unroll
+    for (int g = 0; g < 2; g++) {                                           // stride 32: partner 32 lanes away
+#pragma unroll
+        for (int mm = 4 * g; mm < 4 * g + 4; mm++) swap32(x[2 * mm], x[2 * mm + 1]);
+#define TW5(mm) ldl(twA + 16 + 2 * (mm) + z, hh * 8u)                       /* stride 32: block 2 mm + hh of 16 */
+        BF4(8 * g, 8 * g + 1, TW5(4 * g), 8 * g + 2, 8 * g + 3, TW5(4 * g + 1), 8 * g + 4, 8 * g + 5, TW5(4 * g + 2), 8 * g + 6, 8 * g + 7,
+            TW5(4 * g + 3));
+    }
+    double *wb = T + 72u * hh + 36u * v + j;
+#pragma unroll
+    for (int g = 0; g < 2; g++) {                                           // stride 16: partner 16 lanes away
+#pragma unroll
+        for (int mm = 4 * g; mm < 4 * g + 4; mm++) swap16(x[2 * mm], x[2 * mm + 1]);
+#define TW6(mm) ldl(twA + 32 + 4 * (mm) + z, (lane >> 4) * 8u)              /* stride 16: block 4 mm + 2 hh + v of 32 */
+        BF4(8 * g, 8 * g + 1, TW6(4 * g), 8 * g + 2, 8 * g + 3, TW6(4 * g + 1), 8 * g + 4, 8 * g + 5, TW6(4 * g + 2), 8 * g + 6, 8 * g + 7,
+            TW6(4 * g + 3));
+        double r8[8];
+        const double x8[8] = {x[8 * g], x[8 * g + 1], x[8 * g + 2], x[8 * g + 3], x[8 * g + 4], x[8 * g + 5], x[8 * g + 6], x[8 * g + 7]};
+        reduce_k<8>(r8, x8, m);
+#pragma unroll
+        for (int u = 0; u < 4; u++) {                                       // registers 2 mm, 2 mm + 1 with mm = 4 g + u
+            wb[144 * (4 * g + u)] = r8[2 * u];
+            wb[144 * (4 * g + u) + 18] = r8[2 * u + 1];
+        }
+    }
+    wave_sync();
+    const double *rb = T + 18u * lane;
+#pragma unroll
+    for (int i = 0; i < 16; i += 2) {
+        const double2 t2 = *reinterpret_cast<const double2 *>(rb + i);
+        x[i] = t2.x;
+        x[i + 1] = t2.y;
+    }
+#pragma unroll
+    for (int s = 0; s < 4; s++) {
+        const int t = 8 >> s;
+#pragma unroll
+        for (int g = 0; g < 2; g++) {
+#define FB16_I(b) (((b) / t) * 2 * t + (b) % t)
+#define FB16_W(b) ldl(twB_tab + 64 * ((1 << s) - 1 + (b) / t) + z, lane * 8u)
+            BF4(FB16_I(4 * g), FB16_I(4 * g) + t, FB16_W(4 * g), FB16_I(4 * g + 1), FB16_I(4 * g + 1) + t, FB16_W(4 * g + 1),
+                FB16_I(4 * g + 2), FB16_I(4 * g + 2) + t, FB16_W(4 * g + 2), FB16_I(4 * g + 3), FB16_I(4 * g + 3) + t, FB16_W(4 * g + 3));
+        }
+    }
+}
+
+// Inverse (cyclic decimation-in-time on the bit-reversed spectrum; stops before the stages across 1024-blocks and the
+// twist).  In: layout B, |x| <= 0.51 p.  Out: layout A, |x| <= 6.2 p.  twS: lane-uniform entries inv[t + j], t <= 8;
+// inv: the same natural inverse table for the per-lane entries.  Bounds: 0.5 -> 1 -> 2 (unit twiddles) -> 2.88 -> 3.91,
+// reduction, six more stages -> 6.2.
+__device__ __forceinline__ void inv16(double (&x)[16], double *T, const double *twS, const double *inv, slz_mod m, uint32_t lane, int z) {
+    const uint32_t hh = lane >> 5, v = (lane >> 4) & 1u, j = lane & 15u, l5 = lane & 31u;
+    double twL[15];
+    const double w16 = ldl(inv + 16 + z, j * 8u);
+    const double w32 = ldl(inv + 32 + z, l5 * 8u);
+    {
+        int kk = 0;
+#pragma unroll
+        for (int s = 0; s < 4; s++)
+#pragma unroll
+            for (int jj = 0; jj < (1 << s); jj++) twL[kk++] = ldl(inv + 64 * (1 << s) + 64 * jj + z, lane * 8u);
+    }
+    SCHED_FENCE();
+#pragma unroll
+    for (int i = 0; i < 16; i += 2) bfly_nomul(x[i], x[i + 1]);                        // t = 1
+    {
+        const double w = twS[3 + z];
+#pragma unroll
+        for (int blk = 0; blk < 4; blk++) bfly_nomul(x[4 * blk], x[4 * blk + 2]);       // t = 2, unit twiddle
+        BF4(1, 3, w, 5, 7, w, 9, 11, w, 13, 15, w);                                     // t = 2, twiddle inv[3]
+    }
+#pragma unroll
+    for (int s = 2; s < 4; s++) {                                                       // t = 4, 8
+        const int t = 1 << s;
+#pragma unroll
+        for (int g = 0; g < 2; g++) {
+#define IB16_I(b) (((b) / t) * 2 * t + (b) % t)
+#define IB16_W(b) twS[t + (b) % t + z]
+            BF4(IB16_I(4 * g), IB16_I(4 * g) + t, IB16_W(4 * g), IB16_I(4 * g + 1), IB16_I(4 * g + 1) + t, IB16_W(4 * g + 1),
+                IB16_I(4 * g + 2), IB16_I(4 * g + 2) + t, IB16_W(4 * g + 2), IB16_I(4 * g + 3), IB16_I(4 * g + 3) + t, IB16_W(4 * g + 3));
+        }
+    }
+    wave_sync();                                                                        // earlier reads of T are done
+    double *wb = T + 18u * lane;
+#pragma unroll
+    for (int g = 0; g < 2; g++) {
+        double r8[8];
+        const double x8[8] = {x[8 * g], x[8 * g + 1], x[8 * g + 2], x[8 * g + 3], x[8 * g + 4], x[8 * g + 5], x[8 * g + 6], x[8 * g + 7]};
+        reduce_k<8>(r8, x8, m);
+#pragma unroll
+        for (int u = 0; u < 4; u++) {
+            double2 t2;
+            t2.x = r8[2 * u];
+            t2.y = r8[2 * u + 1];
+            *reinterpret_cast<double2 *>(wb + 8 * g + 2 * u) = t2;
+        }
+    }
+    wave_sync();
+    const double *rb = T + 72u * hh + 36u * v + j;
+#pragma unroll
+    for (int mm = 0; mm < 8; mm++) {
+        x[2 * mm] = rb[144 * mm];
+        x[2 * mm + 1] = rb[144 * mm + 18];
+    }
+#pragma unroll
+    for (int g = 0; g < 2; g++) {                                                       // t = 16
+        BF4(8 * g, 8 * g + 1, w16, 8 * g + 2, 8 * g + 3, w16, 8 * g + 4, 8 * g + 5, w16, 8 * g + 6, 8 * g + 7, w16);
+#pragma unroll
+        for (int mm = 4 * g; mm < 4 * g + 4; mm++) swap16(x[2 * mm], x[2 * mm + 1]);
+    }
+#pragma unroll
+    for (int g = 0; g < 2; g++) {                                                       // t = 32
+        BF4(8 * g, 8 * g + 1, w32, 8 * g + 2, 8 * g + 3, w32, 8 * g + 4, 8 * g + 5, w32, 8 * g + 6, 8 * g + 7, w32);
+#pragma unroll
+        for (int mm = 4 * g; mm < 4 * g + 4; mm++) swap32(x[2 * mm], x[2 * mm + 1]);
+    }
+#pragma unroll
+    for (int s = 0; s < 4; s++) {                                                       // t = 64 .. 512
+        const int half = 1 << s;
+#pragma unroll
+        for (int g = 0; g < 2; g++) {
+#define IA16_I(b) (((b) / half) * 2 * half + (b) % half)
+#define IA16_W(b) twL[half - 1 + (b) % half]
+            BF4(IA16_I(4 * g), IA16_I(4 * g) + half, IA16_W(4 * g), IA16_I(4 * g + 1), IA16_I(4 * g + 1) + half, IA16_W(4 * g + 1),
+                IA16_I(4 * g + 2), IA16_I(4 * g + 2) + half, IA16_W(4 * g + 2), IA16_I(4 * g + 3), IA16_I(4 * g + 3) + half, IA16_W(4 * g + 3));
+        }
+    }
+}

@@ -333,11 +333,13 @@ def test_fused_more_ciphertexts_than_resident_workgroups(slz, orc):
     dict(n=2, N=16384, k=1, pbs_base_log=7, pbs_level=4),
     dict(n=2, N=32768, k=1, pbs_base_log=15, pbs_level=2),
 ], ids=lambda s: "N%d_l%d" % (s["N"], s["pbs_level"]))
-def test_large_n_path_matches_oracle_and_generic(slz, orc, shape):
+@pytest.mark.parametrize("block", [1024, 2048])
+def test_large_n_path_matches_oracle_and_generic(slz, orc, shape, block):
     p = tiny(**shape)
     batch = 5
     case = Case(slz, orc, p, batch, raw_inputs=True)
     assert case.ctx.path == "three_pass_large_n"
+    case.ctx.set_option(slz.SLZ_OPT_LARGE_N_BLOCK, block)       # row pass on 1024-blocks (16 coefficients per lane) or 2048-blocks
     for steps in sorted({0, 1, p.n}):
         want = orc.blind_rotate_batch(p, case.cts, case.luts, case.lut_idx, case.keys.bsk, steps)
         got = slz.to_host_u64(case.ctx.blind_rotate_batch(case.d_cts, case.d_luts, case.d_idx, case.d_bsk, steps))
