@@ -1,13 +1,13 @@
-// Blind rotation for large polynomials, N = 2048 * G with G in {2,4,8,16,32}, k = 1 (the 8-bit-precision-shaped
-// parameter sets: N = 32768).  The accumulator (512 KiB per ciphertext at N = 32768) cannot stay on chip, so a CMux
-// step is three passes over a per-ciphertext workspace that stays in L2 / Infinity Cache when ciphertexts are
-// processed in chunks:
-//   P1 "columns, forward":  per accumulator column c (coefficients 2048 i + c, i < G): rotate, subtract, decompose,
-//                           then the first log2(G) transform stages (they pair coefficients 2048 rows apart, so a
+// Blind rotation for large polynomials, N = BS * G with block size BS = 1024 or 2048 and G in {2,4,8,16,32}, k = 1 (the
+// 8-bit-precision-shaped parameter sets: N = 32768).  The accumulator (512 KiB per ciphertext at N = 32768) cannot stay
+// on chip, so a CMux step is three passes over a per-ciphertext workspace that stays in L2 / Infinity Cache when
+// ciphertexts are processed in chunks:
+//   P1 "columns, forward":  per accumulator column c (coefficients BS i + c, i < G): rotate, subtract, decompose,
+//                           then the first log2(G) transform stages (they pair coefficients BS rows apart, so a
 //                           lane holding one column does them in registers), for every level and both primes.
-//   P2 "rows":              per prime and 2048-block: the remaining 11 forward stages with the wave-level transform
-//                           of the N = 2048 kernel (block-specific twiddles), multiply-accumulate with the prepared
-//                           key over all GGSW rows, the first 11 inverse stages.
+//   P2 "rows":              per prime and block: the remaining forward stages with a wave-level transform (32 or 16
+//                           coefficients per lane, block-specific twiddles), multiply-accumulate with the prepared
+//                           key over all GGSW rows, the same number of inverse stages.
 //   P3 "columns, inverse":  the last log2(G) inverse stages per column, the psi^-j / N twist, CRT lift, accumulate.
 #include "slz_internal.h"
 #include "slz_modarith.h"

@@ -1,5 +1,6 @@
-// Wave-level 2048-point negacyclic transforms on doubles (one wavefront = one polynomial or one 2048-block of a
-// larger one, 32 coefficients per lane), shared by the fused N = 2048 kernel and the large-N path.
+// Wave-level negacyclic transforms on doubles: 2048 points (one wavefront = one polynomial or one 2048-block of a larger
+// one, 32 coefficients per lane), shared by the fused N = 2048 kernel and the large-N path, and 1024 points (16
+// coefficients per lane, at the end of the file) for the large-N path.
 #pragma once
 #include "slz_internal.h"
 #include "slz_modarith.h"
