@@ -352,10 +352,26 @@ def test_large_n_path_matches_oracle_and_generic(slz, orc, shape, block):
     assert np.array_equal(gen, want)
 
 
-def test_large_n_worst_case_magnitudes(slz, orc):
+def test_large_n_path_takes_n2048_with_two_levels(slz, orc):
+    # N = 2048 with more than one level has no fused kernel; it runs the large-N path as two 1024-blocks
+    p = tiny(n=3, N=2048, k=1, pbs_base_log=12, pbs_level=2)
+    case = Case(slz, orc, p, 5, raw_inputs=True)
+    assert case.ctx.path == "three_pass_large_n"
+    with pytest.raises(slz.SlzError):
+        case.ctx.set_option(slz.SLZ_OPT_LARGE_N_BLOCK, 2048)    # a single 2048-block is not a large-N shape
+    want = orc.pbs_batch(p, case.cts, case.luts, case.lut_idx, case.keys.bsk)
+    got = slz.to_host_u64(case.ctx.pbs_batch(case.d_cts, case.d_luts, case.d_idx, case.d_bsk))
+    assert np.array_equal(got, want)
+    case.ctx.set_option(slz.SLZ_OPT_FORCE_GENERIC, 1)
+    assert np.array_equal(slz.to_host_u64(case.ctx.pbs_batch(case.d_cts, case.d_luts, case.d_idx, case.d_bsk)), want)
+
+
+@pytest.mark.parametrize("block", [1024, 2048])
+def test_large_n_worst_case_magnitudes(slz, orc, block):
     p = tiny(n=2, N=8192, k=1, pbs_base_log=21, pbs_level=1)      # 2 * 8192 * 2^20 * 2^63 = 2^97: the largest sums allowed
     case = Case(slz, orc, p, 3, raw_inputs=True)
     assert case.ctx.path == "three_pass_large_n"
+    case.ctx.set_option(slz.SLZ_OPT_LARGE_N_BLOCK, block)
     bsk = case.keys.bsk.copy()
     flat = bsk.reshape(-1)
     flat[0::3] = np.uint64(1 << 63)
