@@ -189,6 +189,83 @@ def bench_sign_rns(args):
     print(json.dumps(result))
 
 
+def bench_loss(args):
+    """--gadget loss_deriv: one step = IntCELossDeriv of a batch of 8 samples with 3 classes (Gamma = 7, kappa = 2, the largest
+    level whose packed lookup fits 8 bits): 5 lookups per entry in 5 dependent rounds.  --gadget weight_update: one step = the
+    clipped update of the 28 x 8 + 8 x 2 = 240 weights of the paper's largest network (alpha = 6), one lookup per weight.
+    Key and ciphertext material is uniform random words."""
+    import torch
+    import synth
+    import paper_2504_17785_amd as slz
+
+    if args.gadget_params == "cfg3":
+        p, max_batch = synth.CONFIGS[3], 256
+    else:
+        p = synth.Params(name="gadget_toy", n=4, k=1, N=2048, pbs_base_log=23, pbs_level=1, ks_base_log=4, ks_level=8,
+                         msg_bits=8, sigma_lwe=2.0 ** -40, sigma_bsk=2.0 ** -50, batch=1, n_luts=1, seed=0x6AD6E7)
+        max_batch = 8192
+    loss = args.gadget == "loss_deriv"
+    a, b, Gamma, kappa, alpha = 8, 3, 7, 2, 6
+    count = a * b if loss else (args.batch or 240)
+    lookups, rounds = (5 * count, 5) if loss else (count, 1)
+    torch.cuda.set_device(0)
+    ctx = slz.Context(p, max_batch)
+    R, C = (p.k + 1) * p.pbs_level, p.k + 1
+    bsk = synth.raw_words(p, "raw_bsk", p.n * R * C * p.N).reshape(p.n, p.k + 1, p.pbs_level, C, p.N)
+    ksk = synth.raw_words(p, "raw_ksk", p.k * p.N * p.ks_level * (p.n + 1)).reshape(p.k * p.N, p.ks_level, p.n + 1)
+    cts = synth.raw_words(p, "raw_ct", 2 * count * (p.n + 1)).reshape(2, count, p.n + 1)
+    d_std = slz.to_device_u64(bsk)
+    d_bskp = ctx.bsk_prepare(d_std)
+    del d_std
+    d_ksk = slz.to_device_u64(ksk)
+    if loss:
+        d_x, d_y = slz.to_device_u64(cts[0].reshape(a, b, p.n + 1)), slz.to_device_u64(cts[1].reshape(a, b, p.n + 1))
+        d_luts = slz.to_device_u64(slz.loss_luts(p, b, Gamma, kappa))
+        run = lambda: ctx.int_ce_loss_deriv(d_x, d_y, Gamma, kappa, d_luts, d_bskp, d_ksk)
+    else:
+        d_x, d_y = slz.to_device_u64(cts[0]), slz.to_device_u64(cts[1])
+        d_luts = slz.to_device_u64(slz.weight_update_luts(p, alpha))
+        run = lambda: ctx.weight_update(d_x, d_y, alpha, d_luts, d_bskp, d_ksk)
+    for _ in range(args.warmup):
+        run()
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for _ in range(args.steps):
+        d_out = run()
+    torch.cuda.synchronize()
+    ms = (time.perf_counter() - t0) * 1e3 / args.steps
+    achieved = lookups * alu_model_ops_per_pbs(p) / (ms * 1e-3) / 1e12
+    what = ("IntCELossDeriv of %d x %d logits (Gamma %d, kappa %d)" % (a, b, Gamma, kappa)) if loss else \
+        ("clipped update of %d weights (alpha %d)" % (count, alpha))
+    result = {
+        "metric": "%s_lookups_per_s" % args.gadget, "value": lookups / (ms * 1e-3), "unit": "PBS+KS/s",
+        "n_gpus": 1, "steps": args.steps, "warmup": args.warmup, "ms_per_step": ms,
+        "higher_is_better": True, "scaling": "weak", "vs_baseline": None, "dtype": "u64", "data": "synthetic",
+        "config": {"workload": "%s at %s: %d lookups in %d dependent rounds" % (what, p.name, lookups, rounds), "path": ctx.path},
+        "roofline": {"bound": "alu", "kernel": "blind rotation inside the lookups (whole gadget timed)", "achieved": achieved,
+                     "peak": PEAK_ALU_TINSTR, "unit": "Tinstr/s", "frac": achieved / PEAK_ALU_TINSTR, "traffic": None},
+    }
+    if not args.no_cpu_baseline and args.gadget_params == "toy":
+        import oracle
+        from oracle import loss as oloss
+        t1 = time.perf_counter()
+        if loss:        # the row sums couple the classes: the oracle follows the first two samples
+            sub = 2
+            want = oloss.int_ce_loss_deriv_encrypted(p, cts[0].reshape(a, b, -1)[:sub], cts[1].reshape(a, b, -1)[:sub], Gamma, kappa, bsk, ksk)
+            done, same = 5 * sub * b, np.array_equal(slz.to_host_u64(d_out)[:sub], want)
+        else:
+            sub = min(count, 32)
+            want = oloss.weight_update_encrypted(p, cts[0][:sub], cts[1][:sub], alpha, bsk, ksk)
+            done, same = sub, np.array_equal(slz.to_host_u64(d_out)[:sub], want)
+        t2 = time.perf_counter()
+        result["cpu_baseline"] = {"value": done / (t2 - t1), "unit": "PBS+KS/s", "cores": min(oracle.num_threads(), done // (5 if loss else 1)),
+                                  "kind": "oracle", "sample": "the first %d %s" % (sub, "samples" if loss else "weights"),
+                                  "gpu_bit_exact_on_sample": bool(same)}
+    else:
+        result["cpu_baseline"] = None       # one lookup at the 8-bit parameter set is 9e12 multiply-adds in the oracle
+    print(json.dumps(result))
+
+
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -200,7 +277,7 @@ def main():
     ap.add_argument("--generic", action="store_true", help="force the generic multi-kernel path")
     ap.add_argument("--calib-copy", action="store_true",
                     help="also run one plain device copy of 256 MiB (a known-size kernel to scale FETCH_SIZE/WRITE_SIZE by)")
-    ap.add_argument("--gadget", choices=["matmul_rns", "sign_rns", "shift2msbs"], default=None,
+    ap.add_argument("--gadget", choices=["matmul_rns", "sign_rns", "shift2msbs", "loss_deriv", "weight_update"], default=None,
                     help="time a gadget built on the lookup primitive instead of the PBS + keyswitch step")
     ap.add_argument("--gadget-params", choices=["cfg3", "toy"], default="cfg3",
                     help="matmul_rns: the 8-bit parameter set of configuration 3, or the toy set the oracle can follow")
@@ -212,6 +289,8 @@ def main():
         return bench_matmul_rns(args)
     if args.gadget in ("sign_rns", "shift2msbs"):
         return bench_sign_rns(args)
+    if args.gadget in ("loss_deriv", "weight_update"):
+        return bench_loss(args)
 
     import torch
     import synth

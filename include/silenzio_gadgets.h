@@ -119,6 +119,54 @@ int slz_shift2msbs_pm(slz_ctx *ctx, const slz_shift_shape *shape, const uint64_t
                       const void *bsk_prepared_dev, const uint64_t *ksk_dev, uint64_t *y_dev, uint64_t *shift_dev,
                       void *workspace_dev, size_t workspace_bytes, void *hip_stream);
 
+/* ---- Lookup with two encrypted inputs, IntCELossDeriv and the clipped weight update ------------------------------------
+ * Two-input lookup (the paper's multivariate lookup; it gives no packing): x in [0, 2^x_bits) and y in [0, 2^y_bits) with
+ * x_bits + y_bits <= msg_bits are packed as 2^y_bits x + y by a linear combination of the two ciphertexts, then one lookup;
+ * the table is indexed by the packed value.
+ * IntCELossDeriv (the paper's Algorithm of that name, Sec. "Integer Cross-Entropy Loss Derivative"), a rows of b classes:
+ *   1. E = ReLU(logit)                       one lookup (logits signed, big_gamma bits, negatives in the upper half of Z_t)
+ *   2. E = round(2^kappa e^(E - (2^(big_gamma-1) - 1)))      one lookup, ties to even
+ *   3. S = sum of E over the row
+ *   4. E = round((E 2^kappa + 1) / (S + 1))  two-input lookup on 2^sb E + S, ties to even
+ *   5. E = E - label * (sum of E over the row)   the product by a two-input lookup on 2^sb label + sum
+ *   6. sign(E)                               one lookup on E + t / 2, results -1 / 0 / 1 (negatives in the upper half)
+ * with eb = kappa + 1 bits for an exponential and sb = bits of b 2^kappa for a row sum; eb + sb <= msg_bits is required.
+ * Clipped weight update (last step of the paper's Algorithm "End-to-End Training"): clip(W - G) to the signed alpha-bit range
+ * by one two-input lookup on 4 (W + 2^(alpha-1)) + code, W signed with negatives in the upper half of Z_t, code = G + 1 in
+ * {0, 1, 2} (the sign gadget asked for the results 0 / 1 / 2); alpha + 2 <= msg_bits is required. */
+typedef struct {
+    uint32_t a, b;                       /* rows (samples) and classes, b <= 16 */
+    uint32_t big_gamma;                  /* signed bitwidth of the logits, 2..msg_bits */
+    uint32_t kappa;                      /* approximation level of the exponential, >= 1 */
+} slz_loss_shape;
+
+/* Bytes of device workspace slz_bivariate_lookup / slz_weight_update need for count ciphertext pairs. */
+int slz_bivariate_workspace(const slz_ctx *ctx, uint32_t count, size_t *bytes);
+/* x_dev, y_dev, out_dev [count][n+1] under the small key; luts_dev [n_luts][N] accumulator polynomials of tables indexed by
+ * 2^y_bits x + y; lut_index_dev [count] device words, or null to use table 0 for every pair.  out_dev may be x_dev or y_dev.
+ * SLZ_E_INVALID_ARG for null or misaligned pointers, count == 0, y_bits >= msg_bits or a workspace that is too small. */
+int slz_bivariate_lookup(slz_ctx *ctx, const uint64_t *x_dev, const uint64_t *y_dev, uint32_t y_bits, const uint64_t *luts_dev,
+                         const uint32_t *lut_index_dev, uint32_t n_luts, const void *bsk_prepared_dev, const uint64_t *ksk_dev,
+                         uint64_t *out_dev, uint32_t count, void *workspace_dev, size_t workspace_bytes, void *hip_stream);
+
+/* Host, pure.  luts_out [5][N]: the tables of steps 1, 2, 4, 5 and 6 above.  SLZ_E_INVALID_ARG for a shape that does not fit
+ * the message space. */
+int slz_loss_luts(const slz_params *params, const slz_loss_shape *shape, uint64_t *luts_out);
+int slz_loss_workspace(const slz_ctx *ctx, const slz_loss_shape *shape, size_t *bytes);
+/* logits_dev, labels_dev (one-hot, 0 / 1) and e_dev: [a][b][n+1] under the small key; e_dev receives the sign of the error.
+ * Conventions as for slz_matmul_rns. */
+int slz_int_ce_loss_deriv(slz_ctx *ctx, const slz_loss_shape *shape, const uint64_t *logits_dev, const uint64_t *labels_dev,
+                          const uint64_t *luts_dev, const void *bsk_prepared_dev, const uint64_t *ksk_dev, uint64_t *e_dev,
+                          void *workspace_dev, size_t workspace_bytes, void *hip_stream);
+
+/* Host, pure.  luts_out [1][N]: the table 4 (w + 2^(alpha-1)) + code -> clip(w - (code - 1)), signed result encoded in Z_t (code 3
+ * is read as 2).  SLZ_E_INVALID_ARG unless 2 <= alpha and alpha + 2 <= msg_bits. */
+int slz_weight_update_luts(const slz_params *params, uint32_t alpha, uint64_t *luts_out);
+/* w_dev, gcode_dev, w_out_dev [count][n+1]; workspace of slz_bivariate_workspace(count) bytes.  w_out_dev may be w_dev. */
+int slz_weight_update(slz_ctx *ctx, uint32_t alpha, const uint64_t *w_dev, const uint64_t *gcode_dev, const uint64_t *luts_dev,
+                      const void *bsk_prepared_dev, const uint64_t *ksk_dev, uint64_t *w_out_dev, uint32_t count,
+                      void *workspace_dev, size_t workspace_bytes, void *hip_stream);
+
 #ifdef __cplusplus
 }
 #endif

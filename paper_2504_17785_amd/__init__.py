@@ -37,7 +37,9 @@ EXPORTS = ("slz_ctx_create", "slz_ctx_destroy", "slz_ctx_set_option", "slz_lut_e
            "slz_pbs_batch", "slz_blind_rotate_batch", "slz_keyswitch_batch", "slz_lwe_lincomb_batch",
            "slz_pbs_path", "slz_strerror", "slz_matmul_rns_luts", "slz_matmul_rns_workspace", "slz_matmul_rns",
            "slz_rns_luts", "slz_rns_workspace", "slz_rns2mrns", "slz_sign_rns",
-           "slz_shift2msbs_luts", "slz_shift2msbs_workspace", "slz_shift2msbs_plus", "slz_shift2msbs_pm")
+           "slz_shift2msbs_luts", "slz_shift2msbs_workspace", "slz_shift2msbs_plus", "slz_shift2msbs_pm",
+           "slz_bivariate_workspace", "slz_bivariate_lookup", "slz_loss_luts", "slz_loss_workspace", "slz_int_ce_loss_deriv",
+           "slz_weight_update_luts", "slz_weight_update")
 
 
 def lib():
@@ -76,6 +78,13 @@ def lib():
         L.slz_shift2msbs_workspace.argtypes = [vp, ctypes.POINTER(SlzShiftShape), ctypes.POINTER(sz)]
         L.slz_shift2msbs_plus.argtypes = [vp, ctypes.POINTER(SlzShiftShape), vp, vp, vp, vp, vp, vp, vp, sz, vp]
         L.slz_shift2msbs_pm.argtypes = [vp, ctypes.POINTER(SlzShiftShape), vp, vp, vp, vp, vp, vp, vp, sz, vp]
+        L.slz_bivariate_workspace.argtypes = [vp, u32, ctypes.POINTER(sz)]
+        L.slz_bivariate_lookup.argtypes = [vp, vp, vp, u32, vp, vp, u32, vp, vp, vp, u32, vp, sz, vp]
+        L.slz_loss_luts.argtypes = [ctypes.POINTER(SlzParams), ctypes.POINTER(SlzLossShape), vp]
+        L.slz_loss_workspace.argtypes = [vp, ctypes.POINTER(SlzLossShape), ctypes.POINTER(sz)]
+        L.slz_int_ce_loss_deriv.argtypes = [vp, ctypes.POINTER(SlzLossShape), vp, vp, vp, vp, vp, vp, vp, sz, vp]
+        L.slz_weight_update_luts.argtypes = [ctypes.POINTER(SlzParams), u32, vp]
+        L.slz_weight_update.argtypes = [vp, u32, vp, vp, vp, vp, vp, vp, u32, vp, sz, vp]
         L.slz_strerror.argtypes = [ctypes.c_int]
         L.slz_strerror.restype = ctypes.c_char_p
         for name in EXPORTS:
@@ -147,6 +156,28 @@ def shift2msbs_luts(p, m, w: int, gamma: int) -> np.ndarray:
     sh = make_shift_shape(m, 1, w, gamma)
     out = np.empty((sh.k * (sh.k - 1) // 2 + 3 * sh.k + 5, p.N), dtype=np.uint64)
     _check(lib().slz_shift2msbs_luts(ctypes.byref(cp), ctypes.byref(sh), out.ctypes.data), "slz_shift2msbs_luts")
+    return out
+
+
+class SlzLossShape(ctypes.Structure):
+    """slz_loss_shape of include/silenzio_gadgets.h."""
+    _fields_ = [("a", ctypes.c_uint32), ("b", ctypes.c_uint32), ("big_gamma", ctypes.c_uint32), ("kappa", ctypes.c_uint32)]
+
+
+def loss_luts(p, b: int, big_gamma: int, kappa: int) -> np.ndarray:
+    """slz_loss_luts: the five lookup polynomials of IntCELossDeriv, u64 [5][N] (host)."""
+    cp = make_params(p)
+    sh = SlzLossShape(1, b, big_gamma, kappa)
+    out = np.empty((5, p.N), dtype=np.uint64)
+    _check(lib().slz_loss_luts(ctypes.byref(cp), ctypes.byref(sh), out.ctypes.data), "slz_loss_luts")
+    return out
+
+
+def weight_update_luts(p, alpha: int) -> np.ndarray:
+    """slz_weight_update_luts: the lookup polynomial of the clipped weight update, u64 [1][N] (host)."""
+    cp = make_params(p)
+    out = np.empty((1, p.N), dtype=np.uint64)
+    _check(lib().slz_weight_update_luts(ctypes.byref(cp), alpha, out.ctypes.data), "slz_weight_update_luts")
     return out
 
 
@@ -334,6 +365,54 @@ class Context:
                "slz_shift2msbs")
         torch.cuda.current_stream().synchronize()     # the workspace is released when this returns
         return y, shift
+
+    def _bivariate_ws(self, count: int, device):
+        import torch
+        need = ctypes.c_size_t(0)
+        _check(lib().slz_bivariate_workspace(self._h, count, ctypes.byref(need)), "slz_bivariate_workspace")
+        return torch.empty(need.value, dtype=torch.uint8, device=device), need.value
+
+    def bivariate_lookup(self, x_cts, y_cts, y_bits: int, luts, bsk_prepared, ksk, lut_index=None):
+        """slz_bivariate_lookup: [count][n+1] pairs -> [count][n+1], one lookup each on 2^y_bits x + y."""
+        import torch
+        count = x_cts.shape[0]
+        ws, need = self._bivariate_ws(count, x_cts.device)
+        out = torch.empty((count, self.p.n + 1), dtype=torch.int64, device=x_cts.device)
+        if lut_index is not None and (lut_index.dtype != torch.int32 or not lut_index.is_cuda or not lut_index.is_contiguous()):
+            raise TypeError("lut_index: need a contiguous int32 CUDA tensor")
+        _check(lib().slz_bivariate_lookup(self._h, _dev_u64(x_cts, "x_cts"), _dev_u64(y_cts, "y_cts"), y_bits, _dev_u64(luts, "luts"),
+                                          None if lut_index is None else lut_index.data_ptr(), luts.shape[0],
+                                          bsk_prepared.data_ptr(), _dev_u64(ksk, "ksk"), _dev_u64(out, "out"), count, ws.data_ptr(),
+                                          need, _stream()), "slz_bivariate_lookup")
+        torch.cuda.current_stream().synchronize()     # the workspace is released when this returns
+        return out
+
+    def int_ce_loss_deriv(self, logits, labels, big_gamma: int, kappa: int, luts, bsk_prepared, ksk):
+        """slz_int_ce_loss_deriv: logits and one-hot labels [a][b][n+1] -> the sign of the error [a][b][n+1]."""
+        import torch
+        a, b = logits.shape[:2]
+        sh = SlzLossShape(a, b, big_gamma, kappa)
+        need = ctypes.c_size_t(0)
+        _check(lib().slz_loss_workspace(self._h, ctypes.byref(sh), ctypes.byref(need)), "slz_loss_workspace")
+        ws = torch.empty(need.value, dtype=torch.uint8, device=logits.device)
+        out = torch.empty((a, b, self.p.n + 1), dtype=torch.int64, device=logits.device)
+        _check(lib().slz_int_ce_loss_deriv(self._h, ctypes.byref(sh), _dev_u64(logits, "logits"), _dev_u64(labels, "labels"),
+                                           _dev_u64(luts, "luts"), bsk_prepared.data_ptr(), _dev_u64(ksk, "ksk"), _dev_u64(out, "out"),
+                                           ws.data_ptr(), need.value, _stream()), "slz_int_ce_loss_deriv")
+        torch.cuda.current_stream().synchronize()     # the workspace is released when this returns
+        return out
+
+    def weight_update(self, w_cts, gcode_cts, alpha: int, luts, bsk_prepared, ksk):
+        """slz_weight_update: weights and codes G + 1, [count][n+1] each -> clip(W - G), [count][n+1]."""
+        import torch
+        count = w_cts.shape[0]
+        ws, need = self._bivariate_ws(count, w_cts.device)
+        out = torch.empty((count, self.p.n + 1), dtype=torch.int64, device=w_cts.device)
+        _check(lib().slz_weight_update(self._h, alpha, _dev_u64(w_cts, "w_cts"), _dev_u64(gcode_cts, "gcode_cts"), _dev_u64(luts, "luts"),
+                                       bsk_prepared.data_ptr(), _dev_u64(ksk, "ksk"), _dev_u64(out, "out"), count, ws.data_ptr(), need,
+                                       _stream()), "slz_weight_update")
+        torch.cuda.current_stream().synchronize()     # the workspace is released when this returns
+        return out
 
     def lwe_lincomb_batch(self, cts, w, out=None):
         import torch

@@ -1,10 +1,8 @@
 // Matmul^RNS (the paper's Algorithm "Matmul^RNS") on LWE ciphertexts: three rounds of table lookups
 // (slz_pbs_batch + slz_keyswitch_batch) joined by element-wise kernels on ciphertext vectors.
-#include "slz_internal.h"
+#include "slz_gadget_util.h"
 #include "../../include/silenzio_gadgets.h"
 #include <vector>
-
-#define MR_THREADS 256
 
 static bool shape_ok(const slz_params *p, const slz_matmul_rns_shape *sh) {
     if (!p || !sh || sh->k == 0 || sh->k > SLZ_MATMUL_RNS_MAX_K || sh->a == 0 || sh->b == 0 || sh->c == 0) return false;
@@ -39,8 +37,6 @@ struct mr_plan {
     // offsets in bytes
     size_t o_rep, o_idx, o_big, o_res, o_packed, o_ys, o_sums, o_wts, o_tmp, total;
 };
-
-static size_t up256(size_t x) { return (x + 255) / 256 * 256; }
 
 static mr_plan make_plan(const slz_ctx *ctx, const slz_matmul_rns_shape *sh) {
     mr_plan P;
@@ -129,22 +125,9 @@ k_mr_accumulate(const uint64_t *__restrict__ y, const uint64_t *__restrict__ sum
     }
 }
 
-static dim3 ew_grid(size_t total) {
-    size_t blocks = (total + MR_THREADS - 1) / MR_THREADS;
-    return dim3((unsigned)(blocks < 65536 ? (blocks ? blocks : 1) : 65536));
-}
-
-// one table lookup per ciphertext, in chunks the context can hold
 static int lookup(slz_ctx *ctx, const mr_plan &P, const uint64_t *in, const uint64_t *luts, const uint32_t *idx, uint32_t n_luts,
                   const void *bskp, const uint64_t *ksk, uint64_t *big, uint64_t *out, size_t count, void *stream) {
-    for (size_t c0 = 0; c0 < count; c0 += P.chunk) {
-        const uint32_t nb = (uint32_t)(count - c0 < P.chunk ? count - c0 : P.chunk);
-        int rc = slz_pbs_batch(ctx, in + c0 * P.n1, luts, idx + c0, n_luts, bskp, big, nb, stream);
-        if (rc != SLZ_OK) return rc;
-        rc = slz_keyswitch_batch(ctx, big, ksk, out + c0 * P.n1, nb, stream);
-        if (rc != SLZ_OK) return rc;
-    }
-    return SLZ_OK;
+    return lookup_n(ctx, P.chunk, P.n1, in, luts, idx, n_luts, bskp, ksk, big, out, count, stream);
 }
 
 extern "C" int slz_matmul_rns(slz_ctx *ctx, const slz_matmul_rns_shape *sh, const uint64_t *x, const uint64_t *w, const uint64_t *luts,
@@ -301,18 +284,6 @@ k_rns_sign_pack(const uint64_t *__restrict__ y, const uint64_t *__restrict__ neg
         for (uint32_t i = 0; i < k; i++) v += y[(size_t)i * total + gid];
         tmp[gid] = v;
     }
-}
-
-static int lookup_n(slz_ctx *ctx, size_t chunk, size_t n1, const uint64_t *in, const uint64_t *luts, const uint32_t *idx, uint32_t n_luts,
-                    const void *bskp, const uint64_t *ksk, uint64_t *big, uint64_t *out, size_t count, void *stream) {
-    for (size_t c0 = 0; c0 < count; c0 += chunk) {
-        const uint32_t nb = (uint32_t)(count - c0 < chunk ? count - c0 : chunk);
-        int rc = slz_pbs_batch(ctx, in + c0 * n1, luts, idx ? idx + c0 : nullptr, n_luts, bskp, big, nb, stream);
-        if (rc != SLZ_OK) return rc;
-        rc = slz_keyswitch_batch(ctx, big, ksk, out + c0 * n1, nb, stream);
-        if (rc != SLZ_OK) return rc;
-    }
-    return SLZ_OK;
 }
 
 static int rns_args_ok(slz_ctx *ctx, const slz_rns_shape *sh, const void *x, const void *luts, const void *bskp, const void *ksk,

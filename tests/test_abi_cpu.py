@@ -115,3 +115,21 @@ def test_shift2msbs_luts_match_oracle_tables(orc):
         slz.shift2msbs_luts(p, (15, 14), 5, 5)            # only 4-bit digits
     with pytest.raises(slz.SlzError):
         slz.shift2msbs_luts(p, (15, 14), 4, 8)            # the output must fit 7 bits
+
+
+def test_loss_and_weight_update_luts_match_oracle_tables(orc):
+    from oracle import loss
+    base = dict(n=4, k=1, N=2048, pbs_base_log=23, pbs_level=1, ks_base_log=4, ks_level=8, sigma_lwe=2.0 ** -40, sigma_bsk=2.0 ** -50,
+                batch=1, n_luts=1, seed=1)
+    for bits, cases in ((8, ((7, 7, 2), (2, 7, 2), (16, 7, 1), (3, 4, 2), (5, 8, 2))), (9, ((3, 7, 3), (2, 9, 2))), (6, ((3, 5, 1),))):
+        p = synth.Params(name="t", msg_bits=bits, **base)
+        for b, Gamma, kappa in cases:
+            assert np.array_equal(slz.loss_luts(p, b, Gamma, kappa), orc.lut_encode(p, loss.loss_tables(p, b, Gamma, kappa)))
+        for alpha in range(2, bits - 1):
+            assert np.array_equal(slz.weight_update_luts(p, alpha), orc.lut_encode(p, loss.weight_update_table(p, alpha)))
+        with pytest.raises(slz.SlzError):
+            slz.weight_update_luts(p, bits - 1)
+    p = synth.Params(name="t", msg_bits=8, **base)
+    for bad in ((3, 7, 4), (17, 7, 1), (3, 9, 2), (3, 1, 2), (3, 7, 0)):       # too wide, too many classes, Gamma out of range, kappa 0
+        with pytest.raises(slz.SlzError):
+            slz.loss_luts(p, *bad)
