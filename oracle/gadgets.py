@@ -1,4 +1,5 @@
-"""CPU oracle of the paper's Matmul^RNS (Algorithm "Matmul^RNS", Sec. "Low-bitwidth Matrix Multiplication").
+"""CPU oracle of the paper's Matmul^RNS (Algorithm "Matmul^RNS", Sec. "Low-bitwidth Matrix Multiplication"), and further down
+of RNS2MRNS, Sign^RNS, Shift2MSBs^+/+- and MatmulHighRes^RNS (each section has its own header).
 
 TEST INFRASTRUCTURE ONLY: imported by tests/ and by bench.py's cpu_baseline leg; the GPU library never imports it.
 
@@ -409,3 +410,106 @@ def shift2msbs_pm_encrypted(p, x_cts, m, w: int, Gamma: int, bsk, ksk):
     with np.errstate(over="ignore"):
         Y = _lookup(p, flag * np.uint64(128) + Yp, pt[k:], np.zeros(count, dtype=np.uint32), bsk, ksk)
     return Y, shift
+
+
+# ---------------------------------------------------------------------------------------------------------------------
+# MatmulHighRes^RNS (Algorithm "MatmulHighRes^RNS", appendix "Low-bitwidth high-resolution MatMul"): the product modulo a base
+# of 5-bit moduli, every intermediate still within 8 bits.
+#
+# Readings of points the paper leaves open:
+#   R15 extractBits(X', [3, 4]) is (X' >> 3) & 3 and extractBits(X', [0, 2]) is X' & 7, one lookup each on the residue (the
+#       paper uses the bit extraction as a black box).  The two expandDims lines of step 3 are read as acting on X_1' and X_2'.
+#   R16 Y_1* = X_1' W' mod m'' is one two-input lookup on 32 x_1 + w (3 + 5 bits); Y_2* = X_2' W' is one two-input lookup on
+#       32 x_2 + w returning the plain product (at most 3 * 31 = 93), followed by the custom lookup v -> 8 v mod m_i the paper
+#       names; step 4 reduces Y_1* + Y_2* (at most 2 * 30) by one more lookup.
+#   R17 Step 5 as R3: the slices summed are those of Y*, and Y + Y' <= 30 + 7 * 30 = 240 is reduced by one lookup.
+RNS_BASES_5BIT = {2: (31, 30), 3: (29, 31, 30), 4: (27, 29, 31, 28), 5: (25, 27, 29, 31, 28), 6: (23, 25, 27, 29, 31, 28)}
+BLOCK_HIGHRES = 7
+
+
+def matmul_highres_clear(X, W, m) -> np.ndarray:
+    """Algorithm "MatmulHighRes^RNS" on clear integers.  X: a x b, W: b x c (signed), m: k moduli below 32.  Returns k x a x c."""
+    X = np.asarray(X, dtype=np.int64)
+    W = np.asarray(W, dtype=np.int64)
+    m = np.asarray(m, dtype=np.int64)
+    b = X.shape[1]
+    mp, mpp = m[:, None, None], m[:, None, None, None]
+    # Step 1: inputs to RNS representation
+    Xr = np.mod(X[None], mp)
+    Wr = np.mod(W[None], mp)
+    # Step 2: bit chunks of X'
+    X2 = (Xr >> 3) & 3
+    X1 = Xr & 7
+    # Step 3: partial products
+    Y1 = np.mod(X1[:, :, :, None] * Wr[:, None, :, :], mpp)
+    Y2 = X2[:, :, :, None] * Wr[:, None, :, :]
+    assert int(Y2.max()) < 128
+    Y2 = np.mod(Y2 * 8, mpp)
+    # Step 4: add the partial products
+    Ys = np.mod(Y1 + Y2, mpp)
+    # Step 5: block-wise summation
+    n = min(BLOCK_HIGHRES, b)
+    Y = np.mod(Ys[:, :, :n, :].sum(axis=2), mp)
+    i = n
+    while i < b:
+        j = min(i + n, b)
+        Yp = Ys[:, :, i:j, :].sum(axis=2)
+        assert int((Y + Yp).max()) < 256
+        Y = np.mod(Y + Yp, mp)
+        i += n
+    return Y
+
+
+def highres_tables(p, m) -> np.ndarray:
+    """The 4k + 3 lookup tables over Z_t (t >= 256): k of v -> signed(v) mod m_i, k of u -> (u >> 5)(u & 31) mod m_i, k of
+    v -> 8 v mod m_i, k of v -> v mod m_i, then v -> (v >> 3) & 3, v -> v & 7 and u -> (u >> 5)(u & 31)."""
+    t = 1 << p.msg_bits
+    if t < 256:
+        raise ValueError("MatmulHighRes^RNS needs an 8-bit message space")
+    v = np.arange(t, dtype=np.int64)
+    inside = v < 256
+    prod = np.where(inside, (v >> 5) * (v & 31), 0)
+    tabs = [np.mod(signed_decode(v, t), q) for q in m]
+    tabs += [np.where(inside, np.mod(prod, q), 0) for q in m]
+    tabs += [np.mod(8 * v, q) for q in m]
+    tabs += [np.mod(v, q) for q in m]
+    tabs += [(v >> 3) & 3, v & 7, prod]
+    return np.stack(tabs).astype(np.uint64)
+
+
+def matmul_highres_encrypted(p, x_cts, w_cts, m, bsk, ksk) -> np.ndarray:
+    """Algorithm "MatmulHighRes^RNS" on ciphertexts.  x_cts: a x b x (n+1), w_cts: b x c x (n+1), encryptions of signed 8-bit values
+    (R1).  Returns k x a x c x (n+1) encryptions of the residues of X W."""
+    m = [int(q) for q in m]
+    k = len(m)
+    a, b = x_cts.shape[:2]
+    c = w_cts.shape[1]
+    tabs = highres_tables(p, m)
+    kk = np.arange(k, dtype=np.uint32)
+    one = lambda shape, i: np.full(shape, i, dtype=np.uint32)
+    # Step 1
+    Xr = _lookup(p, np.broadcast_to(x_cts[None], (k, a, b, p.n + 1)), tabs, np.broadcast_to(kk[:, None, None], (k, a, b)), bsk, ksk)
+    Wr = _lookup(p, np.broadcast_to(w_cts[None], (k, b, c, p.n + 1)), tabs, np.broadcast_to(kk[:, None, None], (k, b, c)), bsk, ksk)
+    # Step 2 (R15)
+    X2 = _lookup(p, Xr, tabs, one((k, a, b), 4 * k), bsk, ksk)
+    X1 = _lookup(p, Xr, tabs, one((k, a, b), 4 * k + 1), bsk, ksk)
+    # Step 3 (R16)
+    per_mod = np.broadcast_to(kk[:, None, None, None], (k, a, b, c))
+    with np.errstate(over="ignore"):
+        Y1 = _lookup(p, X1[:, :, :, None, :] * np.uint64(32) + Wr[:, None, :, :, :], tabs, k + per_mod, bsk, ksk)
+        Y2 = _lookup(p, X2[:, :, :, None, :] * np.uint64(32) + Wr[:, None, :, :, :], tabs, one((k, a, b, c), 4 * k + 2), bsk, ksk)
+    Y2 = _lookup(p, Y2, tabs, 2 * k + per_mod, bsk, ksk)
+    # Step 4
+    with np.errstate(over="ignore"):
+        Ys = _lookup(p, Y1 + Y2, tabs, 3 * k + per_mod, bsk, ksk)
+    # Step 5 (R17)
+    idx = 3 * k + np.broadcast_to(kk[:, None, None], (k, a, c))
+    n = min(BLOCK_HIGHRES, b)
+    with np.errstate(over="ignore"):
+        Y = _lookup(p, Ys[:, :, :n, :, :].sum(axis=2, dtype=np.uint64), tabs, idx, bsk, ksk)
+        i = n
+        while i < b:
+            j = min(i + n, b)
+            Y = _lookup(p, Y + Ys[:, :, i:j, :, :].sum(axis=2, dtype=np.uint64), tabs, idx, bsk, ksk)
+            i += n
+    return Y

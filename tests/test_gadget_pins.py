@@ -299,3 +299,86 @@ def test_encrypted_shift2msbs_decrypts_to_the_clear_clone(orc, gd):
     assert np.array_equal(gd.signed_decode(got.astype(np.int64), 256), want)
     sh, _ = orc.decode(orc.lwe_phase(keys.lwe_sk, shift[None]), p.msg_bits)
     assert int(gd.signed_decode(sh.astype(np.int64), 256)[0]) == want_shift
+
+
+# ---- MatmulHighRes^RNS -------------------------------------------------------------------------------------------------
+def test_5bit_rns_bases_match_the_printed_table(gd):
+    rows = _rows("rns_bases_5bit.txt")
+    assert len(rows) == len(gd.RNS_BASES_5BIT) == 5
+    for row in rows:
+        k, base, bits = [f.strip() for f in row.split("|")]
+        base = tuple(int(x) for x in base.split())
+        assert gd.RNS_BASES_5BIT[int(k)] == base and len(base) == int(k)
+        assert abs(gd.rns_base_bitwidth(base) - float(bits)) < 0.011
+        assert all(16 < q < 32 for q in base)
+        assert all(math.gcd(p, q) == 1 for i, p in enumerate(base) for q in base[i + 1:])
+        assert base[-1] % 2 == 0
+
+
+@pytest.mark.parametrize("a,b,c,k", [(2, 3, 2, 2), (3, 7, 2, 3), (2, 8, 3, 4), (1, 40, 2, 6), (4, 15, 1, 5)])
+def test_highres_clear_clone_is_the_integer_product_modulo_each_modulus(gd, a, b, c, k):
+    m = gd.RNS_BASES_5BIT[k]
+    X = _rand_int8(7 * a + b, "lin_inputs", (a, b))
+    W = _rand_int8(7 * a + b, "weights", (b, c))
+    Y = gd.matmul_highres_clear(X, W, m)
+    assert Y.shape == (k, a, c)
+    for i, q in enumerate(m):
+        assert np.array_equal(Y[i], np.mod(X @ W, q))
+    M = math.prod(m)
+    assert np.array_equal(gd.crt_reconstruct(Y, m), gd.signed_decode(np.mod(X @ W, M), M))
+
+
+def test_highres_against_brute_force_and_at_the_extremes(gd):
+    m = (29, 31, 30)
+    X = _rand_int8(3, "lin_inputs", (2, 9))
+    W = _rand_int8(3, "weights", (9, 2))
+    Y = gd.matmul_highres_clear(X, W, m)
+    for i, q in enumerate(m):
+        for r in range(2):
+            for s in range(2):
+                assert int(Y[i, r, s]) == sum(int(X[r, j]) * int(W[j, s]) for j in range(9)) % q
+    # all-extreme inputs: the clone's own asserts check that no intermediate leaves 8 bits
+    for xv, wv in ((-128, -128), (127, 127), (-1, -1), (127, -128)):
+        X = np.full((1, 30), xv); W = np.full((30, 1), wv)
+        for base in gd.RNS_BASES_5BIT.values():
+            Y = gd.matmul_highres_clear(X, W, base)
+            assert [int(v) for v in Y[:, 0, 0]] == [(30 * xv * wv) % q for q in base]
+
+
+def test_highres_tables(gd):
+    p = Params(name="gadget_toy", n=4, k=1, N=2048, pbs_base_log=23, pbs_level=1, ks_base_log=4, ks_level=8, msg_bits=8,
+               sigma_lwe=2.0 ** -40, sigma_bsk=2.0 ** -50, batch=1, n_luts=1, seed=99)
+    m = (29, 31, 30)
+    tabs = gd.highres_tables(p, m).astype(np.int64)
+    assert tabs.shape == (15, 256)
+    for i, q in enumerate(m):
+        assert tabs[i, 255] == (-1) % q and tabs[i, 128] == (-128) % q and tabs[i, 127] == 127 % q
+        for x in range(8):
+            for w in range(32):
+                assert tabs[3 + i, 32 * x + w] == (x * w) % q
+        assert [int(v) for v in tabs[6 + i, :100]] == [(8 * v) % q for v in range(100)]
+        assert [int(v) for v in tabs[9 + i]] == [v % q for v in range(256)]
+    for v in range(32):
+        assert tabs[12, v] == v >> 3 and tabs[13, v] == v % 8 and 8 * tabs[12, v] + tabs[13, v] == v
+    for x in range(4):
+        for w in range(32):
+            assert tabs[14, 32 * x + w] == x * w
+
+
+def test_encrypted_highres_decrypts_to_the_clear_clone(orc, gd):
+    p = Params(name="gadget_toy", n=4, k=1, N=2048, pbs_base_log=23, pbs_level=1, ks_base_log=4, ks_level=8, msg_bits=8,
+               sigma_lwe=2.0 ** -40, sigma_bsk=2.0 ** -50, batch=1, n_luts=1, seed=0x6AD6E7)
+    keys = orc.Keys(p, synth)
+    m = (29, 31, 30)
+    a, b, c = 2, 9, 1                                       # two blocks in step 5: 7 + 2
+    X = _rand_int8(p.seed, "lin_inputs", (a, b))
+    W = _rand_int8(p.seed, "weights", (b, c))
+    X[0, 0], W[0, 0], X[1, 1], W[1, 0] = -128, -128, 127, -1
+    x_cts = orc.encrypt_messages(p, synth, keys.lwe_sk, gd.signed_encode(X, 256).reshape(-1).astype(np.uint64)).reshape(a, b, p.n + 1)
+    w_cts = orc.encrypt_messages(p, synth, keys.lwe_sk, gd.signed_encode(W, 256).reshape(-1).astype(np.uint64), offset=a * b).reshape(b, c, p.n + 1)
+    Y = gd.matmul_highres_encrypted(p, x_cts, w_cts, m, keys.bsk, keys.ksk)
+    got, err = orc.decode(orc.lwe_phase(keys.lwe_sk, Y.reshape(-1, p.n + 1)), p.msg_bits)
+    want = gd.matmul_highres_clear(X, W, m)
+    assert np.array_equal(got.reshape(want.shape).astype(np.int64), want)
+    assert np.array_equal(want, np.mod((X @ W)[None], np.array(m)[:, None, None]))
+    assert float(np.abs(err).max()) < 2.0 ** -12
