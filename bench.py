@@ -38,7 +38,8 @@ def alu_model_ops_per_pbs(p) -> float:
 def bench_matmul_rns(args):
     """One step = one Matmul^RNS (the paper's Algorithm "Matmul^RNS") of an encrypted 8 x 28 by an encrypted 28 x 8 matrix
     (the paper's batch of 8 and the first dense layer of its 28-8-2 network) over the moduli {7, 11, 13}: 7 104 table
-    lookups in three dependent rounds plus the leveled sums.  Key and ciphertext material is uniform random words."""
+    lookups in three dependent rounds plus the leveled sums.  --gadget matmul_highres: the same product by
+    MatmulHighRes^RNS over the 5-bit moduli {29, 31, 30}.  Key and ciphertext material is uniform random words."""
     import torch
     import synth
     import paper_2504_17785_amd as slz
@@ -49,10 +50,19 @@ def bench_matmul_rns(args):
         p = synth.Params(name="gadget_toy", n=4, k=1, N=2048, pbs_base_log=23, pbs_level=1, ks_base_log=4, ks_level=8,
                          msg_bits=8, sigma_lwe=2.0 ** -40, sigma_bsk=2.0 ** -50, batch=1, n_luts=1, seed=0x6AD6E7)
         max_batch = 8192
-    a, b, c, m = 8, 28, 8, (7, 11, 13)
+    highres = args.gadget == "matmul_highres"
+    a, b, c, m = 8, 28, 8, ((29, 31, 30) if highres else (7, 11, 13))
     k = len(m)
-    nblk = (b + 14) // 15
-    lookups = k * (a * b + b * c) + k * a * b * c + k * a * c * nblk
+    if highres:     # residues, two bit chunks of X', four lookups per product, blocks of 7
+        nblk = (b + 6) // 7
+        lookups = k * (a * b + b * c) + 2 * k * a * b + 4 * k * a * b * c + k * a * c * nblk
+        sub = k * (b + b) + 2 * k * b + 4 * k * b + k * nblk        # lookups behind one output entry
+        rounds = 6 + nblk
+    else:
+        nblk = (b + 14) // 15
+        lookups = k * (a * b + b * c) + k * a * b * c + k * a * c * nblk
+        sub = k * (b + b) + k * b + k * nblk
+        rounds = 2 + nblk
     torch.cuda.set_device(0)
     ctx = slz.Context(p, max_batch)
     R, C = (p.k + 1) * p.pbs_level, p.k + 1
@@ -64,23 +74,23 @@ def bench_matmul_rns(args):
     d_bskp = ctx.bsk_prepare(d_std)
     del d_std
     d_ksk, d_x, d_w = slz.to_device_u64(ksk), slz.to_device_u64(x_cts), slz.to_device_u64(w_cts)
-    d_luts = slz.to_device_u64(slz.matmul_rns_luts(p, m, a, b, c))
+    d_luts = slz.to_device_u64((slz.matmul_highres_luts if highres else slz.matmul_rns_luts)(p, m, a, b, c))
     d_y = torch.empty((k, a, c, p.n + 1), dtype=torch.int64, device="cuda")
     for _ in range(args.warmup):
-        ctx.matmul_rns(d_x, d_w, m, d_luts, d_bskp, d_ksk, out=d_y)
+        ctx.matmul_rns(d_x, d_w, m, d_luts, d_bskp, d_ksk, out=d_y, highres=highres)
     torch.cuda.synchronize()
     t0 = time.perf_counter()
     for _ in range(args.steps):
-        ctx.matmul_rns(d_x, d_w, m, d_luts, d_bskp, d_ksk, out=d_y)
+        ctx.matmul_rns(d_x, d_w, m, d_luts, d_bskp, d_ksk, out=d_y, highres=highres)
     torch.cuda.synchronize()
     ms = (time.perf_counter() - t0) * 1e3 / args.steps
     achieved = lookups * alu_model_ops_per_pbs(p) / (ms * 1e-3) / 1e12
     result = {
-        "metric": "matmul_rns_lookups_per_s", "value": lookups / (ms * 1e-3), "unit": "PBS+KS/s",
+        "metric": "%s_lookups_per_s" % args.gadget, "value": lookups / (ms * 1e-3), "unit": "PBS+KS/s",
         "n_gpus": 1, "steps": args.steps, "warmup": args.warmup, "ms_per_step": ms,
         "higher_is_better": True, "scaling": "weak", "vs_baseline": None, "dtype": "u64", "data": "synthetic",
-        "config": {"workload": "matmul_rns %dx%d by %dx%d over moduli %s at %s: %d lookups in %d dependent rounds" % (
-            a, b, b, c, list(m), p.name, lookups, 2 + nblk), "path": ctx.path},
+        "config": {"workload": "%s %dx%d by %dx%d over moduli %s at %s: %d lookups in %d dependent rounds" % (
+            args.gadget, a, b, b, c, list(m), p.name, lookups, rounds), "path": ctx.path},
         "roofline": {"bound": "alu", "kernel": "blind rotation inside the lookups (whole gadget timed)", "achieved": achieved,
                      "peak": PEAK_ALU_TINSTR, "unit": "Tinstr/s", "frac": achieved / PEAK_ALU_TINSTR, "traffic": None},
     }
@@ -89,9 +99,8 @@ def bench_matmul_rns(args):
         import oracle
         from oracle import gadgets
         t1 = time.perf_counter()
-        want = gadgets.matmul_rns_encrypted(p, x_cts[:1], w_cts[:, :1], m, bsk, ksk)
+        want = (gadgets.matmul_highres_encrypted if highres else gadgets.matmul_rns_encrypted)(p, x_cts[:1], w_cts[:, :1], m, bsk, ksk)
         t2 = time.perf_counter()
-        sub = k * (b + b) + k * b + k * nblk
         got = slz.to_host_u64(d_y)[:, :1, :1]
         result["cpu_baseline"] = {"value": sub / (t2 - t1), "unit": "PBS+KS/s", "cores": min(oracle.num_threads(), k * b),
                                   "kind": "oracle", "sample": "output entry (0, 0) of the product: %d of the %d lookups" % (sub, lookups),
@@ -277,7 +286,7 @@ def main():
     ap.add_argument("--generic", action="store_true", help="force the generic multi-kernel path")
     ap.add_argument("--calib-copy", action="store_true",
                     help="also run one plain device copy of 256 MiB (a known-size kernel to scale FETCH_SIZE/WRITE_SIZE by)")
-    ap.add_argument("--gadget", choices=["matmul_rns", "sign_rns", "shift2msbs", "loss_deriv", "weight_update"], default=None,
+    ap.add_argument("--gadget", choices=["matmul_rns", "matmul_highres", "sign_rns", "shift2msbs", "loss_deriv", "weight_update"], default=None,
                     help="time a gadget built on the lookup primitive instead of the PBS + keyswitch step")
     ap.add_argument("--gadget-params", choices=["cfg3", "toy"], default="cfg3",
                     help="matmul_rns: the 8-bit parameter set of configuration 3, or the toy set the oracle can follow")
@@ -285,7 +294,7 @@ def main():
     if args.gpus != 1:
         print("bench.py measures one GPU only (this build has no multi-GPU path); run with --gpus 1", file=sys.stderr)
         sys.exit(2)
-    if args.gadget == "matmul_rns":
+    if args.gadget in ("matmul_rns", "matmul_highres"):
         return bench_matmul_rns(args)
     if args.gadget in ("sign_rns", "shift2msbs"):
         return bench_sign_rns(args)

@@ -49,6 +49,26 @@ int slz_matmul_rns(slz_ctx *ctx, const slz_matmul_rns_shape *shape, const uint64
                    const uint64_t *luts_dev, const void *bsk_prepared_dev, const uint64_t *ksk_dev, uint64_t *y_dev,
                    void *workspace_dev, size_t workspace_bytes, void *hip_stream);
 
+/* ---- MatmulHighRes^RNS (the paper's Algorithm of that name, appendix "Low-bitwidth high-resolution MatMul") -------------------
+ * The same product modulo a base of 5-bit moduli (every modulus in [2, 32]) with every intermediate still within 8 bits:
+ *   1. X' = X mod m', W' = W mod m'                         one lookup per entry and modulus
+ *   2. X2' = bits 3..4 of X', X1' = bits 0..2 of X'          one lookup each
+ *   3. Y1* = X1' W' mod m (two-input lookup on 32 x1 + w);  Y2* = X2' W' (two-input lookup on 32 x2 + w, the plain product),
+ *      then the lookup v -> 8 v mod m
+ *   4. Y* = (Y1* + Y2*) mod m                                one lookup per product
+ *   5. sums of at most 7 entries, each running sum reduced modulo m_i by one lookup.
+ * The shape struct is the one of slz_matmul_rns; conventions are the same. */
+#define SLZ_MATMUL_HIGHRES_BLOCK 7     /* summands per sub-sum in step 5 */
+
+/* Host, pure.  luts_out [4k + 3][N]: k tables v -> signed(v) mod m_i, k tables u -> (u >> 5)(u & 31) mod m_i (u < 256),
+ * k tables v -> 8 v mod m_i, k tables v -> v mod m_i, then v -> (v >> 3) & 3, v -> v & 7 and u -> (u >> 5)(u & 31). */
+int slz_matmul_highres_luts(const slz_params *params, const slz_matmul_rns_shape *shape, uint64_t *luts_out);
+int slz_matmul_highres_workspace(const slz_ctx *ctx, const slz_matmul_rns_shape *shape, size_t *bytes);
+/* Arguments as for slz_matmul_rns, with luts_dev the polynomials of slz_matmul_highres_luts. */
+int slz_matmul_highres(slz_ctx *ctx, const slz_matmul_rns_shape *shape, const uint64_t *x_dev, const uint64_t *w_dev,
+                       const uint64_t *luts_dev, const void *bsk_prepared_dev, const uint64_t *ksk_dev, uint64_t *y_dev,
+                       void *workspace_dev, size_t workspace_bytes, void *hip_stream);
+
 /* ---- RNS-to-MRNS conversion (the paper's Algorithm "RNS2MRNS") and sign determination (Sec. "Sign Determination in
  * RNS") on encrypted residues ---------------------------------------------------------------------------------------
  * A number x of Z_M, M = m_1 .. m_k, is given as k ciphertexts of its residues x_i = x mod m_i (all in the context's

@@ -39,7 +39,8 @@ EXPORTS = ("slz_ctx_create", "slz_ctx_destroy", "slz_ctx_set_option", "slz_lut_e
            "slz_rns_luts", "slz_rns_workspace", "slz_rns2mrns", "slz_sign_rns",
            "slz_shift2msbs_luts", "slz_shift2msbs_workspace", "slz_shift2msbs_plus", "slz_shift2msbs_pm",
            "slz_bivariate_workspace", "slz_bivariate_lookup", "slz_loss_luts", "slz_loss_workspace", "slz_int_ce_loss_deriv",
-           "slz_weight_update_luts", "slz_weight_update")
+           "slz_weight_update_luts", "slz_weight_update",
+           "slz_matmul_highres_luts", "slz_matmul_highres_workspace", "slz_matmul_highres")
 
 
 def lib():
@@ -70,6 +71,9 @@ def lib():
         L.slz_matmul_rns_workspace.argtypes = [vp, ctypes.POINTER(SlzMatmulRnsShape), ctypes.POINTER(sz)]
         L.slz_matmul_rns.argtypes = [vp, ctypes.POINTER(SlzMatmulRnsShape), vp, vp, vp, vp, vp, vp, vp, sz, vp]
         i32 = ctypes.c_int32
+        L.slz_matmul_highres_luts.argtypes = L.slz_matmul_rns_luts.argtypes
+        L.slz_matmul_highres_workspace.argtypes = L.slz_matmul_rns_workspace.argtypes
+        L.slz_matmul_highres.argtypes = L.slz_matmul_rns.argtypes
         L.slz_rns_luts.argtypes = [ctypes.POINTER(SlzParams), ctypes.POINTER(SlzRnsShape), i32, i32, i32, vp]
         L.slz_rns_workspace.argtypes = [vp, ctypes.POINTER(SlzRnsShape), ctypes.POINTER(sz)]
         L.slz_rns2mrns.argtypes = [vp, ctypes.POINTER(SlzRnsShape), vp, vp, vp, vp, vp, vp, sz, vp]
@@ -113,6 +117,15 @@ def matmul_rns_luts(p, m, a: int, b: int, c: int) -> np.ndarray:
     sh = make_matmul_rns_shape(m, a, b, c)
     out = np.empty((3 * sh.k, p.N), dtype=np.uint64)
     _check(lib().slz_matmul_rns_luts(ctypes.byref(cp), ctypes.byref(sh), out.ctypes.data), "slz_matmul_rns_luts")
+    return out
+
+
+def matmul_highres_luts(p, m, a: int, b: int, c: int) -> np.ndarray:
+    """slz_matmul_highres_luts: the 4k + 3 lookup polynomials of MatmulHighRes^RNS, u64 [4k + 3][N] (host)."""
+    cp = make_params(p)
+    sh = make_matmul_rns_shape(m, a, b, c)
+    out = np.empty((4 * sh.k + 3, p.N), dtype=np.uint64)
+    _check(lib().slz_matmul_highres_luts(ctypes.byref(cp), ctypes.byref(sh), out.ctypes.data), "slz_matmul_highres_luts")
     return out
 
 
@@ -306,20 +319,23 @@ class Context:
                                          batch, _stream()), "slz_keyswitch_batch")
         return out
 
-    def matmul_rns(self, x_cts, w_cts, m, luts, bsk_prepared, ksk, out=None):
-        """slz_matmul_rns: x_cts [a][b][n+1], w_cts [b][c][n+1] -> [k][a][c][n+1]; allocates the workspace the call needs."""
+    def matmul_rns(self, x_cts, w_cts, m, luts, bsk_prepared, ksk, out=None, highres: bool = False):
+        """slz_matmul_rns (highres: slz_matmul_highres, 5-bit moduli): x_cts [a][b][n+1], w_cts [b][c][n+1] -> [k][a][c][n+1];
+        allocates the workspace the call needs."""
         import torch
         a, b = x_cts.shape[:2]
         c = w_cts.shape[1]
         sh = make_matmul_rns_shape(m, a, b, c)
         need = ctypes.c_size_t(0)
-        _check(lib().slz_matmul_rns_workspace(self._h, ctypes.byref(sh), ctypes.byref(need)), "slz_matmul_rns_workspace")
+        L = lib()
+        ws_fn, fn, name = (L.slz_matmul_highres_workspace, L.slz_matmul_highres, "slz_matmul_highres") if highres else \
+            (L.slz_matmul_rns_workspace, L.slz_matmul_rns, "slz_matmul_rns")
+        _check(ws_fn(self._h, ctypes.byref(sh), ctypes.byref(need)), name + "_workspace")
         ws = torch.empty(need.value, dtype=torch.uint8, device=x_cts.device)
         if out is None:
             out = torch.empty((sh.k, a, c, self.p.n + 1), dtype=torch.int64, device=x_cts.device)
-        _check(lib().slz_matmul_rns(self._h, ctypes.byref(sh), _dev_u64(x_cts, "x_cts"), _dev_u64(w_cts, "w_cts"),
-                                    _dev_u64(luts, "luts"), bsk_prepared.data_ptr(), _dev_u64(ksk, "ksk"),
-                                    _dev_u64(out, "out"), ws.data_ptr(), need.value, _stream()), "slz_matmul_rns")
+        _check(fn(self._h, ctypes.byref(sh), _dev_u64(x_cts, "x_cts"), _dev_u64(w_cts, "w_cts"), _dev_u64(luts, "luts"),
+                  bsk_prepared.data_ptr(), _dev_u64(ksk, "ksk"), _dev_u64(out, "out"), ws.data_ptr(), need.value, _stream()), name)
         torch.cuda.current_stream().synchronize()     # the workspace is released when this returns
         return out
 

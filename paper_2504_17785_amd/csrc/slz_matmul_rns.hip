@@ -106,9 +106,9 @@ k_mr_pack(const uint64_t *__restrict__ res, uint64_t *__restrict__ packed, uint3
 }
 
 // wts[j][o] = 1 if input j belongs to block o
-__global__ void k_mr_weights(int32_t *wts, uint32_t b, uint32_t nblk) {
+__global__ void k_mr_weights(int32_t *wts, uint32_t b, uint32_t nblk, uint32_t block) {
     const uint32_t gid = blockIdx.x * blockDim.x + threadIdx.x;
-    if (gid < b * nblk) wts[gid] = (gid / nblk) / SLZ_MATMUL_RNS_BLOCK == gid % nblk ? 1 : 0;
+    if (gid < b * nblk) wts[gid] = (gid / nblk) / block == gid % nblk ? 1 : 0;
 }
 
 // tmp[g][.] = (t > 0 ? y[g][.] : 0) + sums[g][t][.];  idx[g] = g / (a c)
@@ -158,7 +158,8 @@ extern "C" int slz_matmul_rns(slz_ctx *ctx, const slz_matmul_rns_shape *sh, cons
     if (rc != SLZ_OK) return rc;
     // Step 3: sums of at most 15 products per block (one linear combination with block-indicator weights), then the
     // running sum Y <- (Y + Y') mod m', one lookup per block
-    hipLaunchKernelGGL(k_mr_weights, dim3((b * (uint32_t)P.nblk + 255) / 256), dim3(256), 0, s, wts, b, (uint32_t)P.nblk);
+    hipLaunchKernelGGL(k_mr_weights, dim3((b * (uint32_t)P.nblk + 255) / 256), dim3(256), 0, s, wts, b, (uint32_t)P.nblk,
+                       (uint32_t)SLZ_MATMUL_RNS_BLOCK);
     const size_t groups = P.n_out;
     for (size_t g0 = 0; g0 < groups; g0 += 65535) {          // the linear combination takes at most 65535 groups per call
         const uint32_t ng = (uint32_t)(groups - g0 < 65535 ? groups - g0 : 65535);
@@ -169,6 +170,174 @@ extern "C" int slz_matmul_rns(slz_ctx *ctx, const slz_matmul_rns_shape *sh, cons
         hipLaunchKernelGGL(k_mr_accumulate, ew_grid(P.n_out * n1), dim3(MR_THREADS), 0, s, y, sums, tmp, idx, P.n_out, a * c,
                            (uint32_t)P.nblk, t, n1);
         rc = lookup(ctx, P, tmp, luts + (size_t)2 * k * N, idx, k, bskp, ksk, big, y, P.n_out, hip_stream);
+        if (rc != SLZ_OK) return rc;
+    }
+    SLZ_HIP(hipGetLastError());
+    return SLZ_OK;
+}
+
+// ---- MatmulHighRes^RNS (the paper's Algorithm of that name): 5-bit moduli, every intermediate within 8 bits --------------------
+static bool highres_shape_ok(const slz_params *p, const slz_matmul_rns_shape *sh) {
+    if (!p || !sh || sh->k == 0 || sh->k > SLZ_MATMUL_RNS_MAX_K || sh->a == 0 || sh->b == 0 || sh->c == 0) return false;
+    if (p->msg_bits < 8) return false;
+    for (uint32_t i = 0; i < sh->k; i++)
+        if (sh->m[i] < 2 || sh->m[i] > 32) return false;
+    const uint64_t prods = (uint64_t)sh->k * sh->a * sh->b * sh->c;
+    return prods < (1ull << 31) && (uint64_t)sh->k * ((uint64_t)sh->a * sh->b + (uint64_t)sh->b * sh->c) < (1ull << 31);
+}
+
+extern "C" int slz_matmul_highres_luts(const slz_params *p, const slz_matmul_rns_shape *sh, uint64_t *luts_out) {
+    if (!luts_out || !highres_shape_ok(p, sh)) return SLZ_E_INVALID_ARG;
+    const uint64_t t = 1ull << p->msg_bits;
+    const uint32_t k = sh->k;
+    std::vector<uint64_t> tab((size_t)(4 * k + 3) * t, 0);
+    for (uint64_t v = 0; v < t; v++) {
+        const int64_t sv = v < t / 2 ? (int64_t)v : (int64_t)v - (int64_t)t;
+        const uint64_t prod = v < 256 ? (v >> 5) * (v & 31) : 0;
+        for (uint32_t i = 0; i < k; i++) {
+            const int64_t q = sh->m[i];
+            tab[(size_t)i * t + v] = (uint64_t)(((sv % q) + q) % q);
+            tab[(size_t)(k + i) * t + v] = prod % (uint64_t)q;
+            tab[(size_t)(2 * k + i) * t + v] = (8 * v) % (uint64_t)q;
+            tab[(size_t)(3 * k + i) * t + v] = v % (uint64_t)q;
+        }
+        tab[(size_t)(4 * k) * t + v] = (v >> 3) & 3;
+        tab[(size_t)(4 * k + 1) * t + v] = v & 7;
+        tab[(size_t)(4 * k + 2) * t + v] = prod;
+    }
+    return slz_lut_encode(p, tab.data(), 4 * k + 3, luts_out);
+}
+
+struct hr_plan {
+    size_t n1, N1, n_in, n_x, n_prod, n_out, nblk, chunk;
+    size_t o_rep, o_idx, o_big, o_res, o_x1, o_x2, o_pk, o_y1, o_y2, o_sums, o_wts, o_tmp, total;
+};
+
+static hr_plan make_hr_plan(const slz_ctx *ctx, const slz_matmul_rns_shape *sh) {
+    hr_plan P;
+    P.n1 = ctx->prm.n + 1;
+    P.N1 = (size_t)ctx->prm.k * ctx->prm.N + 1;
+    P.n_in = (size_t)sh->k * ((size_t)sh->a * sh->b + (size_t)sh->b * sh->c);
+    P.n_x = (size_t)sh->k * sh->a * sh->b;
+    P.n_prod = (size_t)sh->k * sh->a * sh->b * sh->c;
+    P.n_out = (size_t)sh->k * sh->a * sh->c;
+    P.nblk = (sh->b + SLZ_MATMUL_HIGHRES_BLOCK - 1) / SLZ_MATMUL_HIGHRES_BLOCK;
+    const size_t biggest = P.n_in > P.n_prod ? P.n_in : P.n_prod;
+    P.chunk = biggest < ctx->max_batch ? biggest : ctx->max_batch;
+    size_t o = 0;
+    P.o_rep = o;  o += up256(P.n_in * P.n1 * 8);              // step 1 inputs, one copy per modulus
+    P.o_idx = o;  o += up256(biggest * 4);                    // table index per ciphertext of the current lookup
+    P.o_big = o;  o += up256(P.chunk * P.N1 * 8);             // bootstrapping outputs of one chunk
+    P.o_res = o;  o += up256(P.n_in * P.n1 * 8);              // X', W'
+    P.o_x1 = o;   o += up256(P.n_x * P.n1 * 8);               // bits 0..2 of X'
+    P.o_x2 = o;   o += up256(P.n_x * P.n1 * 8);               // bits 3..4 of X'
+    P.o_pk = o;   o += up256(P.n_prod * P.n1 * 8);            // packed inputs of the product lookups, [k][a][c][b]
+    P.o_y1 = o;   o += up256(P.n_prod * P.n1 * 8);            // Y1*, later Y*
+    P.o_y2 = o;   o += up256(P.n_prod * P.n1 * 8);            // Y2*
+    P.o_sums = o; o += up256(P.n_out * P.nblk * P.n1 * 8);
+    P.o_wts = o;  o += up256((size_t)sh->b * P.nblk * 4);
+    P.o_tmp = o;  o += up256(P.n_out * P.n1 * 8);
+    P.total = o;
+    return P;
+}
+
+extern "C" int slz_matmul_highres_workspace(const slz_ctx *ctx, const slz_matmul_rns_shape *sh, size_t *bytes) {
+    if (!ctx || !bytes || !highres_shape_ok(&ctx->prm, sh)) return SLZ_E_INVALID_ARG;
+    *bytes = make_hr_plan(ctx, sh).total;
+    return SLZ_OK;
+}
+
+// packed[i][r][s][j][.] = 32 xs[i][r][j][.] + res[i][a b + j c + s][.];  idx[...] = idx_base + i.   xs = [k][a b][n1], res = [k][ab + bc][n1]
+__global__ void __launch_bounds__(MR_THREADS)
+k_hr_pack(const uint64_t *__restrict__ xs, const uint64_t *__restrict__ res, uint64_t *__restrict__ packed, uint32_t *__restrict__ idx,
+          uint32_t idx_base, uint32_t k, uint32_t a, uint32_t b, uint32_t c, uint32_t n1) {
+    const size_t per = (size_t)a * b + (size_t)b * c;
+    const size_t total = (size_t)k * a * c * b * n1;
+    for (size_t gid = (size_t)blockIdx.x * MR_THREADS + threadIdx.x; gid < total; gid += (size_t)gridDim.x * MR_THREADS) {
+        const uint32_t word = (uint32_t)(gid % n1);
+        size_t ct = gid / n1;
+        const uint32_t j = (uint32_t)(ct % b);
+        const uint32_t s = (uint32_t)((ct / b) % c);
+        const uint32_t r = (uint32_t)((ct / ((size_t)b * c)) % a);
+        const uint32_t i = (uint32_t)(ct / ((size_t)a * b * c));
+        const uint64_t xv = xs[(((size_t)i * a + r) * b + j) * n1 + word];
+        const uint64_t wv = res[((size_t)i * per + (size_t)a * b + (size_t)j * c + s) * n1 + word];
+        packed[gid] = 32ull * xv + wv;
+        if (word == 0) idx[ct] = idx_base + i;
+    }
+}
+
+// out = x + y on `total` words;  idx[ct] = idx_base + ct / per_mod
+__global__ void __launch_bounds__(MR_THREADS)
+k_hr_add(const uint64_t *__restrict__ x, const uint64_t *__restrict__ y, uint64_t *__restrict__ out, uint32_t *__restrict__ idx,
+         uint32_t idx_base, size_t per_mod, size_t cts, uint32_t n1) {
+    const size_t total = cts * n1;
+    for (size_t gid = (size_t)blockIdx.x * MR_THREADS + threadIdx.x; gid < total; gid += (size_t)gridDim.x * MR_THREADS) {
+        out[gid] = x[gid] + y[gid];
+        if (gid % n1 == 0) idx[gid / n1] = idx_base + (uint32_t)((gid / n1) / per_mod);
+    }
+}
+
+extern "C" int slz_matmul_highres(slz_ctx *ctx, const slz_matmul_rns_shape *sh, const uint64_t *x, const uint64_t *w, const uint64_t *luts,
+                                  const void *bskp, const uint64_t *ksk, uint64_t *y, void *workspace, size_t workspace_bytes,
+                                  void *hip_stream) {
+    if (!ctx || !x || !w || !luts || !bskp || !ksk || !y || !workspace || !highres_shape_ok(&ctx->prm, sh)) return SLZ_E_INVALID_ARG;
+    if (((uintptr_t)workspace & 255u) || ((uintptr_t)x & 7u) || ((uintptr_t)w & 7u) || ((uintptr_t)y & 7u) || ((uintptr_t)luts & 15u))
+        return SLZ_E_INVALID_ARG;
+    const hr_plan P = make_hr_plan(ctx, sh);
+    if (workspace_bytes < P.total) return SLZ_E_INVALID_ARG;
+    hipStream_t s = (hipStream_t)hip_stream;
+    char *ws = (char *)workspace;
+    uint64_t *rep = (uint64_t *)(ws + P.o_rep), *big = (uint64_t *)(ws + P.o_big), *res = (uint64_t *)(ws + P.o_res);
+    uint64_t *x1 = (uint64_t *)(ws + P.o_x1), *x2 = (uint64_t *)(ws + P.o_x2), *pk = (uint64_t *)(ws + P.o_pk);
+    uint64_t *y1 = (uint64_t *)(ws + P.o_y1), *y2 = (uint64_t *)(ws + P.o_y2), *sums = (uint64_t *)(ws + P.o_sums);
+    uint64_t *tmp = (uint64_t *)(ws + P.o_tmp);
+    uint32_t *idx = (uint32_t *)(ws + P.o_idx);
+    int32_t *wts = (int32_t *)(ws + P.o_wts);
+    const uint32_t k = sh->k, a = sh->a, b = sh->b, c = sh->c, n1 = (uint32_t)P.n1, n_tabs = 4 * k + 3;
+    const size_t N = ctx->prm.N, ab = (size_t)a * b, per = ab + (size_t)b * c;
+    auto look = [&](const uint64_t *in, const uint32_t *ix, uint64_t *out, size_t count) {
+        return lookup_n(ctx, P.chunk, P.n1, in, luts, ix, n_tabs, bskp, ksk, big, out, count, hip_stream);
+    };
+    auto look1 = [&](const uint64_t *in, uint32_t table, uint64_t *out, size_t count) {
+        return lookup_n(ctx, P.chunk, P.n1, in, luts + (size_t)table * N, nullptr, 1, bskp, ksk, big, out, count, hip_stream);
+    };
+    // Step 1: X' = X mod m', W' = W mod m'
+    hipLaunchKernelGGL(k_mr_replicate, ew_grid(P.n_in * n1), dim3(MR_THREADS), 0, s, x, w, rep, idx, k, ab, (size_t)b * c, n1);
+    int rc = look(rep, idx, res, P.n_in);
+    if (rc != SLZ_OK) return rc;
+    // Step 2: the bit chunks of X' (the X' of modulus i are the first a b ciphertexts of its slice of res)
+    for (uint32_t i = 0; i < k; i++) {
+        rc = look1(res + (size_t)i * per * n1, 4 * k, x2 + (size_t)i * ab * n1, ab);
+        if (rc != SLZ_OK) return rc;
+        rc = look1(res + (size_t)i * per * n1, 4 * k + 1, x1 + (size_t)i * ab * n1, ab);
+        if (rc != SLZ_OK) return rc;
+    }
+    // Step 3: Y1* = X1' W' mod m'' on 32 x1 + w;  Y2* = X2' W' on 32 x2 + w, then v -> 8 v mod m''
+    hipLaunchKernelGGL(k_hr_pack, ew_grid(P.n_prod * n1), dim3(MR_THREADS), 0, s, x1, res, pk, idx, k, k, a, b, c, n1);
+    rc = look(pk, idx, y1, P.n_prod);
+    if (rc != SLZ_OK) return rc;
+    hipLaunchKernelGGL(k_hr_pack, ew_grid(P.n_prod * n1), dim3(MR_THREADS), 0, s, x2, res, pk, idx, 2 * k, k, a, b, c, n1);
+    rc = look1(pk, 4 * k + 2, y2, P.n_prod);
+    if (rc != SLZ_OK) return rc;
+    rc = look(y2, idx, y2, P.n_prod);          // in place: each chunk is read before it is written
+    if (rc != SLZ_OK) return rc;
+    // Step 4: Y* = (Y1* + Y2*) mod m''
+    hipLaunchKernelGGL(k_hr_add, ew_grid(P.n_prod * n1), dim3(MR_THREADS), 0, s, y1, y2, pk, idx, 3 * k, (size_t)a * b * c, P.n_prod, n1);
+    rc = look(pk, idx, y1, P.n_prod);
+    if (rc != SLZ_OK) return rc;
+    // Step 5: sums of at most 7 entries per block, the running sum reduced by one lookup per block
+    hipLaunchKernelGGL(k_mr_weights, dim3((b * (uint32_t)P.nblk + 255) / 256), dim3(256), 0, s, wts, b, (uint32_t)P.nblk,
+                       (uint32_t)SLZ_MATMUL_HIGHRES_BLOCK);
+    for (size_t g0 = 0; g0 < P.n_out; g0 += 65535) {
+        const uint32_t ng = (uint32_t)(P.n_out - g0 < 65535 ? P.n_out - g0 : 65535);
+        rc = slz_lwe_lincomb_batch(ctx, y1 + g0 * b * n1, wts, sums + g0 * P.nblk * n1, ng, b, (uint32_t)P.nblk, hip_stream);
+        if (rc != SLZ_OK) return rc;
+    }
+    for (uint32_t t = 0; t < P.nblk; t++) {
+        hipLaunchKernelGGL(k_mr_accumulate, ew_grid(P.n_out * n1), dim3(MR_THREADS), 0, s, y, sums, tmp, idx, P.n_out, a * c,
+                           (uint32_t)P.nblk, t, n1);
+        rc = lookup_n(ctx, P.chunk, P.n1, tmp, luts + (size_t)3 * k * N, idx, k, bskp, ksk, big, y, P.n_out, hip_stream);
         if (rc != SLZ_OK) return rc;
     }
     SLZ_HIP(hipGetLastError());

@@ -133,3 +133,15 @@ def test_loss_and_weight_update_luts_match_oracle_tables(orc):
     for bad in ((3, 7, 4), (17, 7, 1), (3, 9, 2), (3, 1, 2), (3, 7, 0)):       # too wide, too many classes, Gamma out of range, kappa 0
         with pytest.raises(slz.SlzError):
             slz.loss_luts(p, *bad)
+
+
+def test_matmul_highres_luts_match_oracle_tables(orc):
+    from oracle import gadgets
+    p = synth.Params(name="t", n=4, k=1, N=2048, pbs_base_log=23, pbs_level=1, ks_base_log=4, ks_level=8, msg_bits=8,
+                     sigma_lwe=2.0 ** -40, sigma_bsk=2.0 ** -50, batch=1, n_luts=1, seed=1)
+    for m in gadgets.RNS_BASES_5BIT.values():
+        assert np.array_equal(slz.matmul_highres_luts(p, m, 1, 1, 1), orc.lut_encode(p, gadgets.highres_tables(p, m)))
+    with pytest.raises(slz.SlzError):
+        slz.matmul_highres_luts(p, (33, 31), 1, 1, 1)               # moduli are at most 5 bits wide
+    with pytest.raises(slz.SlzError):
+        slz.matmul_highres_luts(p.with_(msg_bits=7), (31, 30), 1, 1, 1)

@@ -58,6 +58,45 @@ def test_matmul_rns_matches_oracle_and_decrypts(slz, orc, toy, a, b, c, m, max_b
         assert np.array_equal(clear[i], np.mod(X @ W, q))
 
 
+@pytest.mark.parametrize("a,b,c,m,max_batch", [(2, 3, 2, (31, 30), 64), (2, 9, 1, (29, 31, 30), 512), (1, 15, 2, (25, 27, 29, 31, 28), 37),
+                                                (2, 1, 1, (23, 25, 27, 29, 31, 28), 1)])
+def test_matmul_highres_matches_oracle_and_decrypts(slz, orc, toy, a, b, c, m, max_batch):
+    from oracle import gadgets as gd
+    p, keys = toy
+    X, W, x_cts, w_cts = _inputs(orc, gd, p, keys, a, b, c, offset=2000 * a + b)
+    ctx = slz.Context(p, max_batch)
+    d_bsk = ctx.bsk_prepare(slz.to_device_u64(keys.bsk))
+    d_luts = slz.to_device_u64(slz.matmul_highres_luts(p, m, a, b, c))
+    got = slz.to_host_u64(ctx.matmul_rns(slz.to_device_u64(x_cts), slz.to_device_u64(w_cts), m, d_luts, d_bsk, slz.to_device_u64(keys.ksk),
+                                         highres=True))
+    want = gd.matmul_highres_encrypted(p, x_cts, w_cts, m, keys.bsk, keys.ksk)
+    assert np.array_equal(got, want)
+    dec, err = orc.decode(orc.lwe_phase(keys.lwe_sk, got.reshape(-1, p.n + 1)), p.msg_bits)
+    for i, q in enumerate(m):
+        assert np.array_equal(dec.reshape(len(m), a, c)[i].astype(np.int64), np.mod(X @ W, q))
+
+
+def test_matmul_highres_error_codes(slz, toy):
+    import ctypes
+    p, keys = toy
+    ctx = slz.Context(p, 8)
+    L = slz.lib()
+    sh = slz.make_matmul_rns_shape((31, 30), 2, 2, 2)
+    need = ctypes.c_size_t(0)
+    assert L.slz_matmul_highres_workspace(ctx._h, ctypes.byref(sh), ctypes.byref(need)) == 0 and need.value > 0
+    buf = torch.zeros(need.value + 4096, dtype=torch.uint8, device="cuda")
+    ptr = buf.data_ptr()
+    cts = torch.zeros((8, p.n + 1), dtype=torch.int64, device="cuda")
+    c = cts.data_ptr()
+    call = lambda shape, ws, nbytes, x=c: L.slz_matmul_highres(ctx._h, ctypes.byref(shape), x, c, c, c, c, c, ws, nbytes, None)
+    assert call(sh, ptr, need.value - 1) == slz.SLZ_E_INVALID_ARG
+    assert call(sh, ptr + 8, need.value) == slz.SLZ_E_INVALID_ARG
+    assert call(sh, ptr, need.value, x=c + 4) == slz.SLZ_E_INVALID_ARG
+    assert call(slz.make_matmul_rns_shape((33, 31), 2, 2, 2), ptr, need.value) == slz.SLZ_E_INVALID_ARG
+    assert call(slz.make_matmul_rns_shape((31, 30), 2, 0, 2), ptr, need.value) == slz.SLZ_E_INVALID_ARG
+    torch.cuda.synchronize()
+
+
 def test_matmul_rns_error_codes(slz, toy):
     import ctypes
     p, keys = toy
