@@ -122,6 +122,16 @@ int slz_blind_rotate_batch(slz_ctx *ctx, const uint64_t *lwe_in_dev, const uint6
 int slz_keyswitch_batch(slz_ctx *ctx, const uint64_t *lwe_in_dev, const uint64_t *ksk_dev,
                         uint64_t *lwe_out_dev, uint32_t batch, void *hip_stream);
 
+/* Keyswitch-first order (the order in which a compiler for the scheme usually chains the two): ciphertexts stay under the
+ * big key between lookups, and one lookup is   lwe_out = PBS(keyswitch(lwe_in)).
+ * lwe_in_dev, lwe_out_dev [batch][kN+1] (they may be the same buffer); the other arguments as for slz_keyswitch_batch and
+ * slz_pbs_batch; 1 <= batch <= max_batch (SLZ_E_TOO_LARGE above).  The n+1-word ciphertexts between the two steps live in
+ * a scratch buffer of the context (max_batch rows, allocated by the first call; SLZ_E_NOMEM if that fails), so calls on one
+ * context must not overlap.  The result is bit-identical to calling the two entry points one after the other. */
+int slz_ks_pbs_batch(slz_ctx *ctx, const uint64_t *lwe_in_dev, const uint64_t *ksk_dev, const uint64_t *luts_dev,
+                     const uint32_t *lut_idx_dev, uint32_t n_luts, const void *bsk_prepared_dev,
+                     uint64_t *lwe_out_dev, uint32_t batch, void *hip_stream);
+
 /* Integer linear combination of LWE ciphertexts with clear weights (the leveled sums of step 3 of
  * the paper's Matmul^RNS algorithm):  out[g][o] = sum_{j<J} w[j][o] * ct[g][j]  as vectors of n+1 words.
  * cts_dev [G][J][n+1];  w_dev int32 [J][O];  out_dev [G][O][n+1]. */

@@ -72,6 +72,7 @@ extern "C" int slz_ctx_destroy(slz_ctx *ctx) {
     if (ctx->dig) (void)hipFree(ctx->dig);
     if (ctx->xhat) (void)hipFree(ctx->xhat);
     if (ctx->outhat) (void)hipFree(ctx->outhat);
+    if (ctx->ks_first_small) (void)hipFree(ctx->ks_first_small);
     delete ctx;
     return SLZ_OK;
 }
@@ -183,6 +184,26 @@ extern "C" int slz_keyswitch_batch(slz_ctx *ctx, const uint64_t *lwe_in_dev, con
     if (!ctx || !lwe_in_dev || !ksk_dev || !lwe_out_dev || batch == 0) return SLZ_E_INVALID_ARG;
     if (misaligned8(lwe_in_dev) || misaligned(ksk_dev) || misaligned8(lwe_out_dev)) return SLZ_E_INVALID_ARG;
     return slz_keyswitch_launch(ctx, lwe_in_dev, ksk_dev, lwe_out_dev, batch, (hipStream_t)hip_stream);
+}
+
+// Keyswitch first, then bootstrapping, on ciphertexts under the big key.  The small ciphertexts between the two live in a
+// scratch buffer of the context (max_batch rows, allocated on first use); everything is ordered on the one stream.
+extern "C" int slz_ks_pbs_batch(slz_ctx *ctx, const uint64_t *lwe_in_dev, const uint64_t *ksk_dev, const uint64_t *luts_dev,
+                                const uint32_t *lut_idx_dev, uint32_t n_luts, const void *bsk_prepared_dev, uint64_t *lwe_out_dev,
+                                uint32_t batch, void *hip_stream) {
+    if (!ctx || !lwe_in_dev || !ksk_dev || !luts_dev || !bsk_prepared_dev || !lwe_out_dev || batch == 0 || n_luts == 0)
+        return SLZ_E_INVALID_ARG;
+    if (batch > ctx->max_batch) return SLZ_E_TOO_LARGE;
+    if (misaligned8(lwe_in_dev) || misaligned(ksk_dev) || misaligned(luts_dev) || misaligned(bsk_prepared_dev) ||
+        misaligned8(lwe_out_dev) || ((uintptr_t)lut_idx_dev & 3u))
+        return SLZ_E_INVALID_ARG;
+    if (!ctx->ks_first_small) {
+        if (hipMalloc((void **)&ctx->ks_first_small, (size_t)ctx->max_batch * (ctx->prm.n + 1) * 8) != hipSuccess) return SLZ_E_NOMEM;
+    }
+    int rc = slz_keyswitch_launch(ctx, lwe_in_dev, ksk_dev, ctx->ks_first_small, batch, (hipStream_t)hip_stream);
+    if (rc != SLZ_OK) return rc;
+    return blind_rotate_common(ctx, ctx->ks_first_small, luts_dev, lut_idx_dev, n_luts, bsk_prepared_dev, ctx->prm.n, nullptr,
+                               lwe_out_dev, batch, hip_stream);
 }
 
 extern "C" int slz_lwe_lincomb_batch(slz_ctx *ctx, const uint64_t *cts_dev, const int32_t *w_dev, uint64_t *out_dev, uint32_t G,

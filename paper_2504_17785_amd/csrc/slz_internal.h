@@ -60,6 +60,7 @@ struct slz_ctx {
     double *dig;              // [max_batch][(k+1)l][N]
     double *xhat;             // [max_batch][2][(k+1)l][N]
     double *outhat;           // [max_batch][2][k+1][N]
+    uint64_t *ks_first_small;   // slz_ks_pbs_batch: keyswitch outputs [max_batch][n+1], allocated on first use
     void *ks_dig;             // digit bytes of the matrix-core keyswitch (allocated at its first call)
     void *lc_dig;             // weight digit planes of the matrix-core linear combination (grown on demand)
     size_t lc_dig_bytes;

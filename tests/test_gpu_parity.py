@@ -401,3 +401,58 @@ def test_work_is_enqueued_on_the_callers_stream(slz, orc):
     assert np.array_equal(slz.to_host_u64(big), want)
     assert np.array_equal(slz.to_host_u64(big_gen), want)
     assert np.array_equal(slz.to_host_u64(small), want_small)
+
+
+# ---- keyswitch-first order -------------------------------------------------------------------------------------------------
+@pytest.mark.parametrize("shape,batch", [(dict(n=7, N=16, k=2, pbs_base_log=6, pbs_level=3), 5),
+                                         (dict(n=5, N=2048, k=1, pbs_base_log=23, pbs_level=1, ks_base_log=4, ks_level=8), 70),
+                                         (dict(n=3, N=4096, k=1, pbs_base_log=11, pbs_level=2, ks_base_log=2, ks_level=9), 3)],
+                         ids=["generic_k2", "fused_mfma_ks", "large_n"])
+def test_keyswitch_first_order_matches_oracle(slz, orc, shape, batch):
+    p = tiny(**shape)
+    case = Case(slz, orc, p, batch, raw_inputs=True)
+    big_in = synth.raw_words(p, "raw_ct", batch * (p.k * p.N + 1), offset=77).reshape(batch, p.k * p.N + 1)
+    want = orc.pbs_batch(p, orc.keyswitch_batch(p, big_in, case.keys.ksk), case.luts, case.lut_idx, case.keys.bsk)
+    d_in = slz.to_device_u64(big_in)
+    got = case.ctx.ks_pbs_batch(d_in, case.d_ksk, case.d_luts, case.d_idx, case.d_bsk)
+    assert np.array_equal(slz.to_host_u64(got), want)
+    # identical to the two calls one after the other, and usable in place
+    two = case.ctx.pbs_batch(case.ctx.keyswitch_batch(d_in, case.d_ksk), case.d_luts, case.d_idx, case.d_bsk)
+    assert torch.equal(got, two)
+    case.ctx.ks_pbs_batch(d_in, case.d_ksk, case.d_luts, case.d_idx, case.d_bsk, out=d_in)
+    assert np.array_equal(slz.to_host_u64(d_in), want)
+    # a smaller batch through the same scratch
+    part = case.ctx.ks_pbs_batch(slz.to_device_u64(big_in[1:3]), case.d_ksk, case.d_luts, case.d_idx[1:3].contiguous(), case.d_bsk)
+    assert np.array_equal(slz.to_host_u64(part), want[1:3])
+
+
+def test_keyswitch_first_chain_decrypts_at_config1(slz, orc):
+    """Two lookups in keyswitch-first order at a real parameter set: f, then g on the result, read under the big key."""
+    p = synth.CONFIGS[1]
+    case = Case(slz, orc, p, p.batch, n_tables=2, msgs=synth.config_messages(1))
+    t = 1 << p.msg_bits
+    first = slz.to_host_u64(case.ctx.pbs_batch(case.d_cts, case.d_luts, case.d_idx, case.d_bsk))       # brings the inputs under the big key
+    chained = case.ctx.ks_pbs_batch(slz.to_device_u64(first), case.d_ksk, case.d_luts, case.d_idx, case.d_bsk)
+    want = orc.pbs_batch(p, orc.keyswitch_batch(p, first, case.keys.ksk), case.luts, case.lut_idx, case.keys.bsk)
+    assert np.array_equal(slz.to_host_u64(chained), want)
+    got, err = orc.decode(orc.lwe_phase(case.keys.big_sk, want), p.msg_bits)
+    idx = case.lut_idx.astype(np.int64)
+    inner = case.tables[idx, case.msgs.astype(np.int64)].astype(np.int64) % t
+    assert np.array_equal(got.astype(np.int64), case.tables[idx, inner].astype(np.int64))
+    assert np.abs(err).max() < 2.0 ** -6
+
+
+def test_keyswitch_first_error_codes(slz, orc):
+    p = tiny(n=6, N=64, pbs_base_log=8, pbs_level=2)
+    case = Case(slz, orc, p, 4, raw_inputs=True)
+    L = slz.lib()
+    big = torch.zeros((5, p.k * p.N + 1), dtype=torch.int64, device="cuda")
+    b, k, l, q = big.data_ptr(), case.d_ksk.data_ptr(), case.d_luts.data_ptr(), case.d_bsk.data_ptr()
+    call = lambda *a: L.slz_ks_pbs_batch(case.ctx._h, *a, None)
+    assert call(b, k, l, None, 2, q, b, 5) == slz.SLZ_E_TOO_LARGE
+    assert call(b, k, l, None, 2, q, b, 0) == slz.SLZ_E_INVALID_ARG
+    assert call(b, k, l, None, 0, q, b, 4) == slz.SLZ_E_INVALID_ARG
+    assert call(None, k, l, None, 2, q, b, 4) == slz.SLZ_E_INVALID_ARG
+    assert call(b + 4, k, l, None, 2, q, b, 4) == slz.SLZ_E_INVALID_ARG
+    assert call(b, k + 8, l, None, 2, q, b, 4) == slz.SLZ_E_INVALID_ARG
+    torch.cuda.synchronize()
