@@ -284,6 +284,7 @@ def main():
     ap.add_argument("--batch", type=int, default=0, help="override the configuration's batch size")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--generic", action="store_true", help="force the generic multi-kernel path")
+    ap.add_argument("--large-n-lanes", type=int, default=0, help="large-N path: 1 = one chunk at a time, 2 = two half chunks on two streams")
     ap.add_argument("--calib-copy", action="store_true",
                     help="also run one plain device copy of 256 MiB (a known-size kernel to scale FETCH_SIZE/WRITE_SIZE by)")
     ap.add_argument("--gadget", choices=["matmul_rns", "matmul_highres", "sign_rns", "shift2msbs", "loss_deriv", "weight_update"], default=None,
@@ -311,6 +312,8 @@ def main():
     ctx = slz.Context(p, batch)
     if args.generic:
         ctx.set_option(slz.SLZ_OPT_FORCE_GENERIC, 1)
+    if args.large_n_lanes:
+        ctx.set_option(slz.SLZ_OPT_LARGE_N_LANES, args.large_n_lanes)
 
     # ---- synthetic inputs, resident in HBM ----
     R, C = (p.k + 1) * p.pbs_level, p.k + 1

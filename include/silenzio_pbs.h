@@ -73,6 +73,12 @@ typedef struct slz_ctx slz_ctx;   /* opaque: parameter copy, twiddle tables, scr
 #define SLZ_OPT_LARGE_N_BLOCK 2   /* value 1024 or 2048: block size of the row pass of the large-N path (default: 1024
                                      when N = 1024 G', G' <= 32, else 2048); SLZ_E_INVALID_ARG if this N cannot use it */
 
+#define SLZ_OPT_LARGE_N_LANES 3   /* value 1 or 2: the large-N path runs one chunk of ciphertexts at a time on the caller's stream
+                                     (1), or two half chunks at once on two internal streams that fork from and join
+                                     the caller's stream (2, the default: the arithmetic-bound row pass of one half
+                                     overlaps the memory-bound column passes of the other; results are identical);
+                                     SLZ_E_INVALID_ARG when the context has no large-N path */
+
 /* Creates a context on the current device.  Allocates transform tables and scratch sized for
  * `max_batch` ciphertexts.  Fails with SLZ_E_UNSUPPORTED when the exactness bound
  * 4 * (k+1) * l * N * 2^(beta-1) * 2^63 <= p1 * p2 (the two ~2^50 transform primes) does not hold. */

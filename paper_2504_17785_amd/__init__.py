@@ -17,6 +17,7 @@ LIB_PATH = os.environ.get("SILENZIO_PBS_LIB") or os.path.join(_HERE, "libsilenzi
 
 SLZ_OPT_FORCE_GENERIC = 1
 SLZ_OPT_LARGE_N_BLOCK = 2
+SLZ_OPT_LARGE_N_LANES = 3
 SLZ_OK, SLZ_E_INVALID_ARG, SLZ_E_UNSUPPORTED, SLZ_E_HIP, SLZ_E_NOMEM, SLZ_E_TOO_LARGE = 0, -1, -2, -3, -4, -5
 
 

@@ -401,6 +401,7 @@ int slz_bign_init(slz_ctx *ctx) {
     const uint32_t N = ctx->prm.N;
     ctx->has_bign16 = 0;
     ctx->bign_block = 0;
+    ctx->bign_lanes = 2;
     bool any = false;
     if (block_fits(N, 2048) && bounds_ok(N, 2048)) {
         int rc = build_row_tables(ctx, 2048, &ctx->bign_rowA, &ctx->bign_rowB);
@@ -426,6 +427,13 @@ void slz_bign_destroy(slz_ctx *ctx) {
     if (ctx->bign16_rowA) (void)hipFree(ctx->bign16_rowA);
     if (ctx->bign16_rowB) (void)hipFree(ctx->bign16_rowB);
     ctx->bign_rowA = ctx->bign_rowB = ctx->bign16_rowA = ctx->bign16_rowB = nullptr;
+    for (int j = 0; j < 2; j++) {
+        if (ctx->bign_lane_stream[j]) (void)hipStreamDestroy((hipStream_t)ctx->bign_lane_stream[j]);
+        if (ctx->bign_lane_done[j]) (void)hipEventDestroy((hipEvent_t)ctx->bign_lane_done[j]);
+        ctx->bign_lane_stream[j] = ctx->bign_lane_done[j] = nullptr;
+    }
+    if (ctx->bign_fork) (void)hipEventDestroy((hipEvent_t)ctx->bign_fork);
+    ctx->bign_fork = nullptr;
 }
 
 template <int G, int BS>
@@ -455,6 +463,23 @@ static void launch_cols_any(bool fwd, uint32_t G, uint32_t BS, const bign_args &
     }
 }
 
+// Streams and events of the concurrent lanes (created at the first use, default priority).
+static int ensure_lanes(slz_ctx *ctx) {
+    if (ctx->bign_lane_stream[0]) return SLZ_OK;
+    for (int j = 0; j < 2; j++) {
+        hipStream_t st;
+        hipEvent_t ev;
+        if (hipStreamCreateWithFlags(&st, hipStreamNonBlocking) != hipSuccess) return SLZ_E_HIP;
+        ctx->bign_lane_stream[j] = st;
+        if (hipEventCreateWithFlags(&ev, hipEventDisableTiming) != hipSuccess) return SLZ_E_HIP;
+        ctx->bign_lane_done[j] = ev;
+    }
+    hipEvent_t ev;
+    if (hipEventCreateWithFlags(&ev, hipEventDisableTiming) != hipSuccess) return SLZ_E_HIP;
+    ctx->bign_fork = ev;
+    return SLZ_OK;
+}
+
 // Runs steps [0, n_steps) on accumulators that the caller has initialised in `acc` ([batch][2][N]).
 int slz_bign_cmux_steps(slz_ctx *ctx, const uint64_t *lwe_in, const double *bskp, uint32_t n_steps, uint64_t *acc,
                         uint32_t batch, hipStream_t s) {
@@ -470,36 +495,72 @@ int slz_bign_cmux_steps(slz_ctx *ctx, const uint64_t *lwe_in, const double *bskp
     const uint32_t fill = slots / (2 * G) ? slots / (2 * G) : 1;     // ciphertexts whose row tasks fill the chip once
     chunk = chunk / fill * fill;
     if (chunk < fill) chunk = fill;
+    // Two lanes: the chunk is cut in two halves that run on two streams, so that the row pass of one half (bound by
+    // arithmetic) overlaps the column passes of the other (bound by memory).  Measured at N = 32768: 5 % faster than one
+    // lane; three or four lanes of the same size overflow the Infinity Cache and are slower.
+    uint32_t lanes = (uint32_t)ctx->bign_lanes;
+    if (lanes >= 2) {
+        uint32_t half = chunk / 2 / fill * fill;
+        if (half < fill) half = fill;
+        if (batch > half) chunk = half; else lanes = 1;
+    }
     if (chunk > batch) chunk = batch;
-    for (uint32_t c0 = 0; c0 < batch; c0 += chunk) {
-        const uint32_t nb = (batch - c0 < chunk) ? batch - c0 : chunk;
-        bign_args A;
-        A.lwe_in = lwe_in + (size_t)c0 * (p.n + 1);
-        A.acc = acc + (size_t)c0 * 2 * N;
-        A.X = ctx->xhat;
-        A.Y = ctx->outhat;
-        A.n = p.n; A.N = N; A.logG = logG; A.beta = p.pbs_base_log; A.l = p.pbs_level; A.batch = nb;
-        for (int q = 0; q < 2; q++) {
-            A.tab[q].fwd = ctx->tab[q].fwd;
-            A.tab[q].rowA = (BS == 2048 ? ctx->bign_rowA : ctx->bign16_rowA) + (size_t)q * G * 64;
-            A.tab[q].rowB = BS == 2048 ? ctx->bign_rowB + (size_t)q * G * 31 * 64 : ctx->bign16_rowB + (size_t)q * G * 15 * 64;
-            A.tab[q].inv = ctx->tab[q].inv;
-            A.tab[q].post = ctx->tab[q].post;
-            A.mod[q] = ctx->mod[q];
+    if (lanes >= 2) {
+        int rc = ensure_lanes(ctx);
+        if (rc != SLZ_OK) return rc;
+        SLZ_HIP(hipEventRecord((hipEvent_t)ctx->bign_fork, s));
+        for (uint32_t j = 0; j < lanes; j++) SLZ_HIP(hipStreamWaitEvent((hipStream_t)ctx->bign_lane_stream[j], (hipEvent_t)ctx->bign_fork, 0));
+    }
+    for (uint32_t g0 = 0; g0 < batch; g0 += lanes * chunk) {
+        bign_args A[2];
+        hipStream_t st[2];
+        uint32_t n_tasks[2], nbs[2], used = 0;
+        for (uint32_t j = 0; j < lanes; j++) {
+            const uint32_t c0 = g0 + j * chunk;
+            if (c0 >= batch) break;
+            const uint32_t nb = (batch - c0 < chunk) ? batch - c0 : chunk;
+            bign_args &a = A[j];
+            a.lwe_in = lwe_in + (size_t)c0 * (p.n + 1);
+            a.acc = acc + (size_t)c0 * 2 * N;
+            a.X = ctx->xhat + (size_t)j * chunk * 2 * R * N;
+            a.Y = ctx->outhat + (size_t)j * chunk * 2 * 2 * N;
+            a.n = p.n; a.N = N; a.logG = logG; a.beta = p.pbs_base_log; a.l = p.pbs_level; a.batch = nb;
+            for (int q = 0; q < 2; q++) {
+                a.tab[q].fwd = ctx->tab[q].fwd;
+                a.tab[q].rowA = (BS == 2048 ? ctx->bign_rowA : ctx->bign16_rowA) + (size_t)q * G * 64;
+                a.tab[q].rowB = BS == 2048 ? ctx->bign_rowB + (size_t)q * G * 31 * 64 : ctx->bign16_rowB + (size_t)q * G * 15 * 64;
+                a.tab[q].inv = ctx->tab[q].inv;
+                a.tab[q].post = ctx->tab[q].post;
+                a.mod[q] = ctx->mod[q];
+            }
+            a.p1inv_mod_p2 = ctx->p1inv_mod_p2;
+            n_tasks[j] = nb * 2 * G;
+            nbs[j] = nb;
+            st[j] = lanes >= 2 ? (hipStream_t)ctx->bign_lane_stream[j] : s;
+            used = j + 1;
         }
-        A.p1inv_mod_p2 = ctx->p1inv_mod_p2;
-        const uint32_t n_tasks = nb * 2 * G;
         for (uint32_t step = 0; step < n_steps; step++) {
-            A.step = step;
-            A.bskp_step = bskp + (size_t)step * 2 * R * 2 * N;
-            launch_cols_any(true, G, BS, A, nb, s);
-            // the XCD-aware order needs the task count to split evenly over 8 XCDs x 4 waves x (2G/8) combinations
-            const int xcd_aware = (2 * G) % 8 == 0 && n_tasks % 32 == 0 && (n_tasks / 8) % (2 * G / 8) == 0;
-            if (BS == 2048)
-                hipLaunchKernelGGL(k_big_rows, dim3((n_tasks + 3) / 4), dim3(256), 4 * TBUF * sizeof(double), s, A, G, n_tasks, xcd_aware);
-            else
-                hipLaunchKernelGGL(k_big_rows16, dim3((n_tasks + 3) / 4), dim3(256), 4 * (TBUF16 + 1024) * sizeof(double), s, A, G, n_tasks, xcd_aware);
-            launch_cols_any(false, G, BS, A, nb, s);
+            for (uint32_t j = 0; j < used; j++) {
+                bign_args &a = A[j];
+                a.step = step;
+                a.bskp_step = bskp + (size_t)step * 2 * R * 2 * N;
+                launch_cols_any(true, G, BS, a, nbs[j], st[j]);
+                // the XCD-aware order needs the task count to split evenly over 8 XCDs x 4 waves x (2G/8) combinations
+                const int xcd_aware = (2 * G) % 8 == 0 && n_tasks[j] % 32 == 0 && (n_tasks[j] / 8) % (2 * G / 8) == 0;
+                if (BS == 2048)
+                    hipLaunchKernelGGL(k_big_rows, dim3((n_tasks[j] + 3) / 4), dim3(256), 4 * TBUF * sizeof(double), st[j], a, G,
+                                       n_tasks[j], xcd_aware);
+                else
+                    hipLaunchKernelGGL(k_big_rows16, dim3((n_tasks[j] + 3) / 4), dim3(256), 4 * (TBUF16 + 1024) * sizeof(double), st[j], a,
+                                       G, n_tasks[j], xcd_aware);
+                launch_cols_any(false, G, BS, a, nbs[j], st[j]);
+            }
+        }
+    }
+    if (lanes >= 2) {
+        for (uint32_t j = 0; j < lanes; j++) {
+            SLZ_HIP(hipEventRecord((hipEvent_t)ctx->bign_lane_done[j], (hipStream_t)ctx->bign_lane_stream[j]));
+            SLZ_HIP(hipStreamWaitEvent(s, (hipEvent_t)ctx->bign_lane_done[j], 0));
         }
     }
     SLZ_HIP(hipGetLastError());

@@ -52,6 +52,8 @@ struct slz_ctx {
     double *bign_rowA;        // [2][G][64] block-specific lane-uniform forward twiddles
     double *bign_rowB;        // [2][G][31][64] block-specific per-lane forward twiddles
     int has_bign16;           // large-N path with 1024-blocks available (N = 1024 G', G' = 2..32, k = 1)
+    int bign_lanes;           // 1: one chunk at a time on the caller's stream; 2: two half chunks on two internal streams
+    void *bign_lane_stream[2], *bign_lane_done[2], *bign_fork;   // hipStream_t / hipEvent_t of the lanes, created at first use
     int bign_block;           // block size the large-N path uses: 1024 or 2048
     double *bign16_rowA;      // [2][G'][64] as bign_rowA for 1024-blocks
     double *bign16_rowB;      // [2][G'][15][64] per-lane twiddles of the last four forward stages of a 1024-block

@@ -385,6 +385,27 @@ def test_large_n_worst_case_magnitudes(slz, orc, block):
     assert np.array_equal(got, want)
 
 
+def test_large_n_two_lanes_match_one_lane_and_oracle(slz, orc):
+    # 70 ciphertexts at N = 16384: chunks of 64 + 6 on two internal streams (the default) against one chunk at a time
+    p = tiny(n=2, N=16384, k=1, pbs_base_log=15, pbs_level=1)
+    case = Case(slz, orc, p, 70, raw_inputs=True)
+    assert case.ctx.path == "three_pass_large_n"
+    two = slz.to_host_u64(case.ctx.pbs_batch(case.d_cts, case.d_luts, case.d_idx, case.d_bsk))
+    again = slz.to_host_u64(case.ctx.pbs_batch(case.d_cts, case.d_luts, case.d_idx, case.d_bsk))
+    case.ctx.set_option(slz.SLZ_OPT_LARGE_N_LANES, 1)
+    one = slz.to_host_u64(case.ctx.pbs_batch(case.d_cts, case.d_luts, case.d_idx, case.d_bsk))
+    assert np.array_equal(two, one) and np.array_equal(again, one)
+    idx = np.array([0, 63, 64, 69])
+    want = orc.pbs_batch(p, case.cts[idx], case.luts, case.lut_idx[idx], case.keys.bsk)
+    assert np.array_equal(two[idx], want)
+    case.ctx.set_option(slz.SLZ_OPT_LARGE_N_LANES, 2)
+    acc2 = slz.to_host_u64(case.ctx.blind_rotate_batch(case.d_cts, case.d_luts, case.d_idx, case.d_bsk, 1))
+    want_acc = orc.blind_rotate_batch(p, case.cts[idx], case.luts, case.lut_idx[idx], case.keys.bsk, 1)
+    assert np.array_equal(acc2[idx], want_acc)
+    with pytest.raises(slz.SlzError):
+        case.ctx.set_option(slz.SLZ_OPT_LARGE_N_LANES, 3)
+
+
 def test_work_is_enqueued_on_the_callers_stream(slz, orc):
     # a non-default torch stream: the library must launch on the hipStream_t it is given (same HIP runtime as torch)
     p, case = _fused_case(slz, orc, 3, 7)
