@@ -145,3 +145,17 @@ def test_matmul_highres_luts_match_oracle_tables(orc):
         slz.matmul_highres_luts(p, (33, 31), 1, 1, 1)               # moduli are at most 5 bits wide
     with pytest.raises(slz.SlzError):
         slz.matmul_highres_luts(p.with_(msg_bits=7), (31, 30), 1, 1, 1)
+
+
+def test_headers_are_plain_c():
+    """The boundary is a C ABI: both headers must compile as C99 on their own."""
+    import shutil
+    import subprocess
+    gcc = shutil.which("gcc")
+    if gcc is None:
+        pytest.skip("no C compiler")
+    inc = os.path.join(os.path.dirname(os.path.dirname(os.path.abspath(__file__))), "include")
+    for h in ("silenzio_pbs.h", "silenzio_gadgets.h"):
+        r = subprocess.run([gcc, "-std=c99", "-Wall", "-Wextra", "-pedantic", "-Werror", "-fsyntax-only", "-x", "c", os.path.join(inc, h)],
+                           capture_output=True, text=True)
+        assert r.returncode == 0, r.stderr
