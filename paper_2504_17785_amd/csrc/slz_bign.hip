@@ -345,7 +345,7 @@ static bool block_fits(uint32_t N, uint32_t BS) {
 }
 
 // block-specific forward tables for blocks of BS = 64 * E coefficients (E = 32 or 16 per lane)
-static int build_row_tables(slz_ctx *ctx, uint32_t BS, double **dA, double **dB) {
+int slz_build_block_tables(slz_ctx *ctx, uint32_t BS, double **dA, double **dB) {
     const uint32_t N = ctx->prm.N, G = N / BS, E = BS / 64;
     int late = 0;                                   // stages done after the transposition: log2 E
     for (uint32_t e = E; e > 1; e >>= 1) late++;
@@ -404,14 +404,14 @@ int slz_bign_init(slz_ctx *ctx) {
     ctx->bign_lanes = 2;
     bool any = false;
     if (block_fits(N, 2048) && bounds_ok(N, 2048)) {
-        int rc = build_row_tables(ctx, 2048, &ctx->bign_rowA, &ctx->bign_rowB);
+        int rc = slz_build_block_tables(ctx, 2048, &ctx->bign_rowA, &ctx->bign_rowB);
         if (rc != SLZ_OK) return rc;
         SLZ_HIP(hipFuncSetAttribute((const void *)k_big_rows, hipFuncAttributeMaxDynamicSharedMemorySize, 4 * TBUF * sizeof(double)));
         ctx->bign_block = 2048;
         any = true;
     }
     if (block_fits(N, 1024) && bounds_ok(N, 1024)) {
-        int rc = build_row_tables(ctx, 1024, &ctx->bign16_rowA, &ctx->bign16_rowB);
+        int rc = slz_build_block_tables(ctx, 1024, &ctx->bign16_rowA, &ctx->bign16_rowB);
         if (rc != SLZ_OK) return rc;
         SLZ_HIP(hipFuncSetAttribute((const void *)k_big_rows16, hipFuncAttributeMaxDynamicSharedMemorySize, 4 * (TBUF16 + 1024) * sizeof(double)));
         ctx->has_bign16 = 1;

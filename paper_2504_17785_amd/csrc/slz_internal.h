@@ -41,6 +41,8 @@ struct slz_ctx {
     int device;
     int force_generic;
     int has_fused;
+    int has_fused1024;        // the N = 1024 fused kernel is available
+    double *fused1024_rowA, *fused1024_rowB;   // its forward tables: [2][64] and [2][15][64]
     uint32_t logN;
     slz_mod mod[2];
     double two32[2];          // 2^32 mod p_i (centred)
@@ -84,6 +86,17 @@ int slz_generic_bsk_prepare(slz_ctx *ctx, const uint64_t *bsk, double *dst, hipS
 int slz_generic_blind_rotate(slz_ctx *ctx, const uint64_t *lwe_in, const uint64_t *luts, const uint32_t *lut_idx,
                              const double *bskp, uint32_t n_steps, uint64_t *acc_out, uint64_t *lwe_out,
                              uint32_t batch, hipStream_t s);
+// fused path for N = 1024 (slz_fused_n1024.hip)
+int slz_fused1024_supported(const slz_params *p);
+int slz_fused1024_init(slz_ctx *ctx);
+void slz_fused1024_destroy(slz_ctx *ctx);
+int slz_fused1024_blind_rotate(slz_ctx *ctx, const uint64_t *lwe_in, const uint64_t *luts, const uint32_t *lut_idx,
+                               const double *bskp, uint32_t n_steps, uint64_t *acc_out, uint64_t *lwe_out, uint32_t batch,
+                               hipStream_t s);
+// forward twiddle tables of the blocks of size BS of the wave-level transforms (slz_bign.hip): *dA [2][N/BS][64],
+// *dB [2][N/BS][BS/64 - 1][64], device memory owned by the caller
+int slz_build_block_tables(slz_ctx *ctx, uint32_t BS, double **dA, double **dB);
+
 // fused path (slz_fused.hip)
 int slz_fused_supported(const slz_params *p);
 int slz_fused_init(slz_ctx *ctx);

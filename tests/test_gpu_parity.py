@@ -325,6 +325,61 @@ def test_fused_more_ciphertexts_than_resident_workgroups(slz, orc):
     assert np.array_equal(fused[idx], want)
 
 
+# ---------------------------------------------------------------- fused kernel for N = 1024 (k = 1, l = 1)
+
+@pytest.mark.parametrize("beta", [23, 8, 16, 24])
+def test_fused_n1024_states_and_outputs_match_oracle(slz, orc, beta):
+    p = tiny(n=4, N=1024, k=1, pbs_base_log=beta, pbs_level=1)
+    case = Case(slz, orc, p, 7, raw_inputs=True)
+    assert case.ctx.path == "fused_n1024"
+    for steps in sorted({0, 1, 2, p.n}):
+        want = orc.blind_rotate_batch(p, case.cts, case.luts, case.lut_idx, case.keys.bsk, steps)
+        got = slz.to_host_u64(case.ctx.blind_rotate_batch(case.d_cts, case.d_luts, case.d_idx, case.d_bsk, steps))
+        assert np.array_equal(got, want), "accumulators differ after %d steps" % steps
+    want = orc.pbs_batch(p, case.cts, case.luts, case.lut_idx, case.keys.bsk)
+    assert np.array_equal(slz.to_host_u64(case.ctx.pbs_batch(case.d_cts, case.d_luts, case.d_idx, case.d_bsk)), want)
+    want0 = orc.pbs_batch(p, case.cts, case.luts, None, case.keys.bsk)
+    assert np.array_equal(slz.to_host_u64(case.ctx.pbs_batch(case.d_cts, case.d_luts, None, case.d_bsk)), want0)
+    case.ctx.set_option(slz.SLZ_OPT_FORCE_GENERIC, 1)
+    assert case.ctx.path == "generic"
+    assert np.array_equal(slz.to_host_u64(case.ctx.pbs_batch(case.d_cts, case.d_luts, case.d_idx, case.d_bsk)), want)
+
+
+def test_fused_n1024_worst_case_magnitudes(slz, orc):
+    p = tiny(n=3, N=1024, k=1, pbs_base_log=24, pbs_level=1)      # 2 * 1024 * 2^23 * 2^63 = 2^97: the largest sums allowed
+    case = Case(slz, orc, p, 3, raw_inputs=True)
+    assert case.ctx.path == "fused_n1024"
+    bsk = case.keys.bsk.copy()
+    flat = bsk.reshape(-1)
+    flat[0::3] = np.uint64(1 << 63)
+    flat[1::3] = np.uint64((1 << 63) - 1)
+    luts = case.luts.copy()
+    luts[:, 0::2] = np.uint64((1 << 63) - (1 << 39))      # decomposes to digit +-2^23
+    luts[:, 1::2] = np.uint64(1 << 63)
+    d_bsk = case.ctx.bsk_prepare(slz.to_device_u64(bsk))
+    want = orc.blind_rotate_batch(p, case.cts, luts, case.lut_idx, bsk, p.n)
+    got = slz.to_host_u64(case.ctx.blind_rotate_batch(case.d_cts, slz.to_device_u64(luts), case.d_idx, d_bsk, p.n))
+    assert np.array_equal(got, want)
+
+
+def test_fused_n1024_more_ciphertexts_than_resident_workgroups_and_decryption(slz, orc):
+    # 600 ciphertexts > 512 resident workgroups; real encryptions: the whole batch decrypts to the tables
+    p = tiny(n=16, N=1024, k=1, pbs_base_log=23, pbs_level=1, ks_base_log=4, ks_level=4, msg_bits=3, sigma_lwe=2.0 ** -30,
+             sigma_bsk=2.0 ** -50)
+    case = Case(slz, orc, p, 600)
+    assert case.ctx.path == "fused_n1024"
+    big = case.ctx.pbs_batch(case.d_cts, case.d_luts, case.d_idx, case.d_bsk)
+    fused = slz.to_host_u64(big)
+    small = slz.to_host_u64(case.ctx.keyswitch_batch(big, case.d_ksk))
+    got, _ = orc.decode(orc.lwe_phase(case.keys.lwe_sk, small), p.msg_bits)
+    assert np.array_equal(got, case.tables[case.lut_idx.astype(np.int64), case.msgs.astype(np.int64)])
+    idx = np.array([0, 1, 255, 511, 512, 513, 599])
+    want = orc.pbs_batch(p, case.cts[idx], case.luts, case.lut_idx[idx], case.keys.bsk)
+    assert np.array_equal(fused[idx], want)
+    case.ctx.set_option(slz.SLZ_OPT_FORCE_GENERIC, 1)
+    assert np.array_equal(slz.to_host_u64(case.ctx.pbs_batch(case.d_cts, case.d_luts, case.d_idx, case.d_bsk)), fused)
+
+
 # ---------------------------------------------------------------- large-N three-pass path (N = 2048 G, k = 1)
 
 @pytest.mark.parametrize("shape", [
