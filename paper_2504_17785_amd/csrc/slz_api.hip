@@ -51,6 +51,11 @@ extern "C" int slz_ctx_create(const slz_params *params, uint32_t max_batch, slz_
         ctx->has_fused = (rc == SLZ_OK);
         if (rc == SLZ_E_UNSUPPORTED) rc = SLZ_OK;
     }
+    if (rc == SLZ_OK && slz_fused4096_supported(params)) {
+        rc = slz_fused4096_init(ctx);
+        ctx->has_fused4096 = (rc == SLZ_OK);
+        if (rc == SLZ_E_UNSUPPORTED) rc = SLZ_OK;
+    }
     if (rc == SLZ_OK && slz_fused1024_supported(params)) {
         rc = slz_fused1024_init(ctx);
         ctx->has_fused1024 = (rc == SLZ_OK);
@@ -70,6 +75,7 @@ extern "C" int slz_ctx_destroy(slz_ctx *ctx) {
     if (!ctx) return SLZ_E_INVALID_ARG;
     slz_fused_destroy(ctx);
     slz_fused1024_destroy(ctx);
+    slz_fused4096_destroy(ctx);
     slz_bign_destroy(ctx);
     slz_ksm_destroy(ctx);
     slz_lcm_destroy(ctx);
@@ -104,6 +110,7 @@ extern "C" const char *slz_pbs_path(const slz_ctx *ctx) {
     if (!ctx) return "none";
     if (ctx->force_generic) return "generic";
     if (ctx->has_fused1024) return "fused_n1024";
+    if (ctx->has_fused4096) return "fused_n4096";
     return ctx->has_fused ? "fused_n2048" : (ctx->has_bign ? "three_pass_large_n" : "generic");
 }
 
@@ -170,6 +177,8 @@ static int blind_rotate_common(slz_ctx *ctx, const uint64_t *lwe_in, const uint6
     hipStream_t s = (hipStream_t)hip_stream;
     if (ctx->has_fused && !ctx->force_generic)
         return slz_fused_blind_rotate(ctx, lwe_in, luts, lut_idx, (const double *)bskp, n_steps, acc_out, lwe_out, batch, s);
+    if (ctx->has_fused4096 && !ctx->force_generic)
+        return slz_fused4096_blind_rotate(ctx, lwe_in, luts, lut_idx, (const double *)bskp, n_steps, acc_out, lwe_out, batch, s);
     if (ctx->has_fused1024 && !ctx->force_generic)
         return slz_fused1024_blind_rotate(ctx, lwe_in, luts, lut_idx, (const double *)bskp, n_steps, acc_out, lwe_out, batch, s);
     int rc = ensure_generic_scratch(ctx);

@@ -380,6 +380,55 @@ def test_fused_n1024_more_ciphertexts_than_resident_workgroups_and_decryption(sl
     assert np.array_equal(slz.to_host_u64(case.ctx.pbs_batch(case.d_cts, case.d_luts, case.d_idx, case.d_bsk)), fused)
 
 
+# ---------------------------------------------------------------- fused kernel for N = 4096 (k = 1, l = 1)
+
+@pytest.mark.parametrize("beta", [22, 8, 16])
+def test_fused_n4096_states_and_outputs_match_oracle(slz, orc, beta):
+    p = tiny(n=3, N=4096, k=1, pbs_base_log=beta, pbs_level=1)
+    case = Case(slz, orc, p, 5, raw_inputs=True)
+    assert case.ctx.path == "fused_n4096"
+    for steps in sorted({0, 1, 2, p.n}):
+        want = orc.blind_rotate_batch(p, case.cts, case.luts, case.lut_idx, case.keys.bsk, steps)
+        got = slz.to_host_u64(case.ctx.blind_rotate_batch(case.d_cts, case.d_luts, case.d_idx, case.d_bsk, steps))
+        assert np.array_equal(got, want), "accumulators differ after %d steps" % steps
+    want = orc.pbs_batch(p, case.cts, case.luts, case.lut_idx, case.keys.bsk)
+    assert np.array_equal(slz.to_host_u64(case.ctx.pbs_batch(case.d_cts, case.d_luts, case.d_idx, case.d_bsk)), want)
+    want0 = orc.pbs_batch(p, case.cts, case.luts, None, case.keys.bsk)
+    assert np.array_equal(slz.to_host_u64(case.ctx.pbs_batch(case.d_cts, case.d_luts, None, case.d_bsk)), want0)
+    case.ctx.set_option(slz.SLZ_OPT_FORCE_GENERIC, 1)
+    assert np.array_equal(slz.to_host_u64(case.ctx.pbs_batch(case.d_cts, case.d_luts, case.d_idx, case.d_bsk)), want)
+
+
+def test_fused_n4096_worst_case_magnitudes(slz, orc):
+    p = tiny(n=2, N=4096, k=1, pbs_base_log=22, pbs_level=1)      # 2 * 4096 * 2^21 * 2^63 = 2^97: the largest sums allowed
+    case = Case(slz, orc, p, 3, raw_inputs=True)
+    assert case.ctx.path == "fused_n4096"
+    bsk = case.keys.bsk.copy()
+    flat = bsk.reshape(-1)
+    flat[0::3] = np.uint64(1 << 63)
+    flat[1::3] = np.uint64((1 << 63) - 1)
+    luts = case.luts.copy()
+    luts[:, 0::2] = np.uint64((1 << 63) - (1 << 41))      # decomposes to digit +-2^21
+    luts[:, 1::2] = np.uint64(1 << 63)
+    d_bsk = case.ctx.bsk_prepare(slz.to_device_u64(bsk))
+    want = orc.blind_rotate_batch(p, case.cts, luts, case.lut_idx, bsk, p.n)
+    got = slz.to_host_u64(case.ctx.blind_rotate_batch(case.d_cts, slz.to_device_u64(luts), case.d_idx, d_bsk, p.n))
+    assert np.array_equal(got, want)
+
+
+def test_fused_n4096_more_ciphertexts_than_resident_workgroups(slz, orc):
+    # 300 ciphertexts > 256 resident workgroups; all against the generic path, a sample against the oracle
+    p = tiny(n=3, N=4096, k=1, pbs_base_log=22, pbs_level=1)
+    case = Case(slz, orc, p, 300, raw_inputs=True)
+    assert case.ctx.path == "fused_n4096"
+    fused = slz.to_host_u64(case.ctx.pbs_batch(case.d_cts, case.d_luts, case.d_idx, case.d_bsk))
+    idx = np.array([0, 1, 255, 256, 257, 299])
+    want = orc.pbs_batch(p, case.cts[idx], case.luts, case.lut_idx[idx], case.keys.bsk)
+    assert np.array_equal(fused[idx], want)
+    case.ctx.set_option(slz.SLZ_OPT_FORCE_GENERIC, 1)
+    assert np.array_equal(slz.to_host_u64(case.ctx.pbs_batch(case.d_cts, case.d_luts, case.d_idx, case.d_bsk)), fused)
+
+
 # ---------------------------------------------------------------- large-N three-pass path (N = 2048 G, k = 1)
 
 @pytest.mark.parametrize("shape", [
