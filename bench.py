@@ -284,6 +284,7 @@ def main():
     ap.add_argument("--batch", type=int, default=0, help="override the configuration's batch size")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--generic", action="store_true", help="force the generic multi-kernel path")
+    ap.add_argument("--override", default="", help="comma-separated parameter overrides of the configuration, e.g. N=4096,pbs_base_log=22,n=256")
     ap.add_argument("--large-n-lanes", type=int, default=0, help="large-N path: 1 = one chunk at a time, 2 = two half chunks on two streams")
     ap.add_argument("--calib-copy", action="store_true",
                     help="also run one plain device copy of 256 MiB (a known-size kernel to scale FETCH_SIZE/WRITE_SIZE by)")
@@ -307,6 +308,9 @@ def main():
     import paper_2504_17785_amd as slz
 
     p = synth.CONFIGS[args.config]
+    if args.override:       # another shape with the configuration's tables and message space, e.g. N=4096,pbs_base_log=22,n=256
+        kw = {k.strip(): int(v) for k, v in (item.split("=") for item in args.override.split(","))}
+        p = p.with_(name="%s+%s" % (p.name, args.override), **kw)
     batch = args.batch or p.batch
     torch.cuda.set_device(0)
     ctx = slz.Context(p, batch)
