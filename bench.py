@@ -285,6 +285,7 @@ def main():
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--generic", action="store_true", help="force the generic multi-kernel path")
     ap.add_argument("--override", default="", help="comma-separated parameter overrides of the configuration, e.g. N=4096,pbs_base_log=22,n=256")
+    ap.add_argument("--large-n-block", type=int, default=0, help="large-N path: block size of the row pass, 1024 or 2048")
     ap.add_argument("--large-n-lanes", type=int, default=0, help="large-N path: 1 = one chunk at a time, 2 = two half chunks on two streams")
     ap.add_argument("--calib-copy", action="store_true",
                     help="also run one plain device copy of 256 MiB (a known-size kernel to scale FETCH_SIZE/WRITE_SIZE by)")
@@ -318,6 +319,8 @@ def main():
         ctx.set_option(slz.SLZ_OPT_FORCE_GENERIC, 1)
     if args.large_n_lanes:
         ctx.set_option(slz.SLZ_OPT_LARGE_N_LANES, args.large_n_lanes)
+    if args.large_n_block:
+        ctx.set_option(slz.SLZ_OPT_LARGE_N_BLOCK, args.large_n_block)
 
     # ---- synthetic inputs, resident in HBM ----
     R, C = (p.k + 1) * p.pbs_level, p.k + 1
