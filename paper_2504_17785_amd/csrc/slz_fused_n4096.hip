@@ -176,6 +176,15 @@ k_fused_blind_rotate_n4096(fused4096_args A) {
             __syncthreads();                          // sibling has read my buffer before I reuse it
             // 4. inverse transform inside the block, then the stage across the two blocks and the twist
             fused_inv<false>(x, T, twS, invt, post, m, lane, z);
+            // twiddles of the stage across the blocks (inv[2048 + c]) and the twist (post[2048 b + c]), c = 64 e + lane: requested
+            // one group of four coefficients ahead of their use, the first group before the exchange
+            double wv[2][4], pw[2][4];
+#pragma unroll
+            for (int u = 0; u < 4; u++) {
+                wv[0][u] = ldl(invt + 2048 + 64 * u + z, lane * 8u);
+                pw[0][u] = ldl(post + 2048 * b + 64 * u + z, lane * 8u);
+            }
+            SCHED_FENCE();
             wave_sync();
 #pragma unroll
             for (int g = 0; g < 4; g++) {
@@ -189,20 +198,28 @@ k_fused_blind_rotate_n4096(fused4096_args A) {
             __syncthreads();
 #pragma unroll
             for (int g = 0; g < 8; g++) {
-                double y1[4], wv[4], pw[4], v4[4], r4[4];
+                SCHED_FENCE();
+                if (g < 7) {
+#pragma unroll
+                    for (int u = 0; u < 4; u++) {
+                        wv[(g + 1) & 1][u] = ldl(invt + 2048 + 64 * (4 * (g + 1) + u) + z, lane * 8u);
+                        pw[(g + 1) & 1][u] = ldl(post + 2048 * b + 64 * (4 * (g + 1) + u) + z, lane * 8u);
+                    }
+                }
+                SCHED_FENCE();
+                double y1[4], v4[4], r4[4], s4[4];
 #pragma unroll
                 for (int u = 0; u < 4; u++) {
                     const double other = Tblk[64 * (4 * g + u) + lane];
                     y1[u] = b ? x[4 * g + u] : other;                                    // the value of block 1
                     if (b) x[4 * g + u] = other;                                         // x now holds the value of block 0
-                    wv[u] = ldl(invt + 2048 + 64 * (4 * g + u) + z, lane * 8u);
-                    pw[u] = ldl(post + 2048 * b + 64 * (4 * g + u) + z, lane * 8u);
                 }
-                mulmod_k<4>(v4, y1, wv, m);
-                double s4[4];
+                const double wg[4] = {wv[g & 1][0], wv[g & 1][1], wv[g & 1][2], wv[g & 1][3]};
+                const double pg[4] = {pw[g & 1][0], pw[g & 1][1], pw[g & 1][2], pw[g & 1][3]};
+                mulmod_k<4>(v4, y1, wg, m);
 #pragma unroll
                 for (int u = 0; u < 4; u++) s4[u] = b ? x[4 * g + u] - v4[u] : x[4 * g + u] + v4[u];
-                mulmod_k<4>(r4, s4, pw, m);
+                mulmod_k<4>(r4, s4, pg, m);
 #pragma unroll
                 for (int u = 0; u < 4; u++) x[4 * g + u] = r4[u];
             }
