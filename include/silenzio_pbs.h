@@ -79,6 +79,11 @@ typedef struct slz_ctx slz_ctx;   /* opaque: parameter copy, twiddle tables, scr
                                      overlaps the memory-bound column passes of the other; results are identical);
                                      SLZ_E_INVALID_ARG when the context has no large-N path */
 
+/* Allocation and graph capture: slz_pbs_batch, slz_blind_rotate_batch, slz_keyswitch_batch and slz_ks_pbs_batch allocate
+ * their scratch (and the large-N path its two internal streams) in the first call on a context; later calls with a batch
+ * no larger than max_batch record only kernels and event edges on the given stream and may be captured into a HIP graph
+ * (warm up once outside the capture). */
+
 /* Creates a context on the current device.  Allocates transform tables and scratch sized for
  * `max_batch` ciphertexts.  Fails with SLZ_E_UNSUPPORTED when the exactness bound
  * 4 * (k+1) * l * N * 2^(beta-1) * 2^63 <= p1 * p2 (the two ~2^50 transform primes) does not hold. */

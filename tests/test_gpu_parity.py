@@ -581,3 +581,45 @@ def test_keyswitch_first_error_codes(slz, orc):
     assert call(b + 4, k, l, None, 2, q, b, 4) == slz.SLZ_E_INVALID_ARG
     assert call(b, k + 8, l, None, 2, q, b, 4) == slz.SLZ_E_INVALID_ARG
     torch.cuda.synchronize()
+
+
+# ---- HIP graph capture -----------------------------------------------------------------------------------------------------
+@pytest.mark.parametrize("shape,batch", [(dict(n=5, N=2048, k=1, pbs_base_log=23, pbs_level=1, ks_base_log=4, ks_level=8), 40),
+                                         (dict(n=3, N=1024, k=1, pbs_base_log=23, pbs_level=1), 9),
+                                         (dict(n=6, N=256, k=2, pbs_base_log=8, pbs_level=2), 7),
+                                         (dict(n=2, N=16384, k=1, pbs_base_log=15, pbs_level=1), 70)],
+                         ids=["fused_n2048", "fused_n1024", "generic_k2", "large_n_two_lanes"])
+def test_lookup_replays_from_a_hip_graph(slz, orc, shape, batch):
+    """A serving loop captures one lookup (bootstrapping + keyswitch) once and replays it: after a warm-up call (which makes
+    the library's lazy allocations) the calls record nothing but kernels and event edges, and every replay on new inputs
+    matches the eager result."""
+    p = tiny(**shape)
+    case = Case(slz, orc, p, batch, raw_inputs=True)
+    d_in = case.d_cts.clone()
+    big = torch.empty((batch, p.k * p.N + 1), dtype=torch.int64, device="cuda")
+    small = torch.empty((batch, p.n + 1), dtype=torch.int64, device="cuda")
+
+    def lookup():
+        case.ctx.pbs_batch(d_in, case.d_luts, case.d_idx, case.d_bsk, out=big)
+        case.ctx.keyswitch_batch(big, case.d_ksk, out=small)
+
+    lookup()                                             # warm-up outside the capture
+    torch.cuda.synchronize()
+    graph = torch.cuda.CUDAGraph()
+    with torch.cuda.graph(graph):
+        lookup()
+    for rep in range(3):
+        cts = synth.raw_words(p, "raw_ct", batch * (p.n + 1), offset=1000 * (rep + 1)).reshape(batch, p.n + 1)
+        d_in.copy_(slz.to_device_u64(cts))
+        big.zero_(); small.zero_()
+        graph.replay()
+        torch.cuda.synchronize()
+        got_big, got_small = slz.to_host_u64(big), slz.to_host_u64(small)
+        lookup()                                         # the program's own eager work between replays
+        torch.cuda.synchronize()
+        assert np.array_equal(got_big, slz.to_host_u64(big)) and np.array_equal(got_small, slz.to_host_u64(small)), rep
+        if rep == 0:
+            idx = np.array([0, batch - 1])
+            want = orc.pbs_batch(p, cts[idx], case.luts, case.lut_idx[idx], case.keys.bsk)
+            assert np.array_equal(got_big[idx], want)
+            assert np.array_equal(got_small[idx], orc.keyswitch_batch(p, want, case.keys.ksk))
