@@ -149,8 +149,8 @@ int slz_ks_pbs_batch(slz_ctx *ctx, const uint64_t *lwe_in_dev, const uint64_t *k
 int slz_lwe_lincomb_batch(slz_ctx *ctx, const uint64_t *cts_dev, const int32_t *w_dev,
                           uint64_t *out_dev, uint32_t G, uint32_t J, uint32_t O, void *hip_stream);
 
-/* Name of the kernel path slz_pbs_batch will use for this context ("fused_n2048", "fused_n1024", "fused_n4096",
- * "three_pass_large_n", "generic"). */
+/* Name of the kernel path slz_pbs_batch will use for this context ("fused_n512", "fused_n1024", "fused_n2048",
+ * "fused_n4096", "three_pass_large_n", "generic"). */
 const char *slz_pbs_path(const slz_ctx *ctx);
 
 const char *slz_strerror(int code);

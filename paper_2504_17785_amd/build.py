@@ -8,7 +8,7 @@ import subprocess
 HERE = os.path.dirname(os.path.abspath(__file__))
 CSRC = os.path.join(HERE, "csrc")
 LIB = os.path.join(HERE, "libsilenzio_pbs.so")
-SOURCES = ["slz_api.hip", "slz_tables.hip", "slz_generic.hip", "slz_fused.hip", "slz_fused_n1024.hip", "slz_fused_n4096.hip", "slz_bign.hip", "slz_keyswitch.hip", "slz_keyswitch_mfma.hip",
+SOURCES = ["slz_api.hip", "slz_tables.hip", "slz_generic.hip", "slz_fused.hip", "slz_fused_n512.hip", "slz_fused_n1024.hip", "slz_fused_n4096.hip", "slz_bign.hip", "slz_keyswitch.hip", "slz_keyswitch_mfma.hip",
            "slz_lincomb_mfma.hip", "slz_matmul_rns.hip", "slz_loss.hip"]
 FLAGS = ["--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-ffp-contract=off", "-Wall", "-Wno-unused-function",
          "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops"]

@@ -56,6 +56,11 @@ extern "C" int slz_ctx_create(const slz_params *params, uint32_t max_batch, slz_
         ctx->has_fused4096 = (rc == SLZ_OK);
         if (rc == SLZ_E_UNSUPPORTED) rc = SLZ_OK;
     }
+    if (rc == SLZ_OK && slz_fused512_supported(params)) {
+        rc = slz_fused512_init(ctx);
+        ctx->has_fused512 = (rc == SLZ_OK);
+        if (rc == SLZ_E_UNSUPPORTED) rc = SLZ_OK;
+    }
     if (rc == SLZ_OK && slz_fused1024_supported(params)) {
         rc = slz_fused1024_init(ctx);
         ctx->has_fused1024 = (rc == SLZ_OK);
@@ -75,6 +80,7 @@ extern "C" int slz_ctx_destroy(slz_ctx *ctx) {
     if (!ctx) return SLZ_E_INVALID_ARG;
     slz_fused_destroy(ctx);
     slz_fused1024_destroy(ctx);
+    slz_fused512_destroy(ctx);
     slz_fused4096_destroy(ctx);
     slz_bign_destroy(ctx);
     slz_ksm_destroy(ctx);
@@ -110,6 +116,7 @@ extern "C" const char *slz_pbs_path(const slz_ctx *ctx) {
     if (!ctx) return "none";
     if (ctx->force_generic) return "generic";
     if (ctx->has_fused1024) return "fused_n1024";
+    if (ctx->has_fused512) return "fused_n512";
     if (ctx->has_fused4096) return "fused_n4096";
     return ctx->has_fused ? "fused_n2048" : (ctx->has_bign ? "three_pass_large_n" : "generic");
 }
@@ -179,6 +186,8 @@ static int blind_rotate_common(slz_ctx *ctx, const uint64_t *lwe_in, const uint6
         return slz_fused_blind_rotate(ctx, lwe_in, luts, lut_idx, (const double *)bskp, n_steps, acc_out, lwe_out, batch, s);
     if (ctx->has_fused4096 && !ctx->force_generic)
         return slz_fused4096_blind_rotate(ctx, lwe_in, luts, lut_idx, (const double *)bskp, n_steps, acc_out, lwe_out, batch, s);
+    if (ctx->has_fused512 && !ctx->force_generic)
+        return slz_fused512_blind_rotate(ctx, lwe_in, luts, lut_idx, (const double *)bskp, n_steps, acc_out, lwe_out, batch, s);
     if (ctx->has_fused1024 && !ctx->force_generic)
         return slz_fused1024_blind_rotate(ctx, lwe_in, luts, lut_idx, (const double *)bskp, n_steps, acc_out, lwe_out, batch, s);
     int rc = ensure_generic_scratch(ctx);

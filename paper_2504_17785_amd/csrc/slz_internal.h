@@ -45,6 +45,8 @@ struct slz_ctx {
     double *fused4096_rowA, *fused4096_rowB;   // its block tables: [2][2][64] and [2][2][31][64]
     double fused4096_scalars[2][128];          // host copy of fused4096_rowA (lane-uniform entries go into the kernel arguments)
     double fused4096_w1[2];                    // fwd[1] per prime: the twiddle of the stage across the two blocks
+    int has_fused512;         // the N = 512 fused kernel is available
+    double *fused512_rowA, *fused512_rowB;     // its forward tables: [2][64] and [2][15][64]
     int has_fused1024;        // the N = 1024 fused kernel is available
     double *fused1024_rowA, *fused1024_rowB;   // its forward tables: [2][64] and [2][15][64]
     uint32_t logN;
@@ -97,6 +99,13 @@ void slz_fused4096_destroy(slz_ctx *ctx);
 int slz_fused4096_blind_rotate(slz_ctx *ctx, const uint64_t *lwe_in, const uint64_t *luts, const uint32_t *lut_idx,
                                const double *bskp, uint32_t n_steps, uint64_t *acc_out, uint64_t *lwe_out, uint32_t batch,
                                hipStream_t s);
+// fused path for N = 512 (slz_fused_n512.hip)
+int slz_fused512_supported(const slz_params *p);
+int slz_fused512_init(slz_ctx *ctx);
+void slz_fused512_destroy(slz_ctx *ctx);
+int slz_fused512_blind_rotate(slz_ctx *ctx, const uint64_t *lwe_in, const uint64_t *luts, const uint32_t *lut_idx,
+                              const double *bskp, uint32_t n_steps, uint64_t *acc_out, uint64_t *lwe_out, uint32_t batch,
+                              hipStream_t s);
 // fused path for N = 1024 (slz_fused_n1024.hip)
 int slz_fused1024_supported(const slz_params *p);
 int slz_fused1024_init(slz_ctx *ctx);

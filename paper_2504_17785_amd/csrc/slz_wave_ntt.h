@@ -305,13 +305,16 @@ __device__ __forceinline__ void swap16(double &a, double &b) {
 // Forward.  In: layout A, |x| tiny (digits after the column stages, reduced).  Out: layout B, |x| <= 3.7 p.
 // twA: lane-uniform twiddles of this block, entry (sub-blocks m') + blk for m' = 1 .. 32 (64 doubles);
 // twB_tab: [15][64] per-lane twiddles of the last four stages.  Bounds: six stages 0.5 -> 4.81 p, reduction, four more -> 3.63 p.
+// PAIR: the 16 x 64 values are two independent 512-point polynomials (registers 0..7 and 8..15 on the way in, lanes
+// 0..31 and 32..63 on the way out): the stage that would pair them is left out and the tables carry each half's twiddles.
+template <bool PAIR = false>
 __device__ __forceinline__ void fwd16(double (&x)[16], double *T, const double *twA, const double *twB_tab, slz_mod m, uint32_t lane,
                                       int z) {
     const uint32_t hh = lane >> 5, v = (lane >> 4) & 1u, j = lane & 15u;
     // twA and twB_tab are expected in LDS (the kernel stages its block's tables there once): their reads do not queue
     // behind the kernel's global loads and need no registers until the stage that uses them
 #pragma unroll
-    for (int s = 0; s < 4; s++) {
+    for (int s = PAIR ? 1 : 0; s < 4; s++) {
         const int half = 8 >> s;
 #pragma unroll
         for (int g = 0; g < 2; g++) {
@@ -371,6 +374,9 @@ __device__ __forceinline__ void fwd16(double (&x)[16], double *T, const double *
 // twist).  In: layout B, |x| <= 0.51 p.  Out: layout A, |x| <= 6.2 p.  twS: lane-uniform entries inv[t + j], t <= 8;
 // inv: the same natural inverse table for the per-lane entries.  Bounds: 0.5 -> 1 -> 2 (unit twiddles) -> 2.88 -> 3.91,
 // reduction, six more stages -> 6.2.
+// PAIR: two independent 512-point polynomials (lanes 0..31 and 32..63 on the way in, registers 0..7 and 8..15 on the way
+// out): the last stage, which would pair them, is left out (and its twiddles, which lie past a 512-entry table, are not read).
+template <bool PAIR = false>
 __device__ __forceinline__ void inv16(double (&x)[16], double *T, const double *twS, const double *inv, slz_mod m, uint32_t lane, int z) {
     const uint32_t hh = lane >> 5, v = (lane >> 4) & 1u, j = lane & 15u, l5 = lane & 31u;
     double twL[15];
@@ -379,7 +385,7 @@ __device__ __forceinline__ void inv16(double (&x)[16], double *T, const double *
     {
         int kk = 0;
 #pragma unroll
-        for (int s = 0; s < 4; s++)
+        for (int s = 0; s < (PAIR ? 3 : 4); s++)
 #pragma unroll
             for (int jj = 0; jj < (1 << s); jj++) twL[kk++] = ldl(inv + 64 * (1 << s) + 64 * jj + z, lane * 8u);
     }
@@ -438,7 +444,7 @@ __device__ __forceinline__ void inv16(double (&x)[16], double *T, const double *
         for (int mm = 4 * g; mm < 4 * g + 4; mm++) swap32(x[2 * mm], x[2 * mm + 1]);
     }
 #pragma unroll
-    for (int s = 0; s < 4; s++) {                                                       // t = 64 .. 512
+    for (int s = 0; s < (PAIR ? 3 : 4); s++) {                                          // t = 64 .. 512
         const int half = 1 << s;
 #pragma unroll
         for (int g = 0; g < 2; g++) {

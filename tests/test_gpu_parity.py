@@ -325,6 +325,56 @@ def test_fused_more_ciphertexts_than_resident_workgroups(slz, orc):
     assert np.array_equal(fused[idx], want)
 
 
+# ---------------------------------------------------------------- fused kernel for N = 512 (k = 1 or 3, l = 1)
+
+@pytest.mark.parametrize("k,beta", [(3, 18), (3, 7), (1, 23), (1, 10)])
+def test_fused_n512_states_and_outputs_match_oracle(slz, orc, k, beta):
+    p = tiny(n=4, N=512, k=k, pbs_base_log=beta, pbs_level=1)
+    case = Case(slz, orc, p, 7, raw_inputs=True)
+    assert case.ctx.path == "fused_n512"
+    for steps in sorted({0, 1, 2, p.n}):
+        want = orc.blind_rotate_batch(p, case.cts, case.luts, case.lut_idx, case.keys.bsk, steps)
+        got = slz.to_host_u64(case.ctx.blind_rotate_batch(case.d_cts, case.d_luts, case.d_idx, case.d_bsk, steps))
+        assert np.array_equal(got, want), "accumulators differ after %d steps" % steps
+    want = orc.pbs_batch(p, case.cts, case.luts, case.lut_idx, case.keys.bsk)
+    assert np.array_equal(slz.to_host_u64(case.ctx.pbs_batch(case.d_cts, case.d_luts, case.d_idx, case.d_bsk)), want)
+    want0 = orc.pbs_batch(p, case.cts, case.luts, None, case.keys.bsk)
+    assert np.array_equal(slz.to_host_u64(case.ctx.pbs_batch(case.d_cts, case.d_luts, None, case.d_bsk)), want0)
+    case.ctx.set_option(slz.SLZ_OPT_FORCE_GENERIC, 1)
+    assert np.array_equal(slz.to_host_u64(case.ctx.pbs_batch(case.d_cts, case.d_luts, case.d_idx, case.d_bsk)), want)
+
+
+@pytest.mark.parametrize("k,beta", [(3, 24), (1, 25)])
+def test_fused_n512_worst_case_and_many_ciphertexts(slz, orc, k, beta):
+    # (k + 1) * 512 * 2^(beta - 1) * 2^63 = 2^97: the largest sums allowed
+    p = tiny(n=3, N=512, k=k, pbs_base_log=beta, pbs_level=1, ks_base_log=4, ks_level=4, msg_bits=2, sigma_lwe=2.0 ** -30,
+             sigma_bsk=2.0 ** -50)
+    case = Case(slz, orc, p, 3, raw_inputs=True)
+    assert case.ctx.path == "fused_n512"
+    bsk = case.keys.bsk.copy()
+    flat = bsk.reshape(-1)
+    flat[0::3] = np.uint64(1 << 63)
+    flat[1::3] = np.uint64((1 << 63) - 1)
+    luts = case.luts.copy()
+    luts[:, 0::2] = np.uint64((1 << 63) - (1 << (63 - beta)))
+    luts[:, 1::2] = np.uint64(1 << 63)
+    d_bsk = case.ctx.bsk_prepare(slz.to_device_u64(bsk))
+    want = orc.blind_rotate_batch(p, case.cts, luts, case.lut_idx, bsk, p.n)
+    got = slz.to_host_u64(case.ctx.blind_rotate_batch(case.d_cts, slz.to_device_u64(luts), case.d_idx, d_bsk, p.n))
+    assert np.array_equal(got, want)
+    # 1100 real encryptions: more than the resident workgroups of either variant; decryption of all, oracle on a sample
+    many = Case(slz, orc, p.with_(n=12, pbs_base_log=18), 1100)
+    big = many.ctx.pbs_batch(many.d_cts, many.d_luts, many.d_idx, many.d_bsk)
+    fused = slz.to_host_u64(big)
+    small = slz.to_host_u64(many.ctx.keyswitch_batch(big, many.d_ksk))
+    dec, _ = orc.decode(orc.lwe_phase(many.keys.lwe_sk, small), p.msg_bits)
+    assert np.array_equal(dec, many.tables[many.lut_idx.astype(np.int64), many.msgs.astype(np.int64)])
+    idx = np.array([0, 511, 512, 1023, 1024, 1099])
+    assert np.array_equal(fused[idx], orc.pbs_batch(many.p, many.cts[idx], many.luts, many.lut_idx[idx], many.keys.bsk))
+    many.ctx.set_option(slz.SLZ_OPT_FORCE_GENERIC, 1)
+    assert np.array_equal(slz.to_host_u64(many.ctx.pbs_batch(many.d_cts, many.d_luts, many.d_idx, many.d_bsk)), fused)
+
+
 # ---------------------------------------------------------------- fused kernel for N = 1024 (k = 1, l = 1)
 
 @pytest.mark.parametrize("beta", [23, 8, 16, 24])
