@@ -142,7 +142,7 @@ k_fused_blind_rotate_n1024(fused1024_args A) {
             for (int i = 0; i < 8; i++) { ks[1][i] = ldl(ksib + 32 * (8 + i), key_lane_off); ko[1][i] = ldl(kown + 32 * (8 + i), key_lane_off); }
             SCHED_FENCE();
             // 3. row h of the GGSW times the digits: component h stays, component h + 1 goes to the sibling after mine
-            //    (k = 2: the spectrum is kept for the second sibling's round)
+            //    (k = 2: the spectrum is kept for the second sibling's exchange)
             double xs[K == 2 ? 16 : 1];
             if (K == 2) {
 #pragma unroll
@@ -176,7 +176,7 @@ k_fused_blind_rotate_n1024(fused1024_args A) {
             }
             __syncthreads();                          // sibling has read my buffer before I reuse it
             if (K == 2) {
-                // second round: the product for component h + 2 through the same buffer; mine comes from the row after mine
+                // second exchange: the product for component h + 2 through the same buffer; mine comes from the row after mine
                 const double *k2 = krow + (size_t)((h + 2u) % C) * GN;
                 const double *Tsib2 = lds + (q * C + (h + 1u) % C) * TBUF16;
                 double kt[16];
