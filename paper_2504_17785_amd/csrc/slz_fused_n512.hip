@@ -1,4 +1,5 @@
-// Fused blind rotation for N = 512, l = 1, k = 1 or 3, any base (k = 3 is the shape of 2-bit parameter sets).
+// Fused blind rotation for N = 512, any base: l = 1 with k = 1 or 3 (k = 3 is the shape of 2-bit parameter sets), and
+// k = 1 with l = 2 (second kernel, further down).
 //
 // One wavefront transforms two 512-point polynomials at once (the 1024-point wave transform without the stage that would
 // pair them): in the coefficient domain registers 0..7 hold the first and 8..15 the second polynomial (coefficient
@@ -220,10 +221,171 @@ k_fused_blind_rotate_n512(fused512_args A) {
     }
 }
 
+// ---- k = 1, l = 2 (the shape of the smallest configuration) ------------------------------------------------------------
+// Four waves (q, h): the two polynomials of a wave are the two decomposition levels of component h (GGSW rows (h, 0) and
+// (h, 1)).  Each wave keeps 256 accumulator words (coefficients 64 (4 q + f) + lane of component h).  The products of both
+// levels with the two key columns are added across the half-waves as above; the waves of component 1 hand their sums to
+// the waves of component 0, which run the one inverse transform per prime (both columns at once) and leave the residues
+// in LDS for the CRT lift of all four waves.
+__global__ void __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(2, 2)))
+k_fused_blind_rotate_n512_l2(fused512_args A) {
+    const uint32_t beta = A.beta;
+    extern __shared__ double lds[];
+    const uint32_t lane = threadIdx.x & 63u;
+    const uint32_t w = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
+    const uint32_t q = w >> 1, h = w & 1u;
+    double *T = lds + w * TBUF16;
+    double *Toth = lds + (w ^ 2u) * TBUF16;           // other prime, same component
+    const double *Tsib = lds + (w ^ 1u) * TBUF16;     // same prime, other component
+    const double *Tres0 = lds, *Tres1 = lds + 2u * TBUF16;   // residues of prime 0 / prime 1: buffers of waves (0,0) and (1,0)
+    double *twA = lds + 4u * TBUF16 + q * 1024u, *twB = twA + 64;
+    if (h == 0) {
+        twA[lane] = A.rowA[q][lane];
+#pragma unroll
+        for (int k = 0; k < 15; k++) twB[64 * k + lane] = A.rowB[q][64 * k + lane];
+    }
+    __syncthreads();
+    uint64_t *Smine = reinterpret_cast<uint64_t *>(T + P_STAGE_OFF);
+    const slz_mod m = A.mod[q];
+    const double *invt = A.inv[q], *post = A.post[q];
+    const double *twS = A.tw_inv[q];
+    const uint32_t hv = lane >> 5;                    // transform domain: decomposition level held by this lane
+    const uint32_t key_lane_off = (hv * 2u * PN + 16u * (lane & 1u) * 16u + ((lane & 31u) >> 1)) * 8u;
+
+    for (uint32_t c = blockIdx.x; c < A.batch; c += gridDim.x) {
+        const uint64_t *lwe = A.lwe_in + (size_t)c * (A.n + 1);
+        uint64_t acc[4];
+        if (h == 1) {
+            const uint32_t bt = slz_modswitch(lwe[A.n], PLOGN + 1);
+            const uint32_t r = (2 * PN - bt) & (2 * PN - 1);
+            const uint64_t *lut = A.luts + (size_t)(A.lut_idx ? A.lut_idx[c] : 0) * PN;
+#pragma unroll
+            for (int f = 0; f < 4; f++)
+                acc[f] = slz_rot_coeff([&](uint32_t j) { return lut[j]; }, 64u * (4u * q + f) + lane, r, PN);
+        } else {
+#pragma unroll
+            for (int f = 0; f < 4; f++) acc[f] = 0;
+        }
+
+        for (uint32_t step = 0; step < A.n_steps; step++) {
+            int z;
+            asm volatile("s_mov_b32 %0, 0" : "=s"(z));
+            const uint32_t at = slz_modswitch(lwe[step], PLOGN + 1);
+            // [n][prime][row = 2 comp + level][comp][N]: row (h, 0); the lane offset moves the upper half-wave to row (h, 1)
+            const double *krow = A.bskp + (((size_t)step * 2 + q) * 4 + 2u * h) * 2 * PN + z;
+#pragma unroll
+            for (int f = 0; f < 4; f++) Smine[64 * f + lane] = acc[f];
+            __syncthreads();
+            int32_t dg[8];                            // dg[4 level + f]
+            {
+                uint32_t r = at, neg0 = 0;
+                if (r >= PN) { r -= PN; neg0 = 1; }
+                int32_t *pd = reinterpret_cast<int32_t *>(Toth);
+#pragma unroll
+                for (int f = 0; f < 4; f++) {
+                    const uint32_t idx = 64u * (4u * q + f) + lane;
+                    const uint32_t j = (idx - r) & (PN - 1);
+                    const uint32_t neg = neg0 ^ (idx < r ? 1u : 0u);
+                    const uint64_t *src = reinterpret_cast<const uint64_t *>(lds + ((j >> 8) * 2u + h) * TBUF16 + P_STAGE_OFF);
+                    const uint64_t a = src[64u * ((j >> 6) & 3u) + (j & 63u)];
+                    const uint64_t lam = (neg ? (uint64_t)0 - a : a) - acc[f];
+                    uint64_t v = slz_round_top_bits(lam, 2 * beta);
+                    dg[4 + f] = slz_next_digit(v, beta);         // least significant level first: the carry goes up
+                    dg[f] = slz_next_digit(v, beta);
+                    pd[64 * f + lane] = dg[f];
+                    pd[64 * (4 + f) + lane] = dg[4 + f];
+                }
+            }
+            __syncthreads();
+            double x[16];
+            {
+                const int32_t *md = reinterpret_cast<const int32_t *>(T);
+#pragma unroll
+                for (int u = 0; u < 8; u++) {
+                    const int lev = u >> 2, f = u & 3;
+                    if (q == 0) { x[8 * lev + f] = (double)dg[u]; x[8 * lev + 4 + f] = (double)md[64 * u + lane]; }
+                    else { x[8 * lev + 4 + f] = (double)dg[u]; x[8 * lev + f] = (double)md[64 * u + lane]; }
+                }
+            }
+            fwd16<true>(x, T, twA, twB, m, lane, z);
+            wave_sync();
+#pragma unroll
+            for (int g = 0; g < 4; g++) {
+                double k0[4], k1[4], ra[4], rb[4];
+#pragma unroll
+                for (int u = 0; u < 4; u++) {
+                    k0[u] = ldl(krow + 16 * (4 * g + u), key_lane_off);
+                    k1[u] = ldl(krow + PN + 16 * (4 * g + u), key_lane_off);
+                }
+                const double x4[4] = {x[4 * g], x[4 * g + 1], x[4 * g + 2], x[4 * g + 3]};
+                mulmod_k<4>(ra, x4, k0, m);
+                mulmod_k<4>(rb, x4, k1, m);
+#pragma unroll
+                for (int u = 0; u < 4; u++) {
+                    swap32(ra[u], rb[u]);
+                    x[4 * g + u] = ra[u] + rb[u];     // lanes 0..31: column 0 summed over the levels, lanes 32..63: column 1
+                    if (h == 1) T[64 * (4 * g + u) + lane] = x[4 * g + u];
+                }
+            }
+            __syncthreads();
+            if (h == 0) {
+#pragma unroll
+                for (int g = 0; g < 2; g++) {
+                    double r8[8], x8[8];
+#pragma unroll
+                    for (int u = 0; u < 8; u++) x8[u] = x[8 * g + u] + Tsib[64 * (8 * g + u) + lane];
+                    reduce_k<8>(r8, x8, m);
+#pragma unroll
+                    for (int u = 0; u < 8; u++) x[8 * g + u] = r8[u];
+                }
+                double pw[8];
+#pragma unroll
+                for (int e = 0; e < 8; e++) pw[e] = ldl(post + 64 * e + z, lane * 8u);
+                SCHED_FENCE();
+                inv16<true>(x, T, twS, invt, m, lane, z);
+                wave_sync();
+#pragma unroll
+                for (int g = 0; g < 4; g++) {
+                    double r4[4];
+                    const double x4[4] = {x[4 * g], x[4 * g + 1], x[4 * g + 2], x[4 * g + 3]};
+                    const double w4[4] = {pw[(4 * g) & 7], pw[(4 * g + 1) & 7], pw[(4 * g + 2) & 7], pw[(4 * g + 3) & 7]};
+                    mulmod_k<4>(r4, x4, w4, m);
+#pragma unroll
+                    for (int u = 0; u < 4; u++) T[64 * (4 * g + u) + lane] = r4[u];   // register 8 comp + e: coefficient 64 e + lane
+                }
+            }
+            __syncthreads();
+#pragma unroll
+            for (int f = 0; f < 4; f++) {
+                const uint32_t slot = 64u * (8u * h + 4u * q + f) + lane;
+                acc[f] += slz_crt64(Tres0[slot], Tres1[slot], A.mod[1], A.p1inv_mod_p2);
+            }
+            __syncthreads();                          // residues are read before the next step stages into the same buffers
+        }
+
+#pragma unroll
+        for (int f = 0; f < 4; f++) {
+            const uint32_t idx = 64u * (4u * q + f) + lane;
+            if (A.acc_out) A.acc_out[((size_t)c * 2 + h) * PN + idx] = acc[f];
+            if (A.lwe_out) {
+                uint64_t *dst = A.lwe_out + (size_t)c * (PN + 1);
+                if (h == 0) {
+                    if (idx == 0) dst[0] = acc[f];
+                    else dst[PN - idx] = (uint64_t)0 - acc[f];
+                } else if (idx == 0) {
+                    dst[PN] = acc[f];
+                }
+            }
+        }
+        __syncthreads();
+    }
+}
+
 // ---- host side -----------------------------------------------------------------------------------
 
 int slz_fused512_supported(const slz_params *p) {
-    return p->N == PN && (p->k == 1 || p->k == 3) && p->pbs_level == 1 && p->pbs_base_log <= 30;
+    if (p->N != PN || p->pbs_base_log > 30) return 0;
+    return ((p->k == 1 || p->k == 3) && p->pbs_level == 1) || (p->k == 1 && p->pbs_level == 2);
 }
 
 // Forward tables of the paired transform: the stage of the 1024-point schedule that works on m' sub-blocks of the whole
@@ -277,6 +439,8 @@ int slz_fused512_init(slz_ctx *ctx) {
                                 P_LDS_DOUBLES(1) * sizeof(double)));
     SLZ_HIP(hipFuncSetAttribute((const void *)k_fused_blind_rotate_n512<3>, hipFuncAttributeMaxDynamicSharedMemorySize,
                                 P_LDS_DOUBLES(2) * sizeof(double)));
+    SLZ_HIP(hipFuncSetAttribute((const void *)k_fused_blind_rotate_n512_l2, hipFuncAttributeMaxDynamicSharedMemorySize,
+                                P_LDS_DOUBLES(2) * sizeof(double)));
     return SLZ_OK;
 }
 
@@ -301,7 +465,11 @@ int slz_fused512_blind_rotate(slz_ctx *ctx, const uint64_t *lwe_in, const uint64
         for (int x = 0; x < 16; x++) A.tw_inv[q][x] = ctx->fused_scalars[q][1][x];
     }
     A.p1inv_mod_p2 = ctx->p1inv_mod_p2;
-    if (ctx->prm.k == 3) {
+    if (ctx->prm.pbs_level == 2) {
+        const uint32_t resident = 2u * 256u;
+        const uint32_t grid = batch < resident ? batch : resident;
+        hipLaunchKernelGGL(k_fused_blind_rotate_n512_l2, dim3(grid), dim3(256), P_LDS_DOUBLES(2) * sizeof(double), s, A);
+    } else if (ctx->prm.k == 3) {
         const uint32_t resident = 2u * 256u;           // four waves per workgroup, two waves per SIMD
         const uint32_t grid = batch < resident ? batch : resident;
         hipLaunchKernelGGL(k_fused_blind_rotate_n512<3>, dim3(grid), dim3(256), P_LDS_DOUBLES(2) * sizeof(double), s, A);

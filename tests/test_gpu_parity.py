@@ -375,6 +375,44 @@ def test_fused_n512_worst_case_and_many_ciphertexts(slz, orc, k, beta):
     assert np.array_equal(slz.to_host_u64(many.ctx.pbs_batch(many.d_cts, many.d_luts, many.d_idx, many.d_bsk)), fused)
 
 
+@pytest.mark.parametrize("beta", [8, 12, 3])
+def test_fused_n512_two_levels_states_and_outputs_match_oracle(slz, orc, beta):
+    p = tiny(n=5, N=512, k=1, pbs_base_log=beta, pbs_level=2)
+    case = Case(slz, orc, p, 7, raw_inputs=True)
+    assert case.ctx.path == "fused_n512"
+    for steps in sorted({0, 1, 2, p.n}):
+        want = orc.blind_rotate_batch(p, case.cts, case.luts, case.lut_idx, case.keys.bsk, steps)
+        got = slz.to_host_u64(case.ctx.blind_rotate_batch(case.d_cts, case.d_luts, case.d_idx, case.d_bsk, steps))
+        assert np.array_equal(got, want), "accumulators differ after %d steps" % steps
+    want = orc.pbs_batch(p, case.cts, case.luts, case.lut_idx, case.keys.bsk)
+    assert np.array_equal(slz.to_host_u64(case.ctx.pbs_batch(case.d_cts, case.d_luts, case.d_idx, case.d_bsk)), want)
+    case.ctx.set_option(slz.SLZ_OPT_FORCE_GENERIC, 1)
+    assert np.array_equal(slz.to_host_u64(case.ctx.pbs_batch(case.d_cts, case.d_luts, case.d_idx, case.d_bsk)), want)
+
+
+def test_fused_n512_two_levels_worst_case_and_many_ciphertexts(slz, orc):
+    p = tiny(n=3, N=512, k=1, pbs_base_log=24, pbs_level=2)       # 4 * 512 * 2^23 * 2^63 = 2^97: the largest sums allowed
+    case = Case(slz, orc, p, 3, raw_inputs=True)
+    assert case.ctx.path == "fused_n512"
+    bsk = case.keys.bsk.copy()
+    flat = bsk.reshape(-1)
+    flat[0::3] = np.uint64(1 << 63)
+    flat[1::3] = np.uint64((1 << 63) - 1)
+    luts = case.luts.copy()
+    luts[:, 0::2] = np.uint64((1 << 63) - (1 << 15) - (1 << 39))  # both digits at -2^23 or 2^23 - 1
+    luts[:, 1::2] = np.uint64(1 << 63)
+    d_bsk = case.ctx.bsk_prepare(slz.to_device_u64(bsk))
+    want = orc.blind_rotate_batch(p, case.cts, luts, case.lut_idx, bsk, p.n)
+    got = slz.to_host_u64(case.ctx.blind_rotate_batch(case.d_cts, slz.to_device_u64(luts), case.d_idx, d_bsk, p.n))
+    assert np.array_equal(got, want)
+    many = Case(slz, orc, tiny(n=4, N=512, k=1, pbs_base_log=8, pbs_level=2), 600, raw_inputs=True)
+    fused = slz.to_host_u64(many.ctx.pbs_batch(many.d_cts, many.d_luts, many.d_idx, many.d_bsk))
+    idx = np.array([0, 511, 512, 599])
+    assert np.array_equal(fused[idx], orc.pbs_batch(many.p, many.cts[idx], many.luts, many.lut_idx[idx], many.keys.bsk))
+    many.ctx.set_option(slz.SLZ_OPT_FORCE_GENERIC, 1)
+    assert np.array_equal(slz.to_host_u64(many.ctx.pbs_batch(many.d_cts, many.d_luts, many.d_idx, many.d_bsk)), fused)
+
+
 # ---------------------------------------------------------------- fused kernel for N = 1024 (k = 1, l = 1)
 
 @pytest.mark.parametrize("beta", [23, 8, 16, 24])
