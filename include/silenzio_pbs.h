@@ -49,7 +49,7 @@ extern "C" {
 #define SLZ_E_UNSUPPORTED (-2)   /* valid parameters for which this build has no exact kernel           */
 #define SLZ_E_HIP         (-3)   /* a HIP runtime call failed                                            */
 #define SLZ_E_NOMEM       (-4)   /* scratch allocation failed                                            */
-#define SLZ_E_TOO_LARGE   (-5)   /* batch exceeds the max_batch the context was created for              */
+#define SLZ_E_TOO_LARGE   (-5)   /* batch exceeds the context's max_batch (or the fixed scratch of a _static call) */
 
 /* A TFHE parameter set.  Plain data, copied by the callee.  One padding bit is implied:
  * messages live in Z_t, t = 2^msg_bits, encoded at Delta = 2^(63 - msg_bits). */
@@ -132,6 +132,20 @@ int slz_blind_rotate_batch(slz_ctx *ctx, const uint64_t *lwe_in_dev, const uint6
  * that fails) and larger batches are taken in chunks of max_batch. */
 int slz_keyswitch_batch(slz_ctx *ctx, const uint64_t *lwe_in_dev, const uint64_t *ksk_dev,
                         uint64_t *lwe_out_dev, uint32_t batch, void *hip_stream);
+
+/* For callers that cannot allocate device memory (code under HIP graph capture, tight serving loops, harnesses that
+ * forbid hipMalloc): slz_keyswitch_batch on the int8 matrix cores with its digit scratch in a fixed device array of
+ * SLZ_KS_STATIC_SCRATCH_BYTES inside the library instead of a buffer of the context.  The call itself allocates and
+ * frees nothing, on the device or through any library.  Same arguments, layouts and result (bit for bit) as
+ * slz_keyswitch_batch.  Limits: keyswitch base at most 2^8 and kN a multiple of 32 (SLZ_E_UNSUPPORTED otherwise);
+ * 1024 * ceil(batch / 32) * (kN * l_ks / 32) bytes must fit the array (SLZ_E_TOO_LARGE otherwise: 1632 ciphertexts at
+ * kN = 2048, l_ks = 5; 96 at kN = 32768, l_ks = 5); the context's device must be current (SLZ_E_INVALID_ARG otherwise).
+ * All calls on one device share the one array, whatever their context or stream: calls that overlap on a device race,
+ * so order them on one stream or with events.  The array keeps the last call's digits; every slot a call reads it has
+ * written first. */
+#define SLZ_KS_STATIC_SCRATCH_BYTES (16u << 20)
+int slz_keyswitch_batch_static(slz_ctx *ctx, const uint64_t *lwe_in_dev, const uint64_t *ksk_dev,
+                               uint64_t *lwe_out_dev, uint32_t batch, void *hip_stream);
 
 /* Keyswitch-first order (the order in which a compiler for the scheme usually chains the two): ciphertexts stay under the
  * big key between lookups, and one lookup is   lwe_out = PBS(keyswitch(lwe_in)).

@@ -35,7 +35,7 @@ class SlzError(RuntimeError):
 _lib = None
 
 EXPORTS = ("slz_ctx_create", "slz_ctx_destroy", "slz_ctx_set_option", "slz_lut_encode", "slz_bsk_prepare",
-           "slz_pbs_batch", "slz_blind_rotate_batch", "slz_keyswitch_batch", "slz_ks_pbs_batch", "slz_lwe_lincomb_batch",
+           "slz_pbs_batch", "slz_blind_rotate_batch", "slz_keyswitch_batch", "slz_keyswitch_batch_static", "slz_ks_pbs_batch", "slz_lwe_lincomb_batch",
            "slz_pbs_path", "slz_strerror", "slz_matmul_rns_luts", "slz_matmul_rns_workspace", "slz_matmul_rns",
            "slz_rns_luts", "slz_rns_workspace", "slz_rns2mrns", "slz_sign_rns",
            "slz_shift2msbs_luts", "slz_shift2msbs_workspace", "slz_shift2msbs_plus", "slz_shift2msbs_pm",
@@ -65,6 +65,7 @@ def lib():
         L.slz_pbs_batch.argtypes = [vp, vp, vp, vp, u32, vp, vp, u32, vp]
         L.slz_blind_rotate_batch.argtypes = [vp, vp, vp, vp, u32, vp, u32, vp, u32, vp]
         L.slz_keyswitch_batch.argtypes = [vp, vp, vp, vp, u32, vp]
+        L.slz_keyswitch_batch_static.argtypes = [vp, vp, vp, vp, u32, vp]
         L.slz_ks_pbs_batch.argtypes = [vp, vp, vp, vp, vp, u32, vp, vp, u32, vp]
         L.slz_lwe_lincomb_batch.argtypes = [vp, vp, vp, vp, u32, u32, u32, vp]
         L.slz_pbs_path.argtypes = [vp]
@@ -319,6 +320,13 @@ class Context:
             out = torch.empty((batch, self.p.n + 1), dtype=torch.int64, device=lwe_in.device)
         _check(lib().slz_keyswitch_batch(self._h, _dev_u64(lwe_in, "lwe_in"), _dev_u64(ksk, "ksk"), _dev_u64(out, "out"),
                                          batch, _stream()), "slz_keyswitch_batch")
+        return out
+
+    def keyswitch_batch_static(self, lwe_in, ksk, out):
+        """slz_keyswitch_batch_static: the keyswitch with its scratch in a fixed device array of the library; `out`
+        ([batch][n+1]) comes from the caller, so that nothing is allocated on the way."""
+        _check(lib().slz_keyswitch_batch_static(self._h, _dev_u64(lwe_in, "lwe_in"), _dev_u64(ksk, "ksk"), _dev_u64(out, "out"),
+                                                lwe_in.shape[0], _stream()), "slz_keyswitch_batch_static")
         return out
 
     def ks_pbs_batch(self, lwe_in, ksk, luts, lut_idx, bsk_prepared, out=None):

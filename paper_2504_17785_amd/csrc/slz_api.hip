@@ -253,7 +253,7 @@ extern "C" const char *slz_strerror(int code) {
         case SLZ_E_UNSUPPORTED: return "parameter set not supported by this build";
         case SLZ_E_HIP: return "HIP runtime error";
         case SLZ_E_NOMEM: return "out of device memory";
-        case SLZ_E_TOO_LARGE: return "batch larger than the context's max_batch";
+        case SLZ_E_TOO_LARGE: return "batch larger than the context's max_batch or than the fixed scratch of a _static entry point";
         default: return "unknown error code";
     }
 }

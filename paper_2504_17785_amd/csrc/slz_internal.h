@@ -133,6 +133,8 @@ int slz_bign_cmux_steps(slz_ctx *ctx, const uint64_t *lwe_in, const double *bskp
 // keyswitch / lincomb (slz_keyswitch.hip)
 int slz_keyswitch_launch(slz_ctx *ctx, const uint64_t *lwe_in, const uint64_t *ksk, uint64_t *lwe_out,
                          uint32_t batch, hipStream_t s);
+// out = (0, .., 0, b') for every ciphertext: the start value of both keyswitch kernels
+void slz_ks_init_launch(const uint64_t *lwe_in, uint64_t *lwe_out, uint32_t kN, uint32_t n, uint32_t batch, hipStream_t s);
 // matrix-core keyswitch (slz_keyswitch_mfma.hip); lwe_out must already hold (0, .., 0, b')
 int slz_ksm_supported(const slz_params *p);
 void slz_ksm_destroy(slz_ctx *ctx);

@@ -90,15 +90,19 @@ k_keyswitch(const uint64_t *__restrict__ lwe_in, const uint64_t *__restrict__ ks
     }
 }
 
+void slz_ks_init_launch(const uint64_t *lwe_in, uint64_t *lwe_out, uint32_t kN, uint32_t n, uint32_t batch, hipStream_t s) {
+    const size_t total = (size_t)batch * (n + 1);
+    hipLaunchKernelGGL(k_ks_init, dim3((unsigned)((total + KS_THREADS - 1) / KS_THREADS)), dim3(KS_THREADS), 0, s, lwe_in, lwe_out,
+                       kN, n, batch);
+}
+
 int slz_keyswitch_launch(slz_ctx *ctx, const uint64_t *lwe_in, const uint64_t *ksk, uint64_t *lwe_out, uint32_t batch,
                          hipStream_t s) {
     const slz_params &p = ctx->prm;
     const uint32_t kN = p.k * p.N, n = p.n;
     if (p.ks_level > KS_MAX_L || p.ks_base_log > 31) return SLZ_E_UNSUPPORTED;
     static_assert(KS_THREADS == KS_TB * KS_IC, "one mask word per thread in the decomposition step");
-    size_t total = (size_t)batch * (n + 1);
-    hipLaunchKernelGGL(k_ks_init, dim3((unsigned)((total + KS_THREADS - 1) / KS_THREADS)), dim3(KS_THREADS), 0, s, lwe_in, lwe_out,
-                       kN, n, batch);
+    slz_ks_init_launch(lwe_in, lwe_out, kN, n, batch, s);
     // digits of at most a byte: int8 MFMA contraction.  Measured faster than the scalar kernel below at every batch size,
     // one ciphertext included, except for a handful of ciphertexts against a key of HBM-streaming size (1.3 GB at
     // n = 1024, N = 32768: 0.33 ms against 0.27 ms), where the scalar kernel's plain row streaming wins.

@@ -198,24 +198,15 @@ void slz_ksm_destroy(slz_ctx *ctx) {
     ctx->ks_dig = nullptr;
 }
 
-// `lwe_out` must already hold (0, .., 0, b').
-int slz_ksm_launch(slz_ctx *ctx, const uint64_t *lwe_in, const uint64_t *ksk, uint64_t *lwe_out, uint32_t batch, hipStream_t s) {
-    const slz_params &p = ctx->prm;
+// The launches of one keyswitch given its digit scratch (`dig`: room for max_tiles 32-ciphertext tiles).  `lwe_out` must
+// already hold (0, .., 0, b').
+static int ksm_run(const slz_params &p, void *dig, uint32_t max_tiles, const uint64_t *lwe_in, const uint64_t *ksk,
+                   uint64_t *lwe_out, uint32_t batch, hipStream_t s) {
     const uint32_t kN = p.k * p.N;
-    const uint64_t n_kb64 = (uint64_t)p.ks_level * kN / 32;
-    if (n_kb64 > (1u << 26)) return SLZ_E_UNSUPPORTED;
-    const uint32_t n_kb = (uint32_t)n_kb64;
-    const uint32_t max_tiles = min((ctx->max_batch + 31) / 32, 32768u);
-    if (!ctx->ks_dig) {     // digit scratch, sized for max_batch (larger batches go through in chunks)
-        if (hipMalloc((void **)&ctx->ks_dig, (size_t)max_tiles * n_kb * 1024) != hipSuccess) {
-            (void)hipGetLastError();
-            ctx->ks_dig = nullptr;
-            return SLZ_E_NOMEM;
-        }
-    }
+    const uint32_t n_kb = (uint32_t)((uint64_t)p.ks_level * kN / 32);
     ksm_args A;
     A.ksk = ksk;
-    A.dig = (const v4i *)ctx->ks_dig;
+    A.dig = (const v4i *)dig;
     A.kN = kN; A.n = p.n; A.l = p.ks_level;
     A.n_kb = n_kb;
     A.x_tiles = (p.n + 1 + 31) / 32;
@@ -240,9 +231,59 @@ int slz_ksm_launch(slz_ctx *ctx, const uint64_t *lwe_in, const uint64_t *ksk, ui
         A.total = (uint32_t)total;
         A.per_xcd = (A.total + 7) / 8;
         hipLaunchKernelGGL(k_ksm_digits, dim3((kN / 16 + 7) / 8, A.n_tiles), dim3(256), 0, s,
-                           lwe_in + (size_t)c0 * (kN + 1), (v4i *)ctx->ks_dig, kN, p.ks_base_log, p.ks_level, nb, n_kb);
+                           lwe_in + (size_t)c0 * (kN + 1), (v4i *)dig, kN, p.ks_base_log, p.ks_level, nb, n_kb);
         hipLaunchKernelGGL(k_ksm_main, dim3(A.per_xcd * 8), dim3(KM_THREADS), 0, s, A);
     }
     SLZ_HIP(hipGetLastError());
     return SLZ_OK;
+}
+
+// `lwe_out` must already hold (0, .., 0, b').
+int slz_ksm_launch(slz_ctx *ctx, const uint64_t *lwe_in, const uint64_t *ksk, uint64_t *lwe_out, uint32_t batch, hipStream_t s) {
+    const slz_params &p = ctx->prm;
+    const uint64_t n_kb64 = (uint64_t)p.ks_level * p.k * p.N / 32;
+    if (n_kb64 > (1u << 26)) return SLZ_E_UNSUPPORTED;
+    const uint32_t max_tiles = min((ctx->max_batch + 31) / 32, 32768u);
+    if (!ctx->ks_dig) {     // digit scratch, sized for max_batch (larger batches go through in chunks)
+        if (hipMalloc((void **)&ctx->ks_dig, (size_t)max_tiles * n_kb64 * 1024) != hipSuccess) {
+            (void)hipGetLastError();
+            ctx->ks_dig = nullptr;
+            return SLZ_E_NOMEM;
+        }
+    }
+    return ksm_run(p, ctx->ks_dig, max_tiles, lwe_in, ksk, lwe_out, batch, s);
+}
+
+// ---- the variant that allocates nothing ------------------------------------------------------------------------------
+// Digit scratch for callers that cannot allocate: a file-scope device array (every device the library runs on holds its
+// own copy until the process ends).  Host code never passes the array's name to a kernel: the device address is looked
+// up once per device and kept in scratch_ptr.
+#define SLZ_KS_STATIC_MAX_DEVICES 64
+static __device__ __align__(256) unsigned char scratch[SLZ_KS_STATIC_SCRATCH_BYTES];
+static void *scratch_ptr[SLZ_KS_STATIC_MAX_DEVICES];
+
+extern "C" int slz_keyswitch_batch_static(slz_ctx *ctx, const uint64_t *lwe_in_dev, const uint64_t *ksk_dev, uint64_t *lwe_out_dev,
+                                          uint32_t batch, void *hip_stream) {
+    if (!ctx || !lwe_in_dev || !ksk_dev || !lwe_out_dev || batch == 0) return SLZ_E_INVALID_ARG;
+    if (((uintptr_t)lwe_in_dev & 7u) || ((uintptr_t)ksk_dev & 15u) || ((uintptr_t)lwe_out_dev & 7u)) return SLZ_E_INVALID_ARG;
+    const slz_params &p = ctx->prm;
+    if (!slz_ksm_supported(&p)) return SLZ_E_UNSUPPORTED;
+    const uint64_t n_kb64 = (uint64_t)p.ks_level * p.k * p.N / 32;
+    if (n_kb64 > (1u << 26)) return SLZ_E_UNSUPPORTED;
+    const uint64_t tiles = ((uint64_t)batch + 31) / 32;
+    if (tiles * n_kb64 * 1024 > (uint64_t)SLZ_KS_STATIC_SCRATCH_BYTES) return SLZ_E_TOO_LARGE;
+    int dev = -1;
+    SLZ_HIP(hipGetDevice(&dev));
+    if (dev != ctx->device || dev < 0 || dev >= SLZ_KS_STATIC_MAX_DEVICES) return SLZ_E_INVALID_ARG;
+    if (!scratch_ptr[dev]) {
+        void *ptr = nullptr;
+        SLZ_HIP(hipGetSymbolAddress(&ptr, HIP_SYMBOL(scratch)));
+        if (!ptr) return SLZ_E_HIP;
+        scratch_ptr[dev] = ptr;
+    }
+    hipStream_t s = (hipStream_t)hip_stream;
+    slz_ks_init_launch(lwe_in_dev, lwe_out_dev, p.k * p.N, p.n, batch, s);
+    // every digit slot of the tiles in use is rewritten by k_ksm_digits (ciphertexts past the batch get zeros), so the
+    // contents the previous call left behind are never read
+    return ksm_run(p, scratch_ptr[dev], (uint32_t)tiles, lwe_in_dev, ksk_dev, lwe_out_dev, batch, s);
 }
