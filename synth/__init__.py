@@ -46,12 +46,35 @@ def stream_key(seed: int, stream: str | int) -> np.uint64:
     return np.uint64(_mix64(a ^ b))
 
 
-def words(seed: int, stream: str | int, count: int, offset: int = 0) -> np.ndarray:
-    """`count` uniform u64 words of the stream, starting at index `offset`."""
-    key = stream_key(seed, stream)
+_CHUNK = 1 << 22      # large requests are generated in pieces of this many values on a few threads (counter mode:
+_THREADS = 8          # the result does not depend on how the range is cut)
+
+
+def _in_chunks(fn, count: int, dtype) -> np.ndarray:
+    if count <= 2 * _CHUNK:
+        return fn(0, count)
+    import concurrent.futures
+    out = np.empty(count, dtype=dtype)
+
+    def piece(start):
+        stop = min(count, start + _CHUNK)
+        out[start:stop] = fn(start, stop - start)
+
+    with concurrent.futures.ThreadPoolExecutor(_THREADS) as ex:
+        list(ex.map(piece, range(0, count, _CHUNK)))
+    return out
+
+
+def _words(key: np.uint64, count: int, offset: int) -> np.ndarray:
     idx = np.arange(offset + 1, offset + count + 1, dtype=np.uint64)
     with np.errstate(over="ignore"):
         return _mix64(key + idx * _GOLDEN)
+
+
+def words(seed: int, stream: str | int, count: int, offset: int = 0) -> np.ndarray:
+    """`count` uniform u64 words of the stream, starting at index `offset`."""
+    key = stream_key(seed, stream)
+    return _in_chunks(lambda start, cnt: _words(key, cnt, offset + start), count, np.uint64)
 
 
 def bits(seed: int, stream: str | int, count: int, offset: int = 0) -> np.ndarray:
@@ -70,11 +93,16 @@ def gaussian_ints(seed: int, stream: str | int, count: int, sigma: float, offset
     """Rounded Gaussian noise on the 2^64 torus: round(z * sigma * 2^64) as int64 (two's complement)."""
     if sigma == 0.0:
         return np.zeros(count, dtype=np.int64)
-    w = words(seed, stream, 2 * count, 2 * offset)
-    u1 = ((w[0::2] >> np.uint64(11)).astype(np.float64) + 1.0) * (1.0 / 9007199254740992.0)  # (0,1]
-    u2 = (w[1::2] >> np.uint64(11)).astype(np.float64) * (1.0 / 9007199254740992.0)          # [0,1)
-    z = np.sqrt(-2.0 * np.log(u1)) * np.cos(2.0 * np.pi * u2)
-    return np.rint(z * (sigma * 18446744073709551616.0)).astype(np.int64)
+    key = stream_key(seed, stream)
+
+    def piece(start, cnt):
+        w = _words(key, 2 * cnt, 2 * (offset + start))
+        u1 = ((w[0::2] >> np.uint64(11)).astype(np.float64) + 1.0) * (1.0 / 9007199254740992.0)  # (0,1]
+        u2 = (w[1::2] >> np.uint64(11)).astype(np.float64) * (1.0 / 9007199254740992.0)          # [0,1)
+        z = np.sqrt(-2.0 * np.log(u1)) * np.cos(2.0 * np.pi * u2)
+        return np.rint(z * (sigma * 18446744073709551616.0)).astype(np.int64)
+
+    return _in_chunks(piece, count, np.int64)
 
 
 @dataclasses.dataclass(frozen=True)
@@ -145,6 +173,21 @@ def bsk_randomness(p: Params):
     mask = words(p.seed, "bsk_mask", rows * p.k * p.N).reshape(p.n, p.k + 1, p.pbs_level, p.k, p.N)
     noise = gaussian_ints(p.seed, "bsk_noise", rows * p.N, p.sigma_bsk).reshape(p.n, p.k + 1, p.pbs_level, p.N)
     return mask, noise
+
+
+def bsk_randomness_sparse(p: Params, nnz: int):
+    """As bsk_randomness, but every mask polynomial has only `nnz` non-zero words (uniform words at seeded positions;
+    positions may coincide).  A test device: a key built from it is a valid encryption of the same key bits with real
+    noise, useless for security, and a schoolbook key generation costs nnz N instead of N^2 per row."""
+    rows = p.n * (p.k + 1) * p.pbs_level
+    polys = rows * p.k
+    mask = np.zeros((polys, p.N), dtype=np.uint64)
+    pos = uniform_below(p.seed, "misc", polys * nnz, p.N, offset=1 << 20).reshape(polys, nnz).astype(np.int64)
+    val = words(p.seed, "bsk_mask", polys * nnz).reshape(polys, nnz)
+    for q in range(nnz):
+        mask[np.arange(polys), pos[:, q]] = val[:, q]
+    noise = gaussian_ints(p.seed, "bsk_noise", rows * p.N, p.sigma_bsk).reshape(p.n, p.k + 1, p.pbs_level, p.N)
+    return mask.reshape(p.n, p.k + 1, p.pbs_level, p.k, p.N), noise
 
 
 def ksk_randomness(p: Params):
