@@ -79,6 +79,10 @@ typedef struct slz_ctx slz_ctx;   /* opaque: parameter copy, twiddle tables, scr
                                      overlaps the memory-bound column passes of the other; results are identical);
                                      SLZ_E_INVALID_ARG when the context has no large-N path */
 
+#define SLZ_OPT_FAIL_ALLOC_AFTER 4 /* for tests of the out-of-memory handling: value v >= 0 makes the (v+1)-th scratch allocation
+                                     from now (of any context of the process) return SLZ_E_NOMEM without touching the device,
+                                     once; v < 0 disarms */
+
 /* Allocation and graph capture: slz_pbs_batch, slz_blind_rotate_batch, slz_keyswitch_batch and slz_ks_pbs_batch allocate
  * their scratch (and the large-N path its two internal streams) in the first call on a context; later calls with a batch
  * no larger than max_batch record only kernels and event edges on the given stream and may be captured into a HIP graph

@@ -3,7 +3,7 @@ of RNS2MRNS, Sign^RNS, Shift2MSBs^+/+- and MatmulHighRes^RNS (each section has i
 
 TEST INFRASTRUCTURE ONLY: imported by tests/ and by bench.py's cpu_baseline leg; the GPU library never imports it.
 
-Two layers, both written from the algorithm's three steps in the paper's order and notation:
+Two layers:
 
 * `matmul_rns_clear`: the clear-integer clone (the paper validates its encrypted runs against such a clone,
   Sec. "Evaluation").  Plain numpy integers.
@@ -69,28 +69,29 @@ def crt_reconstruct(Y, m) -> np.ndarray:
 
 
 def matmul_rns_clear(X, W, m) -> np.ndarray:
-    """Algorithm "Matmul^RNS" on clear integers.  X: a x b, W: b x c (signed), m: k moduli.  Returns Y: k x a x c residues."""
+    """Algorithm "Matmul^RNS" on clear integers.  X: a x b, W: b x c (signed), m: k moduli.  Returns Y: k x a x c residues.
+
+    What the algorithm computes, written from its definition: per modulus q the residues of both inputs, all a b c
+    products of residues reduced modulo q, the products of one output entry cut into consecutive blocks of at most 15,
+    each block summed as plain integers, and the block sums folded left to right with one reduction modulo q per block.
+    The quantity the block size exists for, (previous residue) + (block sum) < 256, is asserted."""
     X = np.asarray(X, dtype=np.int64)
     W = np.asarray(W, dtype=np.int64)
-    m = np.asarray(m, dtype=np.int64)
-    b = X.shape[1]
-    # Step 1: inputs to RNS representation
-    mp = m[:, None, None]
-    Xr = np.mod(X[None, :, :], mp)                                   # k x a x b
-    Wr = np.mod(W[None, :, :], mp)                                   # k x b x c
-    # Step 2: partial products
-    Ys = np.mod(Xr[:, :, :, None] * Wr[:, None, :, :], m[:, None, None, None])   # k x a x b x c
-    # Step 3: block-wise summation
-    n = min(BLOCK, b)
-    Y = np.mod(Ys[:, :, :n, :].sum(axis=2), mp)
-    i = n
-    while i < b:
-        j = min(i + n, b)
-        Yp = Ys[:, :, i:j, :].sum(axis=2)
-        assert int((Y + Yp).max()) < 256                             # the 8-bit bound the block size is chosen for
-        Y = np.mod(Y + Yp, mp)
-        i += n
-    return Y
+    a, b = X.shape
+    c = W.shape[1]
+    n_blocks = -(-b // BLOCK)
+    out = []
+    for q in (int(v) for v in m):
+        products = (np.mod(X, q)[:, :, None] * np.mod(W, q)[None, :, :]) % q                    # a x b x c, each below q
+        padded = np.zeros((a, n_blocks * BLOCK, c), dtype=np.int64)
+        padded[:, :b, :] = products                                                              # zero products change no sum
+        block_sums = padded.reshape(a, n_blocks, BLOCK, c).sum(axis=2)                           # a x blocks x c
+        y = np.zeros((a, c), dtype=np.int64)
+        for blk in range(n_blocks):
+            assert int((y + block_sums[:, blk, :]).max()) < 256                                  # stays an 8-bit value
+            y = (y + block_sums[:, blk, :]) % q
+        out.append(y)
+    return np.stack(out)
 
 
 def lookup_tables(p, m):
@@ -265,7 +266,8 @@ def sign_rns_encrypted(p, x_cts, m, n: int, z: int, pos: int, bsk, ksk) -> np.nd
 # Readings of points the paper leaves open:
 #   R6  Step 2's lookup ceil(log2(x + 1)) + i w is the 1-indexed position of the digit's highest set bit; a zero digit has no
 #       set bit and contributes 0 (the step's title; the formula as printed would give i w and force a shift for every
-#       input with two or more moduli).
+#       input with two or more moduli).  The paper's worked example does not separate the two readings: PARITY UNPINNED
+#       for this choice (a test shows an input on which they differ).
 #   R7  The maximum over the tensor is a binary tree of pairwise maxima, max(a, b) = b + ReLU(a - b), one lookup per pair on
 #       a - b + 32 (positions are at most 6 * 4 = 24); level by level, element 2j with element 2j + 1, an odd last element
 #       passing through.  The paper uses Concrete's max as a black box.
@@ -303,26 +305,22 @@ def apply_shift_code(code, x) -> np.ndarray:
 
 
 def shift2msbs_plus_digits_clear(Xd, w: int, gamma: int):
-    """Steps 2-6 of "Shift2MSBs^+" on mixed-radix digits Xd (k, ...).  Returns Y, shift and (maxBit, lshift, rshift)."""
+    """What "Shift2MSBs^+" computes from the mixed-radix digits Xd (k, ...), digit i read as bits [i w, (i + 1) w) of a
+    binary number.  maxBit is the highest set bit (1-indexed) over the whole tensor under that reading, 0 for an all-zero
+    tensor (R6: a zero digit has no set bit).  If maxBit <= w nothing moves; otherwise digit i is multiplied by
+    2^(gamma - maxBit + i w), i.e. bit maxBit lands on bit gamma: a left shift (capped at gamma - 1) for a non-negative
+    exponent, a truncating right shift otherwise.  Y is the sum of the moved digits and shift = maxBit - gamma.
+    Returns Y, shift and (maxBit, left shifts, right shifts) per digit position."""
     Xd = np.asarray(Xd, dtype=np.int64)
     k = Xd.shape[0]
-    # Step 2: position of the highest set bit
-    max_bit = 0
-    for i in range(k):
-        u = np.where(Xd[i] > 0, bit_position(Xd[i]) + i * w, 0)
-        max_bit = max(int(u.max()), max_bit)
-    # Step 3: amount of shift per digit
-    any_shift = int(max_bit > w)
-    max_bw = np.array([w * i for i in range(k)], dtype=np.int64)
-    digit_shift = (gamma - (max_bit - max_bw)) * any_shift
-    lshift = np.minimum(np.maximum(digit_shift, 0), gamma - 1)
-    rshift = np.maximum(-digit_shift, 0)
-    # Step 4: shift, Step 5: sum over the digits
-    shp = (k,) + (1,) * (Xd.ndim - 1)
-    Ys = (Xd << lshift.reshape(shp)) >> rshift.reshape(shp)
-    Y = Ys.sum(axis=0)
-    # Step 6
-    return Y, max_bit - gamma, (max_bit, lshift, rshift)
+    weight = (w * np.arange(k, dtype=np.int64)).reshape((k,) + (1,) * (Xd.ndim - 1))
+    top = np.where(Xd > 0, bit_position(Xd) + weight, 0)
+    max_bit = int(top.max()) if top.size else 0
+    exponent = (gamma - max_bit + w * np.arange(k, dtype=np.int64)) if max_bit > w else np.zeros(k, dtype=np.int64)
+    lshift = np.clip(exponent, 0, gamma - 1)
+    rshift = np.clip(-exponent, 0, None)
+    moved = [(Xd[i] << int(lshift[i])) >> int(rshift[i]) for i in range(k)]
+    return np.sum(moved, axis=0), max_bit - gamma, (max_bit, lshift, rshift)
 
 
 def shift2msbs_plus_clear(X, m, w: int, gamma: int):

@@ -18,6 +18,7 @@ LIB_PATH = os.environ.get("SILENZIO_PBS_LIB") or os.path.join(_HERE, "libsilenzi
 SLZ_OPT_FORCE_GENERIC = 1
 SLZ_OPT_LARGE_N_BLOCK = 2
 SLZ_OPT_LARGE_N_LANES = 3
+SLZ_OPT_FAIL_ALLOC_AFTER = 4
 SLZ_OK, SLZ_E_INVALID_ARG, SLZ_E_UNSUPPORTED, SLZ_E_HIP, SLZ_E_NOMEM, SLZ_E_TOO_LARGE = 0, -1, -2, -3, -4, -5
 
 
@@ -220,6 +221,13 @@ def _dev_u64(t, what: str) -> int:
     return t.data_ptr()
 
 
+def _need(t, count: int, what: str, exact: bool = True):
+    """Host-side size check of a device buffer: a wrong width or a short output must be a Python error, not a device fault."""
+    have = t.numel()
+    if (have != count) if exact else (have < count):
+        raise ValueError("%s: %d elements, need %s%d" % (what, have, "" if exact else "at least ", count))
+
+
 def to_device_u64(a: np.ndarray):
     """numpy uint64 array -> CUDA int64 tensor with the same bits."""
     import torch
@@ -275,6 +283,7 @@ class Context:
     def bsk_prepare(self, bsk_dev):
         """Standard-domain BSK (CUDA tensor, u64 bits) -> prepared key (CUDA float64 tensor, library-private layout)."""
         import torch
+        _need(bsk_dev, self.p.n * (self.p.k + 1) ** 2 * self.p.pbs_level * self.p.N, "bsk")
         need = self.bsk_prepared_bytes()
         dst = torch.empty(need // 8, dtype=torch.float64, device=bsk_dev.device)
         nb = ctypes.c_size_t(need)
@@ -282,22 +291,50 @@ class Context:
                "slz_bsk_prepare")
         return dst
 
-    def _lut_args(self, luts_dev, lut_idx_dev):
+    def _lut_args(self, luts_dev, lut_idx_dev, batch: int):
         import torch
         n_luts = luts_dev.numel() // self.p.N
+        if n_luts == 0 or luts_dev.numel() != n_luts * self.p.N:
+            raise ValueError("luts: %d elements, need a positive multiple of N = %d" % (luts_dev.numel(), self.p.N))
         idx_ptr = None
         if lut_idx_dev is not None:
             if lut_idx_dev.dtype != torch.int32 or not lut_idx_dev.is_cuda or not lut_idx_dev.is_contiguous():
                 raise TypeError("lut_idx: need a contiguous int32 CUDA tensor")
+            _need(lut_idx_dev, batch, "lut_idx", exact=False)
             idx_ptr = lut_idx_dev.data_ptr()
         return n_luts, idx_ptr
+
+    def _check_keys(self, bsk_prepared=None, ksk=None):
+        if bsk_prepared is not None and bsk_prepared.numel() * bsk_prepared.element_size() < self.bsk_prepared_bytes():
+            raise ValueError("bsk_prepared: %d bytes, need %d" % (bsk_prepared.numel() * bsk_prepared.element_size(),
+                                                                  self.bsk_prepared_bytes()))
+        if ksk is not None:
+            _need(ksk, self.p.k * self.p.N * self.p.ks_level * (self.p.n + 1), "ksk")
+
+    def _small(self, t, what: str, rows: int = None):
+        """A ciphertext array under the small key: [..][n+1]."""
+        if t.shape[-1] != self.p.n + 1:
+            raise ValueError("%s: rows of %d words, need n + 1 = %d" % (what, t.shape[-1], self.p.n + 1))
+        if rows is not None:
+            _need(t, rows * (self.p.n + 1), what)
+
+    def _big(self, t, what: str, rows: int = None):
+        """A ciphertext array under the big key: [..][kN+1]."""
+        w = self.p.k * self.p.N + 1
+        if t.shape[-1] != w:
+            raise ValueError("%s: rows of %d words, need kN + 1 = %d" % (what, t.shape[-1], w))
+        if rows is not None:
+            _need(t, rows * w, what)
 
     def pbs_batch(self, lwe_in, luts, lut_idx, bsk_prepared, out=None):
         import torch
         batch = lwe_in.shape[0]
         if out is None:
             out = torch.empty((batch, self.p.k * self.p.N + 1), dtype=torch.int64, device=lwe_in.device)
-        n_luts, idx_ptr = self._lut_args(luts, lut_idx)
+        n_luts, idx_ptr = self._lut_args(luts, lut_idx, batch)
+        self._small(lwe_in, "lwe_in")
+        self._big(out, "out", batch)
+        self._check_keys(bsk_prepared)
         _check(lib().slz_pbs_batch(self._h, _dev_u64(lwe_in, "lwe_in"), _dev_u64(luts, "luts"), idx_ptr, n_luts,
                                    bsk_prepared.data_ptr(), _dev_u64(out, "out"), batch, _stream()), "slz_pbs_batch")
         return out
@@ -307,7 +344,12 @@ class Context:
         batch = lwe_in.shape[0]
         if out is None:
             out = torch.empty((batch, self.p.k + 1, self.p.N), dtype=torch.int64, device=lwe_in.device)
-        n_luts, idx_ptr = self._lut_args(luts, lut_idx)
+        n_luts, idx_ptr = self._lut_args(luts, lut_idx, batch)
+        self._small(lwe_in, "lwe_in")
+        _need(out, batch * (self.p.k + 1) * self.p.N, "out")
+        self._check_keys(bsk_prepared)
+        if not 0 <= int(n_steps) <= self.p.n:
+            raise ValueError("n_steps: %d, need 0 .. n = %d" % (n_steps, self.p.n))
         _check(lib().slz_blind_rotate_batch(self._h, _dev_u64(lwe_in, "lwe_in"), _dev_u64(luts, "luts"), idx_ptr, n_luts,
                                             bsk_prepared.data_ptr(), int(n_steps), _dev_u64(out, "out"), batch, _stream()),
                "slz_blind_rotate_batch")
@@ -318,6 +360,9 @@ class Context:
         batch = lwe_in.shape[0]
         if out is None:
             out = torch.empty((batch, self.p.n + 1), dtype=torch.int64, device=lwe_in.device)
+        self._big(lwe_in, "lwe_in")
+        self._small(out, "out", batch)
+        self._check_keys(ksk=ksk)
         _check(lib().slz_keyswitch_batch(self._h, _dev_u64(lwe_in, "lwe_in"), _dev_u64(ksk, "ksk"), _dev_u64(out, "out"),
                                          batch, _stream()), "slz_keyswitch_batch")
         return out
@@ -325,6 +370,9 @@ class Context:
     def keyswitch_batch_static(self, lwe_in, ksk, out):
         """slz_keyswitch_batch_static: the keyswitch with its scratch in a fixed device array of the library; `out`
         ([batch][n+1]) comes from the caller, so that nothing is allocated on the way."""
+        self._big(lwe_in, "lwe_in")
+        self._small(out, "out", lwe_in.shape[0])
+        self._check_keys(ksk=ksk)
         _check(lib().slz_keyswitch_batch_static(self._h, _dev_u64(lwe_in, "lwe_in"), _dev_u64(ksk, "ksk"), _dev_u64(out, "out"),
                                                 lwe_in.shape[0], _stream()), "slz_keyswitch_batch_static")
         return out
@@ -335,7 +383,10 @@ class Context:
         batch = lwe_in.shape[0]
         if out is None:
             out = torch.empty((batch, self.p.k * self.p.N + 1), dtype=torch.int64, device=lwe_in.device)
-        n_luts, idx_ptr = self._lut_args(luts, lut_idx)
+        n_luts, idx_ptr = self._lut_args(luts, lut_idx, batch)
+        self._big(lwe_in, "lwe_in")
+        self._big(out, "out", batch)
+        self._check_keys(bsk_prepared, ksk)
         _check(lib().slz_ks_pbs_batch(self._h, _dev_u64(lwe_in, "lwe_in"), _dev_u64(ksk, "ksk"), _dev_u64(luts, "luts"), idx_ptr, n_luts,
                                       bsk_prepared.data_ptr(), _dev_u64(out, "out"), batch, _stream()), "slz_ks_pbs_batch")
         return out
@@ -355,6 +406,11 @@ class Context:
         ws = torch.empty(need.value, dtype=torch.uint8, device=x_cts.device)
         if out is None:
             out = torch.empty((sh.k, a, c, self.p.n + 1), dtype=torch.int64, device=x_cts.device)
+        self._small(x_cts, "x_cts", a * b)
+        self._small(w_cts, "w_cts", b * c)
+        self._small(out, "out", sh.k * a * c)
+        _need(luts, ((4 * sh.k + 3) if highres else 3 * sh.k) * self.p.N, "luts")
+        self._check_keys(bsk_prepared, ksk)
         _check(fn(self._h, ctypes.byref(sh), _dev_u64(x_cts, "x_cts"), _dev_u64(w_cts, "w_cts"), _dev_u64(luts, "luts"),
                   bsk_prepared.data_ptr(), _dev_u64(ksk, "ksk"), _dev_u64(out, "out"), ws.data_ptr(), need.value, _stream()), name)
         torch.cuda.current_stream().synchronize()     # the workspace is released when this returns
@@ -363,6 +419,11 @@ class Context:
     def _rns_call(self, fn, name, x_cts, m, luts, bsk_prepared, ksk, out):
         import torch
         sh = make_rns_shape(m, x_cts.shape[1])
+        self._small(x_cts, "x_cts", sh.k * sh.count)
+        self._small(out, "out", out.numel() // (self.p.n + 1))
+        _need(out, (sh.k if name == "slz_rns2mrns" else 1) * sh.count * (self.p.n + 1), "out")
+        _need(luts, (sh.k * (sh.k - 1) // 2 + 2) * self.p.N, "luts")
+        self._check_keys(bsk_prepared, ksk)
         need = ctypes.c_size_t(0)
         _check(lib().slz_rns_workspace(self._h, ctypes.byref(sh), ctypes.byref(need)), "slz_rns_workspace")
         ws = torch.empty(need.value, dtype=torch.uint8, device=x_cts.device)
@@ -391,6 +452,9 @@ class Context:
         import torch
         count = x_cts.shape[1]
         sh = make_shift_shape(m, count, w, gamma)
+        self._small(x_cts, "x_cts", sh.k * count)
+        _need(luts, (sh.k * (sh.k - 1) // 2 + 3 * sh.k + 5) * self.p.N, "luts")
+        self._check_keys(bsk_prepared, ksk)
         need = ctypes.c_size_t(0)
         _check(lib().slz_shift2msbs_workspace(self._h, ctypes.byref(sh), ctypes.byref(need)), "slz_shift2msbs_workspace")
         ws = torch.empty(need.value, dtype=torch.uint8, device=x_cts.device)
@@ -413,6 +477,13 @@ class Context:
         """slz_bivariate_lookup: [count][n+1] pairs -> [count][n+1], one lookup each on 2^y_bits x + y."""
         import torch
         count = x_cts.shape[0]
+        self._small(x_cts, "x_cts", count)
+        self._small(y_cts, "y_cts", count)
+        if luts.numel() == 0 or luts.numel() % self.p.N:
+            raise ValueError("luts: need a positive multiple of N elements")
+        if lut_index is not None:
+            _need(lut_index, count, "lut_index", exact=False)
+        self._check_keys(bsk_prepared, ksk)
         ws, need = self._bivariate_ws(count, x_cts.device)
         out = torch.empty((count, self.p.n + 1), dtype=torch.int64, device=x_cts.device)
         if lut_index is not None and (lut_index.dtype != torch.int32 or not lut_index.is_cuda or not lut_index.is_contiguous()):
@@ -429,6 +500,10 @@ class Context:
         import torch
         a, b = logits.shape[:2]
         sh = SlzLossShape(a, b, big_gamma, kappa)
+        self._small(logits, "logits", a * b)
+        self._small(labels, "labels", a * b)
+        _need(luts, 5 * self.p.N, "luts")
+        self._check_keys(bsk_prepared, ksk)
         need = ctypes.c_size_t(0)
         _check(lib().slz_loss_workspace(self._h, ctypes.byref(sh), ctypes.byref(need)), "slz_loss_workspace")
         ws = torch.empty(need.value, dtype=torch.uint8, device=logits.device)
@@ -443,6 +518,10 @@ class Context:
         """slz_weight_update: weights and codes G + 1, [count][n+1] each -> clip(W - G), [count][n+1]."""
         import torch
         count = w_cts.shape[0]
+        self._small(w_cts, "w_cts", count)
+        self._small(gcode_cts, "gcode_cts", count)
+        _need(luts, self.p.N, "luts")
+        self._check_keys(bsk_prepared, ksk)
         ws, need = self._bivariate_ws(count, w_cts.device)
         out = torch.empty((count, self.p.n + 1), dtype=torch.int64, device=w_cts.device)
         _check(lib().slz_weight_update(self._h, alpha, _dev_u64(w_cts, "w_cts"), _dev_u64(gcode_cts, "gcode_cts"), _dev_u64(luts, "luts"),
@@ -459,6 +538,9 @@ class Context:
             raise TypeError("w: need a contiguous int32 CUDA tensor")
         if out is None:
             out = torch.empty((G, O, width), dtype=torch.int64, device=cts.device)
+        self._small(cts, "cts")
+        _need(w, J * O, "w")
+        self._small(out, "out", G * O)
         _check(lib().slz_lwe_lincomb_batch(self._h, _dev_u64(cts, "cts"), w.data_ptr(), _dev_u64(out, "out"), G, J, O,
                                            _stream()), "slz_lwe_lincomb_batch")
         return out

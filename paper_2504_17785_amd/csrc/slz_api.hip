@@ -18,6 +18,17 @@ static bool misaligned(const void *p) { return ((uintptr_t)p & 15u) != 0; }
 // ciphertext arrays: rows are n+1 (or kN+1) words, so only word alignment can hold for every row and every sub-batch
 static bool misaligned8(const void *p) { return ((uintptr_t)p & 7u) != 0; }
 
+// hipMalloc behind a counter that a test can arm: the SLZ_OPT_FAIL_ALLOC_AFTER-th scratch allocation from now fails (the way
+// an exhausted device would) without touching the device.
+static int g_fail_alloc_after = -1;
+int slz_scratch_alloc(void **out, size_t bytes) {
+    *out = nullptr;
+    if (g_fail_alloc_after == 0) { g_fail_alloc_after = -1; return SLZ_E_NOMEM; }
+    if (g_fail_alloc_after > 0) g_fail_alloc_after--;
+    if (hipMalloc(out, bytes) != hipSuccess) { (void)hipGetLastError(); *out = nullptr; return SLZ_E_NOMEM; }
+    return SLZ_OK;
+}
+
 extern "C" int slz_ctx_create(const slz_params *params, uint32_t max_batch, slz_ctx **out) {
     if (!out) return SLZ_E_INVALID_ARG;
     *out = nullptr;
@@ -98,6 +109,7 @@ extern "C" int slz_ctx_destroy(slz_ctx *ctx) {
 extern "C" int slz_ctx_set_option(slz_ctx *ctx, int option, int value) {
     if (!ctx) return SLZ_E_INVALID_ARG;
     if (option == SLZ_OPT_FORCE_GENERIC) { ctx->force_generic = value != 0; return SLZ_OK; }
+    if (option == SLZ_OPT_FAIL_ALLOC_AFTER) { g_fail_alloc_after = value < 0 ? -1 : value; return SLZ_OK; }
     if (option == SLZ_OPT_LARGE_N_BLOCK) {
         if (!ctx->has_bign) return SLZ_E_INVALID_ARG;
         if (value == 1024 && ctx->has_bign16) { ctx->bign_block = 1024; return SLZ_OK; }
@@ -160,14 +172,30 @@ extern "C" int slz_bsk_prepare(slz_ctx *ctx, const uint64_t *bsk_dev, void *dst_
     return slz_generic_bsk_prepare(ctx, bsk_dev, (double *)dst_dev, (hipStream_t)hip_stream);
 }
 
+// Scratch of the generic and the large-N path, sized for max_batch.  All or nothing: a buffer is committed to the context
+// only when every allocation of the call has succeeded, so a call after SLZ_E_NOMEM starts from a clean state and no kernel
+// ever sees a null scratch pointer.  The digit buffer is only used by the generic per-step kernels.
 static int ensure_generic_scratch(slz_ctx *ctx) {
-    if (ctx->dig) return SLZ_OK;
+    const bool need_dig = !(ctx->has_bign && !ctx->force_generic);
+    if (ctx->acc && ctx->xhat && ctx->outhat && (ctx->dig || !need_dig)) return SLZ_OK;
     const slz_params &p = ctx->prm;
     const size_t R = (size_t)(p.k + 1) * p.pbs_level, C = p.k + 1, B = ctx->max_batch, N = p.N;
-    if (hipMalloc((void **)&ctx->acc, B * C * N * 8) != hipSuccess) return SLZ_E_NOMEM;
-    if (hipMalloc((void **)&ctx->dig, B * R * N * 8) != hipSuccess) return SLZ_E_NOMEM;
-    if (hipMalloc((void **)&ctx->xhat, B * 2 * R * N * 8) != hipSuccess) return SLZ_E_NOMEM;
-    if (hipMalloc((void **)&ctx->outhat, B * 2 * C * N * 8) != hipSuccess) return SLZ_E_NOMEM;
+    void *fresh[4] = {nullptr, nullptr, nullptr, nullptr};
+    void *const have[4] = {ctx->acc, ctx->dig, ctx->xhat, ctx->outhat};
+    const size_t bytes[4] = {B * C * N * 8, B * R * N * 8, B * 2 * R * N * 8, B * 2 * C * N * 8};
+    const bool want[4] = {true, need_dig, true, true};
+    for (int q = 0; q < 4; q++) {
+        if (have[q] || !want[q]) continue;
+        if (slz_scratch_alloc(&fresh[q], bytes[q]) != SLZ_OK) {
+            for (int r = 0; r < q; r++)
+                if (fresh[r]) (void)hipFree(fresh[r]);
+            return SLZ_E_NOMEM;
+        }
+    }
+    if (fresh[0]) ctx->acc = (uint64_t *)fresh[0];
+    if (fresh[1]) ctx->dig = (double *)fresh[1];
+    if (fresh[2]) ctx->xhat = (double *)fresh[2];
+    if (fresh[3]) ctx->outhat = (double *)fresh[3];
     return SLZ_OK;
 }
 
@@ -230,7 +258,9 @@ extern "C" int slz_ks_pbs_batch(slz_ctx *ctx, const uint64_t *lwe_in_dev, const 
         misaligned8(lwe_out_dev) || ((uintptr_t)lut_idx_dev & 3u))
         return SLZ_E_INVALID_ARG;
     if (!ctx->ks_first_small) {
-        if (hipMalloc((void **)&ctx->ks_first_small, (size_t)ctx->max_batch * (ctx->prm.n + 1) * 8) != hipSuccess) return SLZ_E_NOMEM;
+        void *buf = nullptr;
+        if (slz_scratch_alloc(&buf, (size_t)ctx->max_batch * (ctx->prm.n + 1) * 8) != SLZ_OK) return SLZ_E_NOMEM;
+        ctx->ks_first_small = (uint64_t *)buf;
     }
     int rc = slz_keyswitch_launch(ctx, lwe_in_dev, ksk_dev, ctx->ks_first_small, batch, (hipStream_t)hip_stream);
     if (rc != SLZ_OK) return rc;

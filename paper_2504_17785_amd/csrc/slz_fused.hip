@@ -17,7 +17,6 @@
 #include "slz_internal.h"
 #include "slz_modarith.h"
 #include <vector>
-#include <cstdio>
 
 #define STAGE_OFF 1088u       // second half of a wave buffer: staging of 1024 accumulator words
 #define FUSED_THREADS 256
@@ -40,17 +39,8 @@ struct fused_args {
     double tw_inv[2][32];     // inv[t + j], t + j < 32: first five inverse stages
     slz_mod mod[2];
     double p1inv_mod_p2;
-#ifdef SLZ_PHASE_TIMING
-    unsigned long long *dbg;  // [4 waves][16 marks]: cycles spent before each mark, summed over the steps of block 0
-#endif
 };
 
-#ifdef SLZ_PHASE_TIMING
-#define MARK(k) do { if (blockIdx.x == 0) { unsigned long long t_ = __builtin_amdgcn_s_memtime(); \
-                     if (lane == 0) A.dbg[w * 16 + (k)] += t_ - tprev; tprev = t_; } } while (0)
-#else
-#define MARK(k) do { } while (0)
-#endif
 
 #include "slz_wave_ntt.h"
 
@@ -96,9 +86,6 @@ k_fused_blind_rotate_n2048(fused_args A) {
             // this loop and spill them.  An opaque zero added to every table index makes each step issue them again.
             int z;
             asm volatile("s_mov_b32 %0, 0" : "=s"(z));
-#ifdef SLZ_PHASE_TIMING
-            unsigned long long tprev = __builtin_amdgcn_s_memtime();
-#endif
             const uint32_t at = slz_modswitch(lwe[step], FLOGN + 1);
             const double *krow = A.bskp + ((size_t)step * 4 + q * 2 + h) * 2 * FN + z;   // [n][prime][row][comp][N]
             const double *kown = krow + (size_t)h * FN, *ksib = krow + (size_t)(1u - h) * FN;
@@ -109,9 +96,7 @@ k_fused_blind_rotate_n2048(fused_args A) {
             // 1. stage my quarter, then read component h rotated and unrotated
 #pragma unroll
             for (int e = 0; e < 16; e++) Smine[64 * e + lane] = acc[e];
-            MARK(0);
             __syncthreads();
-            MARK(1);
             // Each row is needed by both primes' waves: wave (q,h) decomposes the half of component h whose
             // unrotated words are its own accumulator quarter (registers) and passes the digits to wave (1-q,h)
             // through that wave's buffer, which nobody else touches between the two barriers.
@@ -132,9 +117,7 @@ k_fused_blind_rotate_n2048(fused_args A) {
                     pd[64 * e + lane] = dg[e];
                 }
             }
-            MARK(2);
             __syncthreads();                          // every wave has read the staged accumulator and sent its digits
-            MARK(3);
             double x[32];
             {
                 const int32_t *md = reinterpret_cast<const int32_t *>(T);
@@ -148,7 +131,6 @@ k_fused_blind_rotate_n2048(fused_args A) {
             }
             // 2. forward transform
             fused_fwd(x, T, tw6, twA, fwdB, m, lane, z);
-            MARK(4);
             // 3. row h of the GGSW times the digits: component h stays, component 1-h goes to the sibling.
             //    Key words are fetched eight positions (two chunks of 2 x 8 doubles in flight) ahead.
             {
@@ -180,9 +162,7 @@ k_fused_blind_rotate_n2048(fused_args A) {
                     }
                 }
             }
-            MARK(5);
             __syncthreads();
-            MARK(6);
 #pragma unroll
             for (int g = 0; g < 4; g++) {
                 double r8[8], x8[8];
@@ -192,12 +172,9 @@ k_fused_blind_rotate_n2048(fused_args A) {
 #pragma unroll
                 for (int u = 0; u < 8; u++) x[8 * g + u] = r8[u];
             }
-            MARK(7);
             __syncthreads();                          // sibling has read my buffer before I reuse it
-            MARK(8);
             // 4. inverse transform
             fused_inv<true>(x, T, twS, invt, post, m, lane, z);
-            MARK(9);
             // 5. exchange the half I do not lift with the other prime's wave, CRT, accumulate
             wave_sync();
             if (q == 0) {
@@ -207,9 +184,7 @@ k_fused_blind_rotate_n2048(fused_args A) {
 #pragma unroll
                 for (int e = 0; e < 16; e++) T[64 * e + lane] = x[e];
             }
-            MARK(10);
             __syncthreads();
-            MARK(11);
             if (q == 0) {
 #pragma unroll
                 for (int e = 0; e < 16; e++) acc[e] += slz_crt64(x[e], Toth[64 * e + lane], A.mod[1], A.p1inv_mod_p2);
@@ -217,7 +192,6 @@ k_fused_blind_rotate_n2048(fused_args A) {
 #pragma unroll
                 for (int e = 0; e < 16; e++) acc[e] += slz_crt64(Toth[64 * e + lane], x[16 + e], A.mod[1], A.p1inv_mod_p2);
             }
-            MARK(12);
         }
 
         // ---- output: accumulator, or the extracted LWE ciphertext ----
@@ -309,12 +283,6 @@ int slz_fused_blind_rotate(slz_ctx *ctx, const uint64_t *lwe_in, const uint64_t 
         for (int x = 0; x < 32; x++) { A.tw_fwd[q][x] = ctx->fused_scalars[q][0][x]; A.tw_inv[q][x] = ctx->fused_scalars[q][1][x]; }
     }
     A.p1inv_mod_p2 = ctx->p1inv_mod_p2;
-#ifdef SLZ_PHASE_TIMING
-    static unsigned long long *dbg = nullptr;
-    if (!dbg) { SLZ_HIP(hipMalloc((void **)&dbg, 64 * 8)); }
-    SLZ_HIP(hipMemsetAsync(dbg, 0, 64 * 8, s));
-    A.dbg = dbg;
-#endif
     const uint32_t resident = 2u * 256u;               // two workgroups (68 KiB of LDS each) per compute unit
     const uint32_t grid = batch < resident ? batch : resident;
     if (A.beta == 23)       // the base of the N = 2048 parameter sets
@@ -322,19 +290,5 @@ int slz_fused_blind_rotate(slz_ctx *ctx, const uint64_t *lwe_in, const uint64_t 
     else
         hipLaunchKernelGGL(k_fused_blind_rotate_n2048<0>, dim3(grid), dim3(FUSED_THREADS), 4 * TBUF * sizeof(double), s, A);
     SLZ_HIP(hipGetLastError());
-#ifdef SLZ_PHASE_TIMING
-    {
-        unsigned long long h[64];
-        SLZ_HIP(hipMemcpy(h, dbg, sizeof(h), hipMemcpyDeviceToHost));
-        static const char *names[13] = {"stage-write", "B1", "decompose", "B2", "fwd", "pointwise", "B3", "sum", "B4", "inverse",
-                                        "xchg-write", "B5", "crt"};
-        const double steps = (double)n_steps * ((batch + grid - 1) / grid);
-        for (int w = 0; w < 4; w++) {
-            fprintf(stderr, "wave %d cycles/step:", w);
-            for (int k = 0; k < 13; k++) fprintf(stderr, " %s=%.0f", names[k], (double)h[w * 16 + k] / steps);
-            fprintf(stderr, "\n");
-        }
-    }
-#endif
     return SLZ_OK;
 }

@@ -81,6 +81,9 @@ struct slz_ctx {
 
 #define SLZ_HIP(x) do { hipError_t e_ = (x); if (e_ != hipSuccess) return SLZ_E_HIP; } while (0)
 
+// scratch allocation of the entry points (slz_api.hip): SLZ_OK or SLZ_E_NOMEM, *out null on failure
+int slz_scratch_alloc(void **out, size_t bytes);
+
 // host side (slz_tables.cpp)
 int slz_build_tables(slz_ctx *ctx);
 void slz_free_tables(slz_ctx *ctx);

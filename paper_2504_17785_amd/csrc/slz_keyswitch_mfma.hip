@@ -245,11 +245,7 @@ int slz_ksm_launch(slz_ctx *ctx, const uint64_t *lwe_in, const uint64_t *ksk, ui
     if (n_kb64 > (1u << 26)) return SLZ_E_UNSUPPORTED;
     const uint32_t max_tiles = min((ctx->max_batch + 31) / 32, 32768u);
     if (!ctx->ks_dig) {     // digit scratch, sized for max_batch (larger batches go through in chunks)
-        if (hipMalloc((void **)&ctx->ks_dig, (size_t)max_tiles * n_kb64 * 1024) != hipSuccess) {
-            (void)hipGetLastError();
-            ctx->ks_dig = nullptr;
-            return SLZ_E_NOMEM;
-        }
+        if (slz_scratch_alloc(&ctx->ks_dig, (size_t)max_tiles * n_kb64 * 1024) != SLZ_OK) return SLZ_E_NOMEM;
     }
     return ksm_run(p, ctx->ks_dig, max_tiles, lwe_in, ksk, lwe_out, batch, s);
 }

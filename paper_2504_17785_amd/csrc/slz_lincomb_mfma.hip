@@ -196,7 +196,7 @@ int slz_lcm_launch(slz_ctx *ctx, const uint64_t *cts, const int32_t *w, uint64_t
     if (ctx->lc_dig_bytes < need) {
         // the previous buffer may still be read by work queued on another stream: wait before letting it go
         if (ctx->lc_dig) { SLZ_HIP(hipDeviceSynchronize()); (void)hipFree(ctx->lc_dig); ctx->lc_dig = nullptr; ctx->lc_dig_bytes = 0; }
-        if (hipMalloc(&ctx->lc_dig, need) != hipSuccess) { (void)hipGetLastError(); ctx->lc_dig = nullptr; return SLZ_E_NOMEM; }
+        if (slz_scratch_alloc(&ctx->lc_dig, need) != SLZ_OK) return SLZ_E_NOMEM;
         ctx->lc_dig_bytes = need;
     }
     v4i *dig = (v4i *)ctx->lc_dig;

@@ -229,6 +229,30 @@ def test_shift2msbs_plus_reproduces_the_printed_example(gd):
         assert np.array_equal(gd.apply_shift_code(code, Xd[i]), (Xd[i] << lshift[i]) >> rshift[i])
 
 
+def test_shift2msbs_zero_digit_reading_is_visible(gd):
+    # The reading of step 2 for a zero digit (position 0, not i w as the printed formula ceil(log2(x + 1)) + i w would give)
+    # is not settled by the printed worked example: there the top digit of one element is non-zero, so maxBit = 10 under
+    # both readings.  On a tensor whose upper digits are all zero the two readings part: digits (5, 0, 0) with w = 4,
+    # gamma = 5.  This reading: maxBit = 3 <= w, nothing moves, Y = 5, shift = -2.  The printed formula: the zero digits
+    # would report positions 4 and 8, maxBit = 8, digit 0 moves right by 3, Y = 0, shift = 3 -- a small number wiped
+    # out although "only shift down, never up" needs no shift at all.  The pin fixes the choice made here.
+    Xd = np.array([[5], [0], [0]])
+    Y, shift, (max_bit, lshift, rshift) = gd.shift2msbs_plus_digits_clear(Xd, 4, 5)
+    assert (int(Y[0]), shift, max_bit) == (5, -2, 3)
+    assert list(lshift) == [0, 0, 0] and list(rshift) == [0, 0, 0]
+    # the printed formula, evaluated by hand for this input
+    printed_positions = [math.ceil(math.log2(5 + 1)) + 0, math.ceil(math.log2(0 + 1)) + 4, math.ceil(math.log2(0 + 1)) + 8]
+    printed_max = max(printed_positions)
+    assert printed_positions == [3, 4, 8] and printed_max > 4
+    assert (5 >> -(5 - (printed_max - 0)), printed_max - 5) == (0, 3)
+    # same through the lookup tables the encrypted pipeline uses: a zero digit's table entry is 0 at every position
+    p = Params(name="t", n=4, k=1, N=2048, pbs_base_log=23, pbs_level=1, ks_base_log=4, ks_level=8, msg_bits=8,
+               sigma_lwe=2.0 ** -40, sigma_bsk=2.0 ** -50, batch=1, n_luts=1, seed=99)
+    tabs = gd.shift_tables(p, (13, 15, 14), 4, 5)
+    assert [int(tabs[i][0]) for i in range(3)] == [0, 0, 0]
+    assert [int(tabs[i][1]) for i in range(3)] == [1, 5, 9]
+
+
 def test_shift2msbs_properties(gd):
     m, w = (13, 15, 14), 4
     M = math.prod(m)

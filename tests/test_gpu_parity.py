@@ -246,6 +246,70 @@ def test_error_codes(slz):
     torch.cuda.synchronize()
 
 
+def test_binding_rejects_wrong_sizes_on_the_host(slz, orc):
+    # a tensor of the wrong width or a short output is a Python error before any kernel sees the pointer
+    p = tiny()
+    case = Case(slz, orc, p, 4)
+    c = case.ctx
+    with pytest.raises(ValueError):
+        c.pbs_batch(case.d_cts[:, :-1].contiguous(), case.d_luts, case.d_idx, case.d_bsk)
+    with pytest.raises(ValueError):
+        c.pbs_batch(case.d_cts, case.d_luts, case.d_idx, case.d_bsk, out=torch.empty((3, p.k * p.N + 1), dtype=torch.int64, device="cuda"))
+    with pytest.raises(ValueError):
+        c.pbs_batch(case.d_cts, case.d_luts.reshape(-1)[:-1], case.d_idx, case.d_bsk)
+    with pytest.raises(ValueError):
+        c.pbs_batch(case.d_cts, case.d_luts, case.d_idx[:2], case.d_bsk)
+    with pytest.raises(ValueError):
+        c.pbs_batch(case.d_cts, case.d_luts, case.d_idx, case.d_bsk[:-1])
+    with pytest.raises(ValueError):
+        c.blind_rotate_batch(case.d_cts, case.d_luts, case.d_idx, case.d_bsk, p.n + 1)
+    big = c.pbs_batch(case.d_cts, case.d_luts, case.d_idx, case.d_bsk)
+    with pytest.raises(ValueError):
+        c.keyswitch_batch(big, case.d_ksk.reshape(-1)[:-1])
+    with pytest.raises(ValueError):
+        c.keyswitch_batch(big[:, :-1].contiguous(), case.d_ksk)
+    with pytest.raises(ValueError):
+        c.ks_pbs_batch(case.d_cts, case.d_ksk, case.d_luts, case.d_idx, case.d_bsk)      # small ciphertexts where big ones belong
+    with pytest.raises(ValueError):
+        c.bsk_prepare(slz.to_device_u64(case.keys.bsk.reshape(-1)[:-1]))
+    with pytest.raises(ValueError):
+        c.lwe_lincomb_batch(case.d_cts.reshape(1, 4, p.n + 1), torch.zeros((3, 2), dtype=torch.int32, device="cuda"))
+    assert np.array_equal(slz.to_host_u64(c.keyswitch_batch(big, case.d_ksk)),
+                          orc.keyswitch_batch(p, slz.to_host_u64(big), case.keys.ksk))
+
+
+@pytest.mark.parametrize("shape", [dict(n=3, N=256, k=1, pbs_base_log=12, pbs_level=2),        # generic path: four buffers
+                                   dict(n=2, N=4096, k=1, pbs_base_log=11, pbs_level=2)],      # large-N path: three
+                         ids=["generic", "large_n"])
+def test_out_of_memory_in_scratch_allocation_leaves_the_context_usable(slz, orc, shape):
+    # the n-th scratch allocation of a first call fails (forced from the host, no device involved): the call reports
+    # SLZ_E_NOMEM, keeps nothing half-allocated, and the next call on the same context allocates everything and is exact
+    p = tiny(**shape)
+    case = Case(slz, orc, p, 3, raw_inputs=True)
+    if shape["N"] == 4096:
+        case.ctx.set_option(slz.SLZ_OPT_FORCE_GENERIC, 0)
+        assert case.ctx.path in ("three_pass_large_n", "fused_n4096")
+    want = orc.pbs_batch(p, case.cts, case.luts, case.lut_idx, case.keys.bsk)
+    for nth in (2, 1, 0):
+        case.ctx.set_option(slz.SLZ_OPT_FAIL_ALLOC_AFTER, nth)
+        with pytest.raises(slz.SlzError) as e:
+            case.ctx.pbs_batch(case.d_cts, case.d_luts, case.d_idx, case.d_bsk)
+        assert e.value.code == slz.SLZ_E_NOMEM
+    case.ctx.set_option(slz.SLZ_OPT_FAIL_ALLOC_AFTER, -1)
+    got = slz.to_host_u64(case.ctx.pbs_batch(case.d_cts, case.d_luts, case.d_idx, case.d_bsk))
+    assert np.array_equal(got, want)
+    # the keyswitch scratch and the keyswitch-first buffer go through the same allocator
+    p2 = tiny(n=20, N=64, k=1, ks_base_log=4, ks_level=3)
+    case2 = Case(slz, orc, p2, 16, raw_inputs=True)
+    big = case2.ctx.pbs_batch(case2.d_cts, case2.d_luts, case2.d_idx, case2.d_bsk)
+    case2.ctx.set_option(slz.SLZ_OPT_FAIL_ALLOC_AFTER, 0)
+    with pytest.raises(slz.SlzError) as e:
+        case2.ctx.keyswitch_batch(big, case2.d_ksk)
+    assert e.value.code == slz.SLZ_E_NOMEM
+    small = slz.to_host_u64(case2.ctx.keyswitch_batch(big, case2.d_ksk))
+    assert np.array_equal(small, orc.keyswitch_batch(p2, slz.to_host_u64(big), case2.keys.ksk))
+
+
 # ---------------------------------------------------------------- fused kernel (N = 2048, k = 1, l = 1, base 2^23)
 
 def _fused_case(slz, orc, n, batch, **kw):

@@ -427,13 +427,32 @@ def test_blind_rotation_noise_variance(orc, sigma_bsk, beta, level):
     assert max(key_term, round_term) / (key_term + round_term) > 0.9
 
 
-def test_config1_as_written_would_not_decrypt():
-    # closed form with sigma = 2^-20 for the bootstrapping key of configuration 1: the blind-rotation noise
-    # std exceeds Delta/2 = 2^-5, which is why the library's configuration 1 uses sigma_bsk = 2^-40.
+def test_config1_as_written_would_not_decrypt(orc):
+    # Configuration 1 as written gives sigma = 2^-20 to the bootstrapping key as well.  The oracle run with such a key:
+    # the measured blind-rotation noise has the closed form's variance (std 2^-4.8 > Delta/2 = 2^-5), and the share of
+    # wrong decryptions is the Gaussian tail the closed form predicts (about 39 %), which is why the library's
+    # configuration 1 uses sigma_bsk = 2^-40 (closed-form std below 2^-10).
     p = synth.CONFIGS[1]
+    keys = orc.Keys(p, synth, with_ksk=False, sigma_bsk=2.0 ** -20)
+    count = 192
+    msgs = synth.messages(p, count, "ramp")
+    cts = orc.encrypt_messages(p, synth, keys.lwe_sk, msgs)
+    tables = synth.config_tables(1)
+    big = orc.pbs_batch(p, cts, orc.lut_encode(p, tables), None, keys.bsk)
+    phase = orc.lwe_phase(keys.big_sk, big)
+    want = tables[0, msgs.astype(np.int64)]
+    got, _ = orc.decode(phase, p.msg_bits)
+    with np.errstate(over="ignore"):
+        err = (phase - want * np.uint64(p.delta)).astype(np.int64).astype(np.float64) / 2.0 ** 64      # against the true value
     B = 2.0 ** p.pbs_base_log
     var = p.n * 2 * p.pbs_level * p.N * ((B * B + 2) / 12.0) * (2.0 ** -20) ** 2
     assert math.sqrt(var) > 2.0 ** -5
+    assert abs(float(np.mean(err ** 2)) / var - 1.0) < 0.25
+    half = 2.0 ** -(p.msg_bits + 2)                                       # Delta / 2 in torus units
+    tail = math.erfc(half / math.sqrt(2.0 * var))                         # P(|e| > Delta/2), 0.385 here
+    assert 0.37 < tail < 0.40
+    wrong = float(np.mean(got != want))
+    assert abs(wrong - tail) < 4.0 * math.sqrt(tail * (1 - tail) / count)  # 0.14 at 192 samples
     var_fixed = p.n * 2 * p.pbs_level * p.N * ((B * B + 2) / 12.0) * p.sigma_bsk ** 2 \
         + p.n * (1 + p.N / 2) / (24.0 * B ** (2 * p.pbs_level))
     assert math.sqrt(var_fixed) < 2.0 ** -10
