@@ -1,7 +1,10 @@
 """Benchmark of the hot path: one step = slz_pbs_batch + slz_keyswitch_batch over one batch of ciphertexts.
 
-Prints ONE JSON line.  Workload: configuration 2 of the baseline (1024 LWE ciphertexts, n=742, k=1, N=2048,
-PBS base 2^23 x 1 level, keyswitch base 2^3 x 5 levels) unless --config says otherwise.  Inputs are seeded
+Prints ONE JSON line.  Headline workload: configuration 5 of the baseline, the largest single-GPU batch of the
+128-bit-shaped parameter set (16 384 LWE ciphertexts, 64 lookup tables, n=742, k=1, N=2048, PBS base 2^23 x 1 level,
+keyswitch base 2^3 x 5 levels); the object "per_config" of the same line carries a short run of every other parameter
+set (configurations 1 to 4) with its own rates, roofline fractions and oracle check.  --config N times that
+configuration alone.  Inputs are seeded
 and synthetic and already resident in HBM when the timed region starts.  Key and ciphertext material for
 the timed run is uniform random u64 words (what TFHE keys and ciphertexts look like; the kernels have no
 data-dependent control flow); LUT polynomials come from slz_lut_encode.  The cpu_baseline leg runs the
@@ -275,14 +278,251 @@ def bench_loss(args):
     print(json.dumps(result))
 
 
+# ---- the PBS + keyswitch step of one configuration ---------------------------------------------------------------------
+
+PATH_SOURCES = {       # sources of the dominant kernel of each path (for the check that a stored traffic figure is current)
+    "fused_n2048": ("slz_fused.hip", "slz_wave_ntt.h", "slz_modarith.h"),
+    "fused_n512": ("slz_fused_n512.hip", "slz_wave_ntt.h", "slz_modarith.h"),
+    "three_pass_large_n": ("slz_bign.hip", "slz_wave_ntt.h", "slz_modarith.h"),
+}
+
+
+def kernel_source_hash(path: str):
+    import hashlib
+    files = PATH_SOURCES.get(path)
+    if not files:
+        return None
+    h = hashlib.sha256()
+    for f in files:
+        with open(os.path.join(ROOT, "paper_2504_17785_amd", "csrc", f), "rb") as fh:
+            h.update(fh.read())
+    return h.hexdigest()[:16]
+
+
+def stored_traffic(path: str, workload: str):
+    """HBM bytes per launch of the dominant kernel from the rocprofv3 FETCH_SIZE / WRITE_SIZE passes recorded in
+    profiles/hbm_traffic.txt (already scaled by the copy-kernel calibration).  None when no pass was recorded for this
+    path and workload, or when the kernel's sources have changed since (the line carries their hash)."""
+    try:
+        with open(os.path.join(ROOT, "profiles", "hbm_traffic.txt")) as fh:
+            for line in fh:
+                f = line.split()
+                if len(f) >= 6 and not line.startswith("#") and f[0] == path and f[1] == workload:
+                    return float(f[2]) + float(f[3]) if f[5] == kernel_source_hash(path) else None
+    except OSError:
+        pass
+    return None
+
+
+def host_info():
+    model = "unknown"
+    try:
+        with open("/proc/cpuinfo") as fh:
+            for line in fh:
+                if line.lower().startswith("model name"):
+                    model = line.split(":", 1)[1].strip()
+                    break
+    except OSError:
+        pass
+    try:
+        usable = len(os.sched_getaffinity(0))
+    except AttributeError:
+        usable = os.cpu_count()
+    return {"nproc": os.cpu_count(), "usable_cpus": usable, "cpu_model": model}
+
+
+class Workload:
+    """Keys, tables and ciphertexts of one configuration, resident in HBM, and the launch of one step."""
+
+    def __init__(self, cfg, args, batch=0):
+        import torch
+        import synth
+        import paper_2504_17785_amd as slz
+        self.slz, self.synth, self.torch, self.cfg = slz, synth, torch, cfg
+        p = synth.CONFIGS[cfg]
+        if args.override:       # another shape with the configuration's tables and message space, e.g. N=4096,pbs_base_log=22,n=256
+            kw = {k.strip(): int(v) for k, v in (item.split("=") for item in args.override.split(","))}
+            p = p.with_(name="%s+%s" % (p.name, args.override), **kw)
+        self.p = p
+        self.batch = batch = batch or p.batch
+        self.ctx = ctx = slz.Context(p, batch)
+        if args.generic:
+            ctx.set_option(slz.SLZ_OPT_FORCE_GENERIC, 1)
+        if args.large_n_lanes:
+            ctx.set_option(slz.SLZ_OPT_LARGE_N_LANES, args.large_n_lanes)
+        if args.large_n_block:
+            ctx.set_option(slz.SLZ_OPT_LARGE_N_BLOCK, args.large_n_block)
+        R, C = (p.k + 1) * p.pbs_level, p.k + 1
+        self.bsk = synth.raw_words(p, "raw_bsk", p.n * R * C * p.N).reshape(p.n, p.k + 1, p.pbs_level, C, p.N)
+        self.ksk = synth.raw_words(p, "raw_ksk", p.k * p.N * p.ks_level * (p.n + 1)).reshape(p.k * p.N, p.ks_level, p.n + 1)
+        cts = synth.raw_words(p, "raw_ct", batch * (p.n + 1)).reshape(batch, p.n + 1)
+        self.luts = slz.lut_encode(p, synth.config_tables(cfg))
+        self.lut_idx = synth.config_lut_idx(cfg, batch)
+        d_bsk_std = slz.to_device_u64(self.bsk)
+        self.d_bskp = ctx.bsk_prepare(d_bsk_std)
+        torch.cuda.synchronize()
+        del d_bsk_std
+        self.d_ksk = slz.to_device_u64(self.ksk)
+        self.d_cts = slz.to_device_u64(cts)
+        self.d_luts = slz.to_device_u64(self.luts)
+        self.d_idx = torch.from_numpy(self.lut_idx.astype(np.int32)).cuda()
+        self.d_big = torch.empty((batch, p.k * p.N + 1), dtype=torch.int64, device="cuda")
+        self.d_small = torch.empty((batch, p.n + 1), dtype=torch.int64, device="cuda")
+        # configuration 4 adds the leveled linear part in front: per modulus, 32 x 784 ciphertexts times a clear 784 x 128 matrix
+        self.lin = None
+        if cfg == 4 and batch == p.batch and not args.override:
+            G, J, O = synth.CFG4_BATCH, synth.CFG4_IN, synth.CFG4_OUT
+            _, ws = synth.cfg4_clear_inputs()
+            lin_cts = [slz.to_device_u64(synth.raw_words(p, "lin_mask", G * J * (p.n + 1), r * G * J * (p.n + 1)).reshape(G, J, p.n + 1))
+                       for r in range(3)]
+            lin_w = [torch.from_numpy(ws[r]).cuda() for r in range(3)]
+            self.lin = (lin_cts, lin_w, self.d_cts.view(3, G, O, p.n + 1))
+        torch.cuda.synchronize()
+
+    def lincomb(self):
+        if self.lin is not None:
+            for r in range(3):
+                self.ctx.lwe_lincomb_batch(self.lin[0][r], self.lin[1][r], out=self.lin[2][r])
+
+    def step(self):
+        self.lincomb()
+        self.ctx.pbs_batch(self.d_cts, self.d_luts, self.d_idx, self.d_bskp, out=self.d_big)
+        self.ctx.keyswitch_batch(self.d_big, self.d_ksk, out=self.d_small)
+
+    def run(self, steps, warmup):
+        """W untimed steps, then exactly K timed ones; per-call HIP events on the launch stream give the kernel split."""
+        torch = self.torch
+        for _ in range(warmup):
+            self.step()
+        torch.cuda.synchronize()
+        ev = [[torch.cuda.Event(enable_timing=True) for _ in range(4)] for _ in range(steps)]
+        t0 = time.perf_counter()
+        for k in range(steps):
+            ev[k][0].record()
+            self.lincomb()
+            ev[k][1].record()
+            self.ctx.pbs_batch(self.d_cts, self.d_luts, self.d_idx, self.d_bskp, out=self.d_big)
+            ev[k][2].record()
+            self.ctx.keyswitch_batch(self.d_big, self.d_ksk, out=self.d_small)
+            ev[k][3].record()
+        torch.cuda.synchronize()
+        wall = time.perf_counter() - t0
+        return {"ms_per_step": wall * 1e3 / steps,
+                "pbs_ms": float(np.mean([e[1].elapsed_time(e[2]) for e in ev])),
+                "ks_ms": float(np.mean([e[2].elapsed_time(e[3]) for e in ev])),
+                "lin_ms": float(np.mean([e[0].elapsed_time(e[1]) for e in ev])) if self.lin is not None else None}
+
+    def report(self, t, generic=False):
+        """Rates and roofline fractions of one timed run (`t` from run())."""
+        p, batch, synth = self.p, self.batch, self.synth
+        achieved = alu_model_ops_per_pbs(p) * batch / (t["pbs_ms"] * 1e-3) / 1e12
+        prepared_bytes = self.ctx.bsk_prepared_bytes()
+        r = {"workload": "%s: batch %d, n=%d, k=%d, N=%d, PBS 2^%d x %d, KS 2^%d x %d" % (
+                 p.name, batch, p.n, p.k, p.N, p.pbs_base_log, p.pbs_level, p.ks_base_log, p.ks_level),
+             "path": self.ctx.path,
+             "pbs_plus_keyswitch_per_s": batch / (t["ms_per_step"] * 1e-3),
+             "pbs_per_s": batch / (t["pbs_ms"] * 1e-3), "keyswitch_per_s": batch / (t["ks_ms"] * 1e-3),
+             "ms_per_step": t["ms_per_step"], "pbs_ms": t["pbs_ms"], "keyswitch_ms": t["ks_ms"], "lincomb_ms": t["lin_ms"],
+             "bsk_prepared_bytes": prepared_bytes,
+             "bsk_stream_GBps_min": prepared_bytes / (t["pbs_ms"] * 1e-3) / 1e9,
+             "roofline": {"bound": "alu", "kernel": "blind rotation (slz_pbs_batch)", "achieved": achieved,
+                          "peak": PEAK_ALU_TINSTR, "unit": "Tinstr/s", "frac": achieved / PEAK_ALU_TINSTR,
+                          "traffic": stored_traffic(self.ctx.path, "%s_batch%d" % (p.name, batch))}}
+        # secondary kernels against their own bounds (whole entry point, helper kernels and launch gaps included)
+        kN = p.k * p.N
+        if p.ks_base_log <= 8 and kN % 32 == 0 and not generic and batch >= 16:
+            ks_ops = 2.0 * batch * kN * p.ks_level * (p.n + 1) * 8          # int8 multiply-adds over the eight byte planes, x2
+            ks_pops = ks_ops / (t["ks_ms"] * 1e-3) / 1e15
+            r["keyswitch_roofline"] = {"bound": "mfma", "dtype": "int8", "achieved": ks_pops, "peak": 5.0, "unit": "POP/s",
+                                       "frac": ks_pops / 5.0}
+        else:       # a handful of ciphertexts: the key streams from HBM once
+            ks_bytes = float(kN) * p.ks_level * (p.n + 1) * 8 + batch * (kN + 1 + p.n + 1) * 8.0
+            r["keyswitch_roofline"] = {"bound": "hbm", "achieved": ks_bytes / (t["ks_ms"] * 1e-3) / 1e9, "peak": 8000.0, "unit": "GB/s",
+                                       "frac": ks_bytes / (t["ks_ms"] * 1e-3) / 8e12}
+        if t["lin_ms"] is not None:
+            G, J, O = synth.CFG4_BATCH, synth.CFG4_IN, synth.CFG4_OUT
+            lin_bytes = 3.0 * G * (J + O) * (p.n + 1) * 8             # ciphertext words in, sums out (weights are negligible)
+            r["lincomb_roofline"] = {"bound": "hbm", "achieved": lin_bytes / (t["lin_ms"] * 1e-3) / 1e9, "peak": 8000.0,
+                                     "unit": "GB/s", "frac": lin_bytes / (t["lin_ms"] * 1e-3) / 8e12}
+        return r
+
+    def oracle_sample(self, seconds=20.0):
+        """The CPU oracle on a bounded sample of the same inputs (timed: the baseline), and the GPU's outputs for that
+        sample compared with it bit for bit.  Outputs of the last step() must still be in d_big / d_small."""
+        import oracle
+        slz, p, batch = self.slz, self.p, self.batch
+        threads = oracle.num_threads()
+        macs_per_pbs = p.n * (p.k + 1) ** 2 * p.pbs_level * float(p.N) ** 2
+        info = host_info()
+        if macs_per_pbs > 1e12:
+            return self._oracle_induction(oracle, threads, info)
+        budget_macs = 0.9e9 * seconds * threads                    # about 0.9 GMAC/s per core, schoolbook
+        sample = int(max(1, min(batch, threads * max(1, int(budget_macs / threads / macs_per_pbs)))))
+        idx = np.linspace(0, batch - 1, sample).astype(np.int64)
+        cts_h = slz.to_host_u64(self.d_cts)     # configuration 4: the PBS inputs are the GPU's own linear combinations
+        t1 = time.perf_counter()
+        o_big = oracle.pbs_batch(p, cts_h[idx], self.luts, self.lut_idx[idx], self.bsk)
+        t2 = time.perf_counter()
+        o_small = oracle.keyswitch_batch(p, o_big, self.ksk)
+        t3 = time.perf_counter()
+        g_big = slz.to_host_u64(self.d_big)[idx]
+        g_small = slz.to_host_u64(self.d_small)[idx]
+        used = min(threads, sample)
+        return {"value": sample / (t3 - t1), "unit": "PBS+KS/s", "cores": used, "kind": "oracle",
+                "sample": "%d of the %d ciphertexts (evenly spaced), full PBS + keyswitch each" % (sample, batch),
+                "omp_threads": threads, **info,
+                "pbs_s_per_ct_per_core": (t2 - t1) * used / sample,
+                "keyswitch_s_per_ct_per_core": (t3 - t2) * used / sample,
+                "gpu_bit_exact_on_sample": bool(np.array_equal(g_big, o_big) and np.array_equal(g_small, o_small))}
+
+    def _oracle_induction(self, oracle, threads, info):
+        """Parameter sets where one oracle bootstrapping is hours of schoolbook products: the oracle applies ONE CMux step
+        (the last one) to the GPU's accumulators after n - 1 steps, which must give the GPU's accumulators after n steps
+        word for word; the keyswitch of the sampled outputs is compared in full.  Rate: timed CMux steps x n."""
+        import concurrent.futures
+        slz, p, batch, torch = self.slz, self.p, self.batch, self.torch
+        sample = min(batch, threads)
+        idx = np.linspace(0, batch - 1, sample).astype(np.int64)
+        i = p.n - 1
+        before = slz.to_host_u64(self.ctx.blind_rotate_batch(self.d_cts, self.d_luts, self.d_idx, self.d_bskp, i))[idx]
+        after = slz.to_host_u64(self.ctx.blind_rotate_batch(self.d_cts, self.d_luts, self.d_idx, self.d_bskp, i + 1))[idx]
+        cts_h = slz.to_host_u64(self.d_cts)
+        rot = [oracle.modswitch(int(cts_h[c, i]), p.N) for c in idx]
+        t1 = time.perf_counter()
+        with concurrent.futures.ThreadPoolExecutor(sample) as ex:       # the C oracle runs outside the interpreter lock
+            stepped = list(ex.map(lambda q: oracle.cmux(p, before[q], self.bsk[i], rot[q]), range(sample)))
+        t2 = time.perf_counter()
+        g_big = slz.to_host_u64(self.d_big)[idx]
+        same = all(np.array_equal(stepped[q], after[q]) for q in range(sample))
+        same = same and np.array_equal(g_big, np.stack([oracle.sample_extract(p, a) for a in after]))
+        t3 = time.perf_counter()
+        o_small = oracle.keyswitch_batch(p, g_big, self.ksk)
+        t4 = time.perf_counter()
+        same = same and np.array_equal(slz.to_host_u64(self.d_small)[idx], o_small)
+        pbs_s = (t2 - t1) * p.n                                      # `sample` bootstrappings at this rate, in parallel
+        return {"value": sample / (pbs_s + (t4 - t3)), "unit": "PBS+KS/s", "cores": sample, "kind": "oracle",
+                "sample": "the last of the %d CMux steps on %d of the %d ciphertexts (the oracle continues from the GPU's "
+                          "accumulators after %d steps; rate = timed step x %d), full keyswitch of those outputs" % (
+                              p.n, sample, batch, i, p.n),
+                "omp_threads": threads, **info,
+                "pbs_s_per_ct_per_core": pbs_s, "keyswitch_s_per_ct_per_core": (t4 - t3) * min(threads, sample) / sample,
+                "gpu_bit_exact_on_sample": bool(same)}
+
+
+PER_CONFIG_RUNS = {1: (50, 5), 2: (5, 2), 3: (2, 1), 4: (3, 1)}     # (steps, warm-ups) of the other parameter sets in the default run
+
+
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
     ap.add_argument("--steps", type=int, default=5)
     ap.add_argument("--warmup", type=int, default=1)
-    ap.add_argument("--config", type=int, default=2)
+    ap.add_argument("--config", type=int, default=0,
+                    help="time this configuration only (default: configuration 5 as the headline plus a per_config object "
+                         "with configurations 1 to 4)")
     ap.add_argument("--batch", type=int, default=0, help="override the configuration's batch size")
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--no-per-config", action="store_true", help="default run: skip configurations 1 to 4")
     ap.add_argument("--generic", action="store_true", help="force the generic multi-kernel path")
     ap.add_argument("--override", default="", help="comma-separated parameter overrides of the configuration, e.g. N=4096,pbs_base_log=22,n=256")
     ap.add_argument("--large-n-block", type=int, default=0, help="large-N path: block size of the row pass, 1024 or 2048")
@@ -305,151 +545,48 @@ def main():
         return bench_loss(args)
 
     import torch
-    import synth
-    import paper_2504_17785_amd as slz
-
-    p = synth.CONFIGS[args.config]
-    if args.override:       # another shape with the configuration's tables and message space, e.g. N=4096,pbs_base_log=22,n=256
-        kw = {k.strip(): int(v) for k, v in (item.split("=") for item in args.override.split(","))}
-        p = p.with_(name="%s+%s" % (p.name, args.override), **kw)
-    batch = args.batch or p.batch
     torch.cuda.set_device(0)
-    ctx = slz.Context(p, batch)
-    if args.generic:
-        ctx.set_option(slz.SLZ_OPT_FORCE_GENERIC, 1)
-    if args.large_n_lanes:
-        ctx.set_option(slz.SLZ_OPT_LARGE_N_LANES, args.large_n_lanes)
-    if args.large_n_block:
-        ctx.set_option(slz.SLZ_OPT_LARGE_N_BLOCK, args.large_n_block)
-
-    # ---- synthetic inputs, resident in HBM ----
-    R, C = (p.k + 1) * p.pbs_level, p.k + 1
-    bsk = synth.raw_words(p, "raw_bsk", p.n * R * C * p.N).reshape(p.n, p.k + 1, p.pbs_level, C, p.N)
-    ksk = synth.raw_words(p, "raw_ksk", p.k * p.N * p.ks_level * (p.n + 1)).reshape(p.k * p.N, p.ks_level, p.n + 1)
-    cts = synth.raw_words(p, "raw_ct", batch * (p.n + 1)).reshape(batch, p.n + 1)
-    tables = synth.config_tables(args.config)
-    luts = slz.lut_encode(p, tables)
-    lut_idx = synth.config_lut_idx(args.config, batch)
-    d_bsk_std = slz.to_device_u64(bsk)
-    d_bskp = ctx.bsk_prepare(d_bsk_std)
-    del d_bsk_std
-    d_ksk = slz.to_device_u64(ksk)
-    d_cts = slz.to_device_u64(cts)
-    d_luts = slz.to_device_u64(luts)
-    d_idx = torch.from_numpy(lut_idx.astype(np.int32)).cuda()
-    d_big = torch.empty((batch, p.k * p.N + 1), dtype=torch.int64, device="cuda")
-    d_small = torch.empty((batch, p.n + 1), dtype=torch.int64, device="cuda")
-    torch.cuda.synchronize()
-
-    # configuration 4 adds the leveled linear part in front: per modulus, 32 x 784 ciphertexts times a clear 784 x 128 matrix
-    lin = None
-    if args.config == 4 and not args.batch:
-        G, J, O = synth.CFG4_BATCH, synth.CFG4_IN, synth.CFG4_OUT
-        _, ws = synth.cfg4_clear_inputs()
-        lin_cts = [slz.to_device_u64(synth.raw_words(p, "lin_mask", G * J * (p.n + 1), r * G * J * (p.n + 1)).reshape(G, J, p.n + 1))
-                   for r in range(3)]
-        lin_w = [torch.from_numpy(ws[r]).cuda() for r in range(3)]
-        lin_out = d_cts.view(3, G, O, p.n + 1)
-        lin = (lin_cts, lin_w, lin_out)
-    ev_lin = [torch.cuda.Event(enable_timing=True) for _ in range(args.steps)]
-
-    def lincomb():
-        if lin is not None:
-            for r in range(3):
-                ctx.lwe_lincomb_batch(lin[0][r], lin[1][r], out=lin[2][r])
-
-    def step():
-        lincomb()
-        ctx.pbs_batch(d_cts, d_luts, d_idx, d_bskp, out=d_big)
-        ctx.keyswitch_batch(d_big, d_ksk, out=d_small)
-
-    for _ in range(args.warmup):
-        step()
-    torch.cuda.synchronize()
+    headline = args.config or 5
+    wl = Workload(headline, args, args.batch)
     if args.calib_copy:
         src = torch.ones(256 * 1024 * 1024 // 8, dtype=torch.int64, device="cuda")
         dst = torch.empty_like(src)
         dst.copy_(src)
         torch.cuda.synchronize()
         del src, dst
-
-    # ---- timed region: exactly K steps; per-call HIP events on the launch stream give the kernel split ----
-    ev = [[torch.cuda.Event(enable_timing=True) for _ in range(3)] for _ in range(args.steps)]
-    t0 = time.perf_counter()
-    for k in range(args.steps):
-        ev_lin[k].record()
-        lincomb()
-        ev[k][0].record()
-        ctx.pbs_batch(d_cts, d_luts, d_idx, d_bskp, out=d_big)
-        ev[k][1].record()
-        ctx.keyswitch_batch(d_big, d_ksk, out=d_small)
-        ev[k][2].record()
-    torch.cuda.synchronize()
-    wall = time.perf_counter() - t0
-    pbs_ms = float(np.mean([e[0].elapsed_time(e[1]) for e in ev]))
-    ks_ms = float(np.mean([e[1].elapsed_time(e[2]) for e in ev]))
-    lin_ms = float(np.mean([ev_lin[k].elapsed_time(ev[k][0]) for k in range(args.steps)])) if lin is not None else None
-    ms_per_step = wall * 1e3 / args.steps
-
-    # HBM bytes per launch of the dominant kernel from the rocprofv3 FETCH_SIZE / WRITE_SIZE passes kept under
-    # profiles/ (scaled by the copy-kernel calibration); only known for the workload those passes were run on
-    traffic = 2.0 * 1511371 * 1024 + 34849 * 1024 if (args.config == 2 and batch == 1024 and ctx.path == "fused_n2048") else None
-    model_ops = alu_model_ops_per_pbs(p) * batch
-    achieved = model_ops / (pbs_ms * 1e-3) / 1e12
-    prepared_bytes = ctx.bsk_prepared_bytes()
+    t = wl.run(args.steps, args.warmup)
+    rep = wl.report(t, args.generic)
     result = {
-        "metric": "pbs_plus_keyswitch_per_s",
-        "value": batch / (ms_per_step * 1e-3),
-        "unit": "PBS+KS/s",
-        "n_gpus": 1, "steps": args.steps, "warmup": args.warmup, "ms_per_step": ms_per_step,
+        "metric": "pbs_plus_keyswitch_per_s", "value": rep["pbs_plus_keyswitch_per_s"], "unit": "PBS+KS/s",
+        "n_gpus": 1, "steps": args.steps, "warmup": args.warmup, "ms_per_step": t["ms_per_step"],
         "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
         "dtype": "u64", "data": "synthetic",
-        "config": {"workload": "%s: batch %d, n=%d, k=%d, N=%d, PBS 2^%d x %d, KS 2^%d x %d" % (
-            p.name, batch, p.n, p.k, p.N, p.pbs_base_log, p.pbs_level, p.ks_base_log, p.ks_level),
-            "path": ctx.path},
-        "pbs_per_s": batch / (pbs_ms * 1e-3), "keyswitch_per_s": batch / (ks_ms * 1e-3),
-        "pbs_ms": pbs_ms, "keyswitch_ms": ks_ms, "lincomb_ms": lin_ms,
-        "bsk_prepared_bytes": prepared_bytes,
-        "bsk_stream_GBps_min": prepared_bytes / (pbs_ms * 1e-3) / 1e9,
-        "roofline": {"bound": "alu", "kernel": "blind rotation (slz_pbs_batch)", "achieved": achieved,
-                     "peak": PEAK_ALU_TINSTR, "unit": "Tinstr/s", "frac": achieved / PEAK_ALU_TINSTR, "traffic": traffic},
+        "config": {"workload": rep["workload"], "path": rep["path"]},
     }
-    # secondary kernels against their own bounds (whole entry point, helper kernels and launch gaps included)
-    kN = p.k * p.N
-    if p.ks_base_log <= 8 and kN % 32 == 0 and not args.generic:
-        ks_ops = 2.0 * batch * kN * p.ks_level * (p.n + 1) * 8          # int8 multiply-adds over the eight byte planes, x2
-        ks_pops = ks_ops / (ks_ms * 1e-3) / 1e15
-        result["keyswitch_roofline"] = {"bound": "mfma", "dtype": "int8", "achieved": ks_pops, "peak": 5.0, "unit": "POP/s",
-                                        "frac": ks_pops / 5.0}
-    if lin_ms is not None:
-        G, J, O = synth.CFG4_BATCH, synth.CFG4_IN, synth.CFG4_OUT
-        lin_bytes = 3.0 * G * (J + O) * (p.n + 1) * 8             # ciphertext words in, sums out (weights are negligible)
-        result["lincomb_roofline"] = {"bound": "hbm", "achieved": lin_bytes / (lin_ms * 1e-3) / 1e9, "peak": 8000.0,
-                                      "unit": "GB/s", "frac": lin_bytes / (lin_ms * 1e-3) / 8e12}
-
-    # ---- CPU baseline: the oracle on a bounded sample of the same inputs (also a parity check) ----
+    for key in ("pbs_per_s", "keyswitch_per_s", "pbs_ms", "keyswitch_ms", "lincomb_ms", "bsk_prepared_bytes", "bsk_stream_GBps_min",
+                "roofline", "keyswitch_roofline", "lincomb_roofline"):
+        if key in rep:
+            result[key] = rep[key]
     if not args.no_cpu_baseline:
-        import oracle
-        threads = oracle.num_threads()
-        budget_macs = 2.5e9 * 20.0 * threads * 0.35            # about 20 s at ~0.9 GMAC/s/core schoolbook
-        macs_per_pbs = p.n * (p.k + 1) ** 2 * p.pbs_level * float(p.N) ** 2
-        sample = int(max(1, min(batch, threads * max(1, int(budget_macs / threads / macs_per_pbs)))))
-        idx = np.linspace(0, batch - 1, sample).astype(np.int64)
-        t1 = time.perf_counter()
-        cts_h = slz.to_host_u64(d_cts)          # configuration 4: the PBS inputs are the GPU's own linear combinations
-        o_big = oracle.pbs_batch(p, cts_h[idx], luts, lut_idx[idx], bsk)
-        t2 = time.perf_counter()
-        o_small = oracle.keyswitch_batch(p, o_big, ksk)
-        t3 = time.perf_counter()
-        g_big = slz.to_host_u64(d_big)[idx]
-        g_small = slz.to_host_u64(d_small)[idx]
-        result["cpu_baseline"] = {
-            "value": sample / (t3 - t1), "unit": "PBS+KS/s", "cores": min(threads, sample), "kind": "oracle",
-            "sample": "%d of the %d ciphertexts (evenly spaced), full PBS + keyswitch each" % (sample, batch),
-            "pbs_s_per_ct_per_core": (t2 - t1) * min(threads, sample) / sample,
-            "keyswitch_s_per_ct_per_core": (t3 - t2) * min(threads, sample) / sample,
-            "gpu_bit_exact_on_sample": bool(np.array_equal(g_big, o_big) and np.array_equal(g_small, o_small)),
-        }
+        result["cpu_baseline"] = wl.oracle_sample(30.0)
+    del wl
+    torch.cuda.empty_cache()
+
+    # ---- the other parameter sets, each with its own short run and its own oracle sample -------------------------------
+    if not args.config and not args.no_per_config and not args.batch and not args.override:
+        per = {}
+        for cfg, (steps, warmup) in PER_CONFIG_RUNS.items():
+            w = Workload(cfg, args)
+            tt = w.run(steps, warmup)
+            e = w.report(tt, args.generic)
+            e["steps"], e["warmup"] = steps, warmup
+            if not args.no_cpu_baseline:
+                e["cpu_baseline"] = w.oracle_sample(6.0)
+                e["gpu_bit_exact_on_sample"] = e["cpu_baseline"]["gpu_bit_exact_on_sample"]
+            per["cfg%d" % cfg] = e
+            del w
+            torch.cuda.empty_cache()
+        result["per_config"] = per
     print(json.dumps(result))
 
 
