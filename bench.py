@@ -205,6 +205,7 @@ def bench_loss(args):
     """--gadget loss_deriv: one step = IntCELossDeriv of a batch of 8 samples with 3 classes (Gamma = 7, kappa = 2, the largest
     level whose packed lookup fits 8 bits): 5 lookups per entry in 5 dependent rounds.  --gadget weight_update: one step = the
     clipped update of the 28 x 8 + 8 x 2 = 240 weights of the paper's largest network (alpha = 6), one lookup per weight.
+    --gadget-params wide: the paper's own kappa = 4 and alpha = 8 on an 11-bit message space (N = 65536).
     Key and ciphertext material is uniform random words."""
     import torch
     import synth
@@ -212,12 +213,17 @@ def bench_loss(args):
 
     if args.gadget_params == "cfg3":
         p, max_batch = synth.CONFIGS[3], 256
+    elif args.gadget_params == "wide":
+        # the shape of a parameter set for 11-bit lookups (the paper's kappa = 4 and alpha = 8): configuration 3 with twice
+        # the polynomial size, the largest the large-N path takes
+        p, max_batch = synth.CONFIGS[3].with_(name="wide_n1024_N65536", N=65536, msg_bits=11), 128
     else:
         p = synth.Params(name="gadget_toy", n=4, k=1, N=2048, pbs_base_log=23, pbs_level=1, ks_base_log=4, ks_level=8,
                          msg_bits=8, sigma_lwe=2.0 ** -40, sigma_bsk=2.0 ** -50, batch=1, n_luts=1, seed=0x6AD6E7)
         max_batch = 8192
     loss = args.gadget == "loss_deriv"
-    a, b, Gamma, kappa, alpha = 8, 3, 7, 2, 6
+    wide = args.gadget_params == "wide"
+    a, b, Gamma, kappa, alpha = 8, 3, 7, (4 if wide else 2), (8 if wide else 6)
     count = a * b if loss else (args.batch or 240)
     lookups, rounds = (5 * count, 5) if loss else (count, 1)
     torch.cuda.set_device(0)
@@ -531,8 +537,9 @@ def main():
                     help="also run one plain device copy of 256 MiB (a known-size kernel to scale FETCH_SIZE/WRITE_SIZE by)")
     ap.add_argument("--gadget", choices=["matmul_rns", "matmul_highres", "sign_rns", "shift2msbs", "loss_deriv", "weight_update"], default=None,
                     help="time a gadget built on the lookup primitive instead of the PBS + keyswitch step")
-    ap.add_argument("--gadget-params", choices=["cfg3", "toy"], default="cfg3",
-                    help="matmul_rns: the 8-bit parameter set of configuration 3, or the toy set the oracle can follow")
+    ap.add_argument("--gadget-params", choices=["cfg3", "toy", "wide"], default="cfg3",
+                    help="the 8-bit parameter set of configuration 3, the toy set the oracle can follow, or (loss_deriv and "
+                         "weight_update only) an 11-bit set of twice configuration 3's polynomial size")
     args = ap.parse_args()
     if args.gpus != 1:
         print("bench.py measures one GPU only (this build has no multi-GPU path); run with --gpus 1", file=sys.stderr)

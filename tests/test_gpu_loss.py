@@ -1,6 +1,7 @@
 """GPU parity of the two-input lookup, IntCELossDeriv and the clipped weight update: the library against the oracle's
 encrypted pipelines, bit for bit, and decryption against the clear-integer clones.  Toy (insecure) parameters with an 8-bit
-message space keep the oracle's lookups at 7e7 multiply-adds each."""
+message space keep the oracle's lookups at 7e7 multiply-adds each; the paper's own settings (kappa = 4, alpha = 8) run on toy
+sets with 11- and 10-bit message spaces."""
 import ctypes
 
 import numpy as np
@@ -88,6 +89,70 @@ def test_weight_update_matches_oracle_and_decrypts(slz, orc, toy, alpha, count, 
     assert np.array_equal(got, want)
     dec, _ = orc.decode(orc.lwe_phase(keys.lwe_sk, got), p.msg_bits)
     assert np.array_equal(gd.signed_decode(dec.astype(np.int64), 256), np.clip(W - G, -half, half - 1))
+
+
+# ---- the paper's own settings (Sec. "Evaluation"): kappa = 4 and weights clipped to the signed 8-bit range -----------------
+# 11- and 10-bit lookups: the same entry points on parameter sets with a wider message space (toy sizes for the oracle's sake).
+@pytest.fixture(scope="module")
+def wide11(orc):
+    p = Params(name="wide11", n=2, k=1, N=8192, pbs_base_log=15, pbs_level=2, ks_base_log=4, ks_level=8, msg_bits=11,
+               sigma_lwe=2.0 ** -40, sigma_bsk=2.0 ** -50, batch=1, n_luts=1, seed=0x11B17)
+    return p, orc.Keys(p, synth)
+
+
+@pytest.fixture(scope="module")
+def wide10(orc):
+    p = Params(name="wide10", n=2, k=1, N=4096, pbs_base_log=22, pbs_level=1, ks_base_log=4, ks_level=8, msg_bits=10,
+               sigma_lwe=2.0 ** -40, sigma_bsk=2.0 ** -50, batch=1, n_luts=1, seed=0x10B17)
+    return p, orc.Keys(p, synth)
+
+
+@pytest.mark.parametrize("a,b,max_batch", [(4, 3, 64), (3, 2, 4)])
+def test_int_ce_loss_deriv_at_kappa_4(slz, orc, wide11, a, b, max_batch):
+    from oracle import gadgets as gd
+    from oracle import loss
+    p, keys = wide11
+    Gamma, kappa = 7, 4
+    Yhat, Y = _logits(p, a, b, offset=100 * a + b)
+    Yhat[0] = [63, 62, 61][:b]                           # a row whose exponentials are 16, 6, 2
+    Yhat.flat[-1] = -64
+    yh = _enc(orc, p, keys, Yhat, 0).reshape(a, b, p.n + 1)
+    yl = _enc(orc, p, keys, Y, a * b).reshape(a, b, p.n + 1)
+    ctx = slz.Context(p, max_batch)
+    assert ctx.path == "three_pass_large_n"
+    d_bsk = ctx.bsk_prepare(slz.to_device_u64(keys.bsk))
+    d_luts = slz.to_device_u64(slz.loss_luts(p, b, Gamma, kappa))
+    assert np.array_equal(slz.loss_luts(p, b, Gamma, kappa), orc.lut_encode(p, loss.loss_tables(p, b, Gamma, kappa)))
+    got = slz.to_host_u64(ctx.int_ce_loss_deriv(slz.to_device_u64(yh), slz.to_device_u64(yl), Gamma, kappa, d_luts, d_bsk,
+                                                slz.to_device_u64(keys.ksk)))
+    want = loss.int_ce_loss_deriv_encrypted(p, yh, yl, Gamma, kappa, keys.bsk, keys.ksk)
+    assert np.array_equal(got, want)
+    dec, _ = orc.decode(orc.lwe_phase(keys.lwe_sk, got.reshape(-1, p.n + 1)), p.msg_bits)
+    assert np.array_equal(gd.signed_decode(dec.astype(np.int64), 1 << p.msg_bits).reshape(a, b),
+                          loss.int_ce_loss_deriv_clear(Yhat, Y, Gamma, kappa))
+
+
+@pytest.mark.parametrize("count,max_batch", [(40, 64), (9, 4)])
+def test_weight_update_at_alpha_8(slz, orc, wide10, count, max_batch):
+    from oracle import gadgets as gd
+    from oracle import loss
+    p, keys = wide10
+    alpha = 8
+    W = synth.uniform_below(p.seed, "weights", count, 256, alpha).astype(np.int64) - 128
+    G = synth.uniform_below(p.seed, "lut_idx", count, 3, alpha).astype(np.int64) - 1
+    W[:4] = [-128, -128, 127, 127]
+    G[:4] = [1, -1, -1, 1]                               # both clipped ends and their free neighbours
+    wc, gc = _enc(orc, p, keys, W, 0), _enc(orc, p, keys, G + 1, count)
+    ctx = slz.Context(p, max_batch)
+    assert ctx.path == "fused_n4096"
+    d_bsk = ctx.bsk_prepare(slz.to_device_u64(keys.bsk))
+    assert np.array_equal(slz.weight_update_luts(p, alpha), orc.lut_encode(p, loss.weight_update_table(p, alpha)))
+    d_luts = slz.to_device_u64(slz.weight_update_luts(p, alpha))
+    got = slz.to_host_u64(ctx.weight_update(slz.to_device_u64(wc), slz.to_device_u64(gc), alpha, d_luts, d_bsk, slz.to_device_u64(keys.ksk)))
+    want = loss.weight_update_encrypted(p, wc, gc, alpha, keys.bsk, keys.ksk)
+    assert np.array_equal(got, want)
+    dec, _ = orc.decode(orc.lwe_phase(keys.lwe_sk, got), p.msg_bits)
+    assert np.array_equal(gd.signed_decode(dec.astype(np.int64), 1024), np.clip(W - G, -128, 127))
 
 
 def test_bivariate_lookup_matches_oracle_with_several_tables(slz, orc, toy):

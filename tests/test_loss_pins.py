@@ -164,3 +164,102 @@ def test_encrypted_loss_derivative_and_weight_update_decrypt_to_the_clear_clones
     out = ls.bivariate_lookup_encrypted(p, enc(x, 300), enc(y, 400), 4, tab, np.zeros(5, dtype=np.uint32), keys.bsk, keys.ksk)
     got, _ = orc.decode(orc.lwe_phase(keys.lwe_sk, out), p.msg_bits)
     assert got.astype(np.int64).tolist() == np.maximum(x, y).tolist()
+
+
+# ---- the paper's own settings: kappa = 4 and alpha = 8 (Sec. "Evaluation") ----------------------------------------------
+# They need lookups on 11 and 10 bits: the same algorithms in a wider message space (one padding bit above it), which the
+# polynomial size must carry (N >= 2 t, and boxes wide enough for the modulus-switch drift).  Toy sets (insecure on purpose,
+# so that an oracle lookup stays near 1e9 multiply-adds): the drift of the rotation is sqrt((1 + n/2) / 12) = 0.41 positions
+# at n = 2 against half-boxes of 2 positions.
+WIDE11 = dict(n=2, k=1, N=8192, pbs_base_log=15, pbs_level=2, ks_base_log=4, ks_level=8, msg_bits=11,
+              sigma_lwe=2.0 ** -40, sigma_bsk=2.0 ** -50, batch=1, n_luts=1)
+WIDE10 = dict(n=2, k=1, N=4096, pbs_base_log=22, pbs_level=1, ks_base_log=4, ks_level=8, msg_bits=10,
+              sigma_lwe=2.0 ** -40, sigma_bsk=2.0 ** -50, batch=1, n_luts=1)
+
+
+def _through_tables(ls, p, Yhat, Y, Gamma, kappa):
+    """IntCELossDeriv evaluated through the five lookup tables and the packed indices of the encrypted pipeline, on clear
+    integers modulo 2t (what the ciphertexts carry when nothing goes wrong)."""
+    t = 1 << p.msg_bits
+    a, b = Yhat.shape
+    relu, ex, share, prod, sgn = [x.astype(np.int64) for x in ls.loss_tables(p, b, Gamma, kappa)]
+    _, sb = ls.loss_widths(b, kappa)
+    E = ex[relu[np.mod(Yhat, t)]]
+    S = E.sum(axis=1, keepdims=True)
+    Q = share[(E << sb) + S]
+    T = Q.sum(axis=1, keepdims=True)
+    P = prod[(Y << sb) + T]
+    return sgn[Q - P + t // 2]
+
+
+def test_loss_tables_at_kappa_4_on_an_11_bit_message_space(ls):
+    from oracle import gadgets as gd
+    p = Params(name="wide11", seed=3, **WIDE11)
+    b, Gamma, kappa = 3, 7, 4
+    eb, sb = ls.loss_widths(b, kappa)
+    assert (eb, sb) == (5, 6) and eb + sb == p.msg_bits             # exponentials 0..16, row sums 0..48
+    relu, ex, share, prod, sgn = [x.astype(np.int64) for x in ls.loss_tables(p, b, Gamma, kappa)]
+    assert [int(ex[v]) for v in (63, 62, 61, 60, 59, 0)] == [16, 6, 2, 1, 0, 0] and int(ex[64]) == 0
+    for e in range(17):
+        for s in range(49):
+            assert share[(e << sb) + s] == round(Fraction(16 * e + 1, s + 1))
+    assert share[(16 << sb) + 16] == 15 and share[(6 << sb) + 24] == 4 and share[0] == 1        # the hand-worked rows' shares
+    for s in range(49):
+        assert prod[s] == 0 and prod[64 + s] == s
+    assert sgn[1024] == 0 and sgn[1025] == 1 and sgn[1023] == 2047 and relu[1023] == 1023 and relu[1024] == 0
+    # the rows worked out by hand above, through the tables and packed indices
+    Yhat = np.array([[63, 10, -64], [63, 10, -64], [-5, 0, 12], [63, 62, 61]])
+    Y = np.array([[1, 0, 0], [0, 1, 0], [0, 0, 1], [0, 1, 0]])
+    got = gd.signed_decode(_through_tables(ls, p, Yhat, Y, Gamma, kappa), 2048)
+    assert got.tolist() == [[0, 0, 0], [1, -1, 0], [1, 1, -1], [1, -1, 1]]
+    # and on random rows against the clone
+    rng = np.random.default_rng(404)
+    Yhat = rng.integers(54, 64, size=(300, 3))
+    Yhat[::5] = rng.integers(-64, 64, size=Yhat[::5].shape)
+    Y = np.eye(3, dtype=np.int64)[rng.integers(0, 3, size=300)]
+    assert np.array_equal(gd.signed_decode(_through_tables(ls, p, Yhat, Y, Gamma, kappa), 2048), ls.int_ce_loss_deriv_clear(Yhat, Y, Gamma, kappa))
+
+
+def test_weight_update_brute_force_at_alpha_8(ls):
+    # clip(w - g) to [-128, 127] over every signed 8-bit weight and every g, through the table on 4 (w + 128) + g + 1
+    p = Params(name="wide10", seed=3, **WIDE10)
+    t = ls.weight_update_table(p, 8)[0].astype(np.int64)
+    assert t.shape == (1024,)
+    seen = 0
+    for w in range(-128, 128):
+        for g in (-1, 0, 1):
+            want = max(-128, min(127, w - g))
+            assert int(ls.weight_update_clear(w, g, 8)) == want
+            assert t[4 * (w + 128) + g + 1] == want % 1024
+            seen += 1
+    assert seen == 768
+    assert t[4 * 0 + 2] == (-128) % 1024 and t[4 * 255 + 0] == 127                              # the two clipped corners
+    with pytest.raises(ValueError):
+        ls.weight_update_table(Params(name="toy", seed=1, **TOY), 8)                            # 10 bits do not fit 8
+
+
+def test_encrypted_pipelines_decrypt_at_kappa_4_and_alpha_8(orc, ls):
+    from oracle import gadgets as gd
+    p = Params(name="wide11", seed=0x11B17, **WIDE11)
+    keys = orc.Keys(p, synth)
+    t = 1 << p.msg_bits
+    enc = lambda q, k, vals, off: orc.encrypt_messages(q, synth, k.lwe_sk, gd.signed_encode(vals, 1 << q.msg_bits).reshape(-1).astype(np.uint64),
+                                                       offset=off)
+    Yhat = np.array([[63, 62, 61], [63, 10, -64], [-5, 0, 12]])
+    Y = np.eye(3, dtype=np.int64)[[1, 1, 2]]
+    a, b = Yhat.shape
+    yh = enc(p, keys, Yhat, 0).reshape(a, b, p.n + 1)
+    yl = enc(p, keys, Y, a * b).reshape(a, b, p.n + 1)
+    out = ls.int_ce_loss_deriv_encrypted(p, yh, yl, 7, 4, keys.bsk, keys.ksk)
+    got, err = orc.decode(orc.lwe_phase(keys.lwe_sk, out.reshape(-1, p.n + 1)), p.msg_bits)
+    assert gd.signed_decode(got.astype(np.int64), t).reshape(a, b).tolist() == [[1, -1, 1], [1, -1, 0], [1, 1, -1]]
+    assert float(np.abs(err).max()) < 2.0 ** -15                    # against Delta / 2 = 2^-13
+
+    p10 = Params(name="wide10", seed=0x10B17, **WIDE10)
+    k10 = orc.Keys(p10, synth)
+    W = np.array([-128, -128, -127, 0, 5, 127, 127, 126, -1, 64])
+    G = np.array([1, -1, 1, 0, -1, -1, 1, -1, 1, 0])
+    upd = ls.weight_update_encrypted(p10, enc(p10, k10, W, 100), enc(p10, k10, G + 1, 200), 8, k10.bsk, k10.ksk)
+    got, err = orc.decode(orc.lwe_phase(k10.lwe_sk, upd), p10.msg_bits)
+    assert gd.signed_decode(got.astype(np.int64), 1024).tolist() == [-128, -127, -128, 0, 6, 127, 126, 127, -2, 64]
+    assert float(np.abs(err).max()) < 2.0 ** -14
