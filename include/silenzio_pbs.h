@@ -79,6 +79,12 @@ typedef struct slz_ctx slz_ctx;   /* opaque: parameter copy, twiddle tables, scr
                                      overlaps the memory-bound column passes of the other; results are identical);
                                      SLZ_E_INVALID_ARG when the context has no large-N path */
 
+#define SLZ_OPT_LARGE_N_LATENCY 5 /* value 1 (default) or 0: on the large-N path with 1024-blocks, calls with so few ciphertexts that
+                                     the chip stays mostly empty (at most 512 / (2 N / 1024): 8 at N = 32768) run every CMux step
+                                     as four shorter launches with four times the threads (lower latency, identical results; their
+                                     scratch of 2 (k+1) l (k+1) N doubles per such ciphertext is allocated by the first such call);
+                                     0 keeps the throughput kernels at every batch size; SLZ_E_INVALID_ARG without a large-N path */
+
 #define SLZ_OPT_FAIL_ALLOC_AFTER 4 /* for tests of the out-of-memory handling: value v >= 0 makes the (v+1)-th scratch allocation
                                      from now (of any context of the process) return SLZ_E_NOMEM without touching the device,
                                      once; v < 0 disarms */

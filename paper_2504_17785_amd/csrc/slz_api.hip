@@ -116,6 +116,11 @@ extern "C" int slz_ctx_set_option(slz_ctx *ctx, int option, int value) {
         if (value == 2048 && ctx->bign_rowA) { ctx->bign_block = 2048; return SLZ_OK; }
         return SLZ_E_INVALID_ARG;
     }
+    if (option == SLZ_OPT_LARGE_N_LATENCY) {
+        if (!ctx->has_bign || (value != 0 && value != 1)) return SLZ_E_INVALID_ARG;
+        ctx->bign_latency = value;
+        return SLZ_OK;
+    }
     if (option == SLZ_OPT_LARGE_N_LANES) {
         if (!ctx->has_bign || (value != 1 && value != 2)) return SLZ_E_INVALID_ARG;
         ctx->bign_lanes = value;

@@ -38,11 +38,16 @@ struct bign_args {
 
 // ---- P1 ------------------------------------------------------------------------------------------
 // BS: block size of the row pass (2048 or 1024); G = N / BS rows of BS columns
-template <int G, int BS>
+// SPLIT: one thread per (column, component, level, prime) instead of one per (column, component): four times (l = 2) as
+// many threads, each repeating the cheap rotate / subtract / round and doing one column transform.  For a handful of
+// ciphertexts, where the pass is one thread's latency.
+template <int G, int BS, bool SPLIT>
 __global__ void __launch_bounds__(256)
 k_big_cols_fwd(bign_args A) {
     const uint32_t c = blockIdx.x * 256 + threadIdx.x;          // column, < BS
-    const uint32_t comp = blockIdx.y, b = blockIdx.z;
+    const uint32_t b = blockIdx.z;
+    const uint32_t comp = SPLIT ? blockIdx.y / (2 * A.l) : blockIdx.y;
+    const int only_lev = SPLIT ? (int)((blockIdx.y >> 1) % A.l) : -1, only_q = SPLIT ? (int)(blockIdx.y & 1u) : -1;
     const uint32_t N = A.N, R = 2 * A.l;
     uint32_t logN2 = 1;                                          // log2(2N)
     for (uint32_t g = N; g > 1; g >>= 1) logN2++;
@@ -59,7 +64,9 @@ k_big_cols_fwd(bign_args A) {
         double d[G];
 #pragma unroll
         for (int i = 0; i < G; i++) d[i] = (double)slz_next_digit(lam[i], A.beta);
+        if (SPLIT && lev != only_lev) continue;                  // lower levels are only peeled for their carries
         for (int q = 0; q < 2; q++) {
+            if (SPLIT && q != only_q) continue;
             const slz_mod m = A.mod[q];
             const double *tw = A.tab[q].fwd;
             double y[G];
@@ -79,6 +86,7 @@ k_big_cols_fwd(bign_args A) {
 #pragma unroll
             for (int i = 0; i < G; i++) dst[(uint32_t)BS * i] = slz_reduce(y[i], m);
         }
+        if (SPLIT) break;
     }
 }
 
@@ -330,6 +338,152 @@ k_big_cols_inv(bign_args A) {
     for (int i = 0; i < G; i++) poly[(uint32_t)BS * i] += slz_crt64(res[0][i], res[1][i], A.mod[1], A.p1inv_mod_p2);
 }
 
+// ---- a handful of ciphertexts: the same step cut into more, shorter pieces --------------------------------------------
+// With few ciphertexts the chip is mostly empty and a step costs the latency of its longest thread: one row task runs R
+// forward transforms, the products and two inverse transforms one after the other.  Here a row task is one GGSW row
+// (k_big_rows16_lat_a: forward transform, products with both key columns, written to P) or one output component
+// (k_big_rows16_lat_b: sum of the R partial products, inverse transform), and the inverse column pass runs the two primes
+// of a column on two neighbouring lanes.  More launches and more traffic per step, several times the parallelism.
+// P: [batch][2 primes][R][2 components][N], a row-block stored as [16 registers][64 lanes].
+__global__ void __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(2, 2)))
+k_big_rows16_lat_a(bign_args A, double *__restrict__ P, uint32_t G, uint32_t n_tasks) {
+    extern __shared__ double lds[];
+    const uint32_t lane = threadIdx.x & 63u;
+    const uint32_t wv = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
+    const uint32_t task = blockIdx.x * 4 + wv;
+    if (task >= n_tasks) return;                                 // whole wave leaves; no workgroup barriers below
+    double *T = lds + wv * (TBUF16 + 1024u);
+    double *twA = T + TBUF16, *twB = twA + 64;
+    const uint32_t N = A.N, R = 2 * A.l;
+    const uint32_t r = task % R, row = (task / R) % G, q = (task / (R * G)) & 1u, b = task / (2 * R * G);
+    const slz_mod m = A.mod[q];
+    const bign_tabs tb = A.tab[q];
+    const uint32_t stride = N / 32;
+    const uint32_t key_lane_off = (16u * (lane & 1u) * stride + (lane >> 1)) * 8u;
+    int z;
+    asm volatile("s_mov_b32 %0, 0" : "=s"(z));
+    double x[16], kk0[16], kk1[16];
+    {
+        const double *src = A.X + (((size_t)b * 2 + q) * R + r) * N + 1024u * row;
+#pragma unroll
+        for (int e = 0; e < 16; e++) x[e] = ldl(src + 64 * e, lane * 8u);
+        const double *gA = tb.rowA + (size_t)row * 64, *gB = tb.rowB + (size_t)row * 15 * 64;
+        twA[lane] = gA[lane];
+#pragma unroll
+        for (int k = 0; k < 15; k++) twB[64 * k + lane] = gB[64 * k + lane];
+        const double *k0 = A.bskp_step + (((size_t)q * R + r) * 2 + 0) * N + 32u * row;
+        const double *k1 = k0 + N;
+#pragma unroll
+        for (int i = 0; i < 16; i++) { kk0[i] = ldl(k0 + (size_t)i * stride, key_lane_off); kk1[i] = ldl(k1 + (size_t)i * stride, key_lane_off); }
+        wave_sync();
+    }
+    SCHED_FENCE();
+    fwd16(x, T, twA, twB, m, lane, z);
+    double *dst = P + ((((size_t)b * 2 + q) * R + r) * 2) * N + 1024u * row + lane;
+#pragma unroll
+    for (int g = 0; g < 4; g++) {
+        double r0[4], r1[4];
+        const double x4[4] = {x[4 * g], x[4 * g + 1], x[4 * g + 2], x[4 * g + 3]};
+        const double ka[4] = {kk0[4 * g], kk0[4 * g + 1], kk0[4 * g + 2], kk0[4 * g + 3]};
+        const double kb[4] = {kk1[4 * g], kk1[4 * g + 1], kk1[4 * g + 2], kk1[4 * g + 3]};
+        mulmod_k<4>(r0, x4, ka, m);
+        mulmod_k<4>(r1, x4, kb, m);
+#pragma unroll
+        for (int u = 0; u < 4; u++) {
+            dst[64 * (4 * g + u)] = r0[u];
+            dst[(size_t)N + 64 * (4 * g + u)] = r1[u];
+        }
+    }
+}
+
+__global__ void __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(2, 2)))
+k_big_rows16_lat_b(bign_args A, const double *__restrict__ P, uint32_t G, uint32_t n_tasks) {
+    extern __shared__ double lds[];
+    const uint32_t lane = threadIdx.x & 63u;
+    const uint32_t wv = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
+    const uint32_t task = blockIdx.x * 4 + wv;
+    if (task >= n_tasks) return;
+    double *T = lds + wv * TBUF16;
+    const uint32_t N = A.N, R = 2 * A.l;
+    const uint32_t comp = task & 1u, row = (task >> 1) % G, q = (task / (2 * G)) & 1u, b = task / (4 * G);
+    const slz_mod m = A.mod[q];
+    const bign_tabs tb = A.tab[q];
+    int z;
+    asm volatile("s_mov_b32 %0, 0" : "=s"(z));
+    double x[16];
+    {
+        const double *src = P + ((((size_t)b * 2 + q) * R) * 2 + comp) * N + 1024u * row + lane;
+#pragma unroll
+        for (int i = 0; i < 16; i++) x[i] = src[64 * i];
+        for (uint32_t r = 1; r < R; r++) {
+            const double *sr = src + (size_t)r * 2 * N;
+#pragma unroll
+            for (int i = 0; i < 16; i++) x[i] += sr[64 * i];
+            if ((r & 3u) == 3u && r + 1 < R) {                   // as in the throughput kernel: at most four products per reduction
+#pragma unroll
+                for (int i = 0; i < 16; i++) x[i] = slz_reduce(x[i], m);
+            }
+        }
+    }
+#pragma unroll
+    for (int g = 0; g < 2; g++) {
+        double r8[8], x8[8];
+#pragma unroll
+        for (int u = 0; u < 8; u++) x8[u] = x[8 * g + u];
+        reduce_k<8>(r8, x8, m);
+#pragma unroll
+        for (int u = 0; u < 8; u++) x[8 * g + u] = r8[u];
+    }
+    inv16(x, T, tb.inv, tb.inv, m, lane, z);
+    double *dst = A.Y + (((size_t)b * 2 + q) * 2 + comp) * N + 1024u * row;
+#pragma unroll
+    for (int g = 0; g < 2; g++) {
+        double r8[8], x8[8];
+#pragma unroll
+        for (int u = 0; u < 8; u++) x8[u] = x[8 * g + u];
+        reduce_k<8>(r8, x8, m);
+#pragma unroll
+        for (int u = 0; u < 8; u++) dst[64 * (8 * g + u) + lane] = r8[u];
+    }
+}
+
+// P3 with the two primes of a column on lanes 2j and 2j + 1: each lane runs its prime's column stages and twist, the
+// lanes swap the halves they do not lift (rows below G/2 are lifted by the lane of prime 0, the others by prime 1's).
+template <int G, int BS>
+__global__ void __launch_bounds__(256)
+k_big_cols_inv_lat(bign_args A) {
+    const uint32_t c = blockIdx.x * 128 + (threadIdx.x >> 1);
+    const uint32_t q = threadIdx.x & 1u;
+    const uint32_t comp = blockIdx.y, b = blockIdx.z;
+    const uint32_t N = A.N;
+    const slz_mod m = A.mod[q];
+    const double *src = A.Y + (((size_t)b * 2 + q) * 2 + comp) * N + c;
+    const double *tw = A.tab[q].inv, *post = A.tab[q].post;
+    double y[G];
+#pragma unroll
+    for (int i = 0; i < G; i++) y[i] = src[(uint32_t)BS * i];
+#pragma unroll
+    for (int half = 1; half < G; half <<= 1) {
+#pragma unroll
+        for (int j = 0; j < half; j++) {
+            const double w = tw[(uint32_t)BS * half + (uint32_t)BS * j + c];
+#pragma unroll
+            for (int blk = 0; blk < G / (2 * half); blk++) bfly(y[blk * 2 * half + j], y[blk * 2 * half + j + half], w, m);
+        }
+    }
+#pragma unroll
+    for (int i = 0; i < G; i++) y[i] = slz_mulmod(y[i], post[(uint32_t)BS * i + c], m);
+    uint64_t *poly = A.acc + ((size_t)b * 2 + comp) * N + c;
+#pragma unroll
+    for (int j = 0; j < G / 2; j++) {
+        const double send = q ? y[j] : y[G / 2 + j];             // the half the partner lifts
+        const double got = __shfl_xor(send, 1);
+        const int i = q ? G / 2 + j : j;
+        const double r1 = q ? got : y[j], r2 = q ? y[G / 2 + j] : got;
+        poly[(uint32_t)BS * i] += slz_crt64(r1, r2, A.mod[1], A.p1inv_mod_p2);
+    }
+}
+
 // ---- host ------------------------------------------------------------------------------------------
 
 int slz_bign_supported(const slz_params *p) {
@@ -402,6 +556,7 @@ int slz_bign_init(slz_ctx *ctx) {
     ctx->has_bign16 = 0;
     ctx->bign_block = 0;
     ctx->bign_lanes = 2;
+    ctx->bign_latency = 1;
     bool any = false;
     if (block_fits(N, 2048) && bounds_ok(N, 2048)) {
         int rc = slz_build_block_tables(ctx, 2048, &ctx->bign_rowA, &ctx->bign_rowB);
@@ -414,6 +569,8 @@ int slz_bign_init(slz_ctx *ctx) {
         int rc = slz_build_block_tables(ctx, 1024, &ctx->bign16_rowA, &ctx->bign16_rowB);
         if (rc != SLZ_OK) return rc;
         SLZ_HIP(hipFuncSetAttribute((const void *)k_big_rows16, hipFuncAttributeMaxDynamicSharedMemorySize, 4 * (TBUF16 + 1024) * sizeof(double)));
+        SLZ_HIP(hipFuncSetAttribute((const void *)k_big_rows16_lat_a, hipFuncAttributeMaxDynamicSharedMemorySize, 4 * (TBUF16 + 1024) * sizeof(double)));
+        SLZ_HIP(hipFuncSetAttribute((const void *)k_big_rows16_lat_b, hipFuncAttributeMaxDynamicSharedMemorySize, 4 * TBUF16 * sizeof(double)));
         ctx->has_bign16 = 1;
         ctx->bign_block = 1024;                                  // preferred: two waves per SIMD in the row pass
         any = true;
@@ -426,7 +583,8 @@ void slz_bign_destroy(slz_ctx *ctx) {
     if (ctx->bign_rowB) (void)hipFree(ctx->bign_rowB);
     if (ctx->bign16_rowA) (void)hipFree(ctx->bign16_rowA);
     if (ctx->bign16_rowB) (void)hipFree(ctx->bign16_rowB);
-    ctx->bign_rowA = ctx->bign_rowB = ctx->bign16_rowA = ctx->bign16_rowB = nullptr;
+    if (ctx->bign_partial) (void)hipFree(ctx->bign_partial);
+    ctx->bign_rowA = ctx->bign_rowB = ctx->bign16_rowA = ctx->bign16_rowB = ctx->bign_partial = nullptr;
     for (int j = 0; j < 2; j++) {
         if (ctx->bign_lane_stream[j]) (void)hipStreamDestroy((hipStream_t)ctx->bign_lane_stream[j]);
         if (ctx->bign_lane_done[j]) (void)hipEventDestroy((hipEvent_t)ctx->bign_lane_done[j]);
@@ -436,29 +594,36 @@ void slz_bign_destroy(slz_ctx *ctx) {
     ctx->bign_fork = nullptr;
 }
 
+// mode 0: the throughput kernels; mode 1: the latency-oriented ones (forward pass split over levels and primes, inverse
+// pass with the two primes of a column on neighbouring lanes)
 template <int G, int BS>
-static void launch_cols(bool fwd, const bign_args &A, uint32_t batch, hipStream_t s) {
-    dim3 grid(BS / 256, 2, batch);
-    if (fwd) hipLaunchKernelGGL((k_big_cols_fwd<G, BS>), grid, dim3(256), 0, s, A);
-    else hipLaunchKernelGGL((k_big_cols_inv<G, BS>), grid, dim3(256), 0, s, A);
+static void launch_cols(bool fwd, int mode, const bign_args &A, uint32_t batch, hipStream_t s) {
+    if (mode == 0) {
+        dim3 grid(BS / 256, 2, batch);
+        if (fwd) hipLaunchKernelGGL((k_big_cols_fwd<G, BS, false>), grid, dim3(256), 0, s, A);
+        else hipLaunchKernelGGL((k_big_cols_inv<G, BS>), grid, dim3(256), 0, s, A);
+    } else {
+        if (fwd) hipLaunchKernelGGL((k_big_cols_fwd<G, BS, true>), dim3(BS / 256, 2 * A.l * 2, batch), dim3(256), 0, s, A);
+        else hipLaunchKernelGGL((k_big_cols_inv_lat<G, BS>), dim3(BS / 128, 2, batch), dim3(256), 0, s, A);
+    }
 }
 
-static void launch_cols_any(bool fwd, uint32_t G, uint32_t BS, const bign_args &A, uint32_t batch, hipStream_t s) {
+static void launch_cols_any(bool fwd, int mode, uint32_t G, uint32_t BS, const bign_args &A, uint32_t batch, hipStream_t s) {
     if (BS == 2048) {
         switch (G) {
-            case 2: launch_cols<2, 2048>(fwd, A, batch, s); break;
-            case 4: launch_cols<4, 2048>(fwd, A, batch, s); break;
-            case 8: launch_cols<8, 2048>(fwd, A, batch, s); break;
-            case 16: launch_cols<16, 2048>(fwd, A, batch, s); break;
-            default: launch_cols<32, 2048>(fwd, A, batch, s); break;
+            case 2: launch_cols<2, 2048>(fwd, mode, A, batch, s); break;
+            case 4: launch_cols<4, 2048>(fwd, mode, A, batch, s); break;
+            case 8: launch_cols<8, 2048>(fwd, mode, A, batch, s); break;
+            case 16: launch_cols<16, 2048>(fwd, mode, A, batch, s); break;
+            default: launch_cols<32, 2048>(fwd, mode, A, batch, s); break;
         }
     } else {
         switch (G) {
-            case 2: launch_cols<2, 1024>(fwd, A, batch, s); break;
-            case 4: launch_cols<4, 1024>(fwd, A, batch, s); break;
-            case 8: launch_cols<8, 1024>(fwd, A, batch, s); break;
-            case 16: launch_cols<16, 1024>(fwd, A, batch, s); break;
-            default: launch_cols<32, 1024>(fwd, A, batch, s); break;
+            case 2: launch_cols<2, 1024>(fwd, mode, A, batch, s); break;
+            case 4: launch_cols<4, 1024>(fwd, mode, A, batch, s); break;
+            case 8: launch_cols<8, 1024>(fwd, mode, A, batch, s); break;
+            case 16: launch_cols<16, 1024>(fwd, mode, A, batch, s); break;
+            default: launch_cols<32, 1024>(fwd, mode, A, batch, s); break;
         }
     }
 }
@@ -480,6 +645,11 @@ static int ensure_lanes(slz_ctx *ctx) {
     return SLZ_OK;
 }
 
+// Ciphertexts the latency-oriented kernels are used for: while their row tasks (2 G per ciphertext) fill at most a quarter
+// of the 2048 resident-wave slots of the row pass (measured at N = 32768: 47 against 57 us per step at 8 ciphertexts, 35
+// against 47 at one; from 12 ciphertexts on the throughput kernels are as fast or faster).
+static uint32_t latency_max_batch(uint32_t G) { return 512u / (2 * G) ? 512u / (2 * G) : 1u; }
+
 // Runs steps [0, n_steps) on accumulators that the caller has initialised in `acc` ([batch][2][N]).
 int slz_bign_cmux_steps(slz_ctx *ctx, const uint64_t *lwe_in, const double *bskp, uint32_t n_steps, uint64_t *acc,
                         uint32_t batch, hipStream_t s) {
@@ -487,6 +657,14 @@ int slz_bign_cmux_steps(slz_ctx *ctx, const uint64_t *lwe_in, const double *bskp
     const uint32_t N = p.N, BS = (uint32_t)ctx->bign_block, G = N / BS, R = 2 * p.pbs_level;
     uint32_t logG = 0;
     while ((1u << logG) < G) logG++;
+    // A handful of ciphertexts: every step in four shorter launches (1024-blocks only)
+    const bool lat = ctx->bign_latency && BS == 1024 && batch <= latency_max_batch(G);
+    if (lat && !ctx->bign_partial) {
+        const size_t cts = ctx->max_batch < latency_max_batch(G) ? ctx->max_batch : latency_max_batch(G);
+        void *buf = nullptr;
+        if (slz_scratch_alloc(&buf, cts * 2 * R * 2 * N * sizeof(double)) != SLZ_OK) return SLZ_E_NOMEM;
+        ctx->bign_partial = (double *)buf;
+    }
     // Ciphertexts go through all steps in chunks whose workspace (X, Y, accumulators: (2R + 4 + 2) N doubles each) stays
     // in the 256 MB Infinity Cache; the key (read once per chunk and step) streams from HBM.
     const size_t per_ct = (size_t)(2 * R + 4 + 2) * N * 8;
@@ -498,7 +676,7 @@ int slz_bign_cmux_steps(slz_ctx *ctx, const uint64_t *lwe_in, const double *bskp
     // Two lanes: the chunk is cut in two halves that run on two streams, so that the row pass of one half (bound by
     // arithmetic) overlaps the column passes of the other (bound by memory).  Measured at N = 32768: 5 % faster than one
     // lane; three or four lanes of the same size overflow the Infinity Cache and are slower.
-    uint32_t lanes = (uint32_t)ctx->bign_lanes;
+    uint32_t lanes = lat ? 1u : (uint32_t)ctx->bign_lanes;
     if (lanes >= 2) {
         uint32_t half = chunk / 2 / fill * fill;
         if (half < fill) half = fill;
@@ -544,7 +722,16 @@ int slz_bign_cmux_steps(slz_ctx *ctx, const uint64_t *lwe_in, const double *bskp
                 bign_args &a = A[j];
                 a.step = step;
                 a.bskp_step = bskp + (size_t)step * 2 * R * 2 * N;
-                launch_cols_any(true, G, BS, a, nbs[j], st[j]);
+                launch_cols_any(true, lat ? 1 : 0, G, BS, a, nbs[j], st[j]);
+                if (lat) {
+                    const uint32_t ta = n_tasks[j] * R, tb = n_tasks[j] * 2;
+                    hipLaunchKernelGGL(k_big_rows16_lat_a, dim3((ta + 3) / 4), dim3(256), 4 * (TBUF16 + 1024) * sizeof(double), st[j], a,
+                                       ctx->bign_partial, G, ta);
+                    hipLaunchKernelGGL(k_big_rows16_lat_b, dim3((tb + 3) / 4), dim3(256), 4 * TBUF16 * sizeof(double), st[j], a,
+                                       ctx->bign_partial, G, tb);
+                    launch_cols_any(false, 1, G, BS, a, nbs[j], st[j]);
+                    continue;
+                }
                 // the XCD-aware order needs the task count to split evenly over 8 XCDs x 4 waves x (2G/8) combinations
                 const int xcd_aware = (2 * G) % 8 == 0 && n_tasks[j] % 32 == 0 && (n_tasks[j] / 8) % (2 * G / 8) == 0;
                 if (BS == 2048)
@@ -553,7 +740,7 @@ int slz_bign_cmux_steps(slz_ctx *ctx, const uint64_t *lwe_in, const double *bskp
                 else
                     hipLaunchKernelGGL(k_big_rows16, dim3((n_tasks[j] + 3) / 4), dim3(256), 4 * (TBUF16 + 1024) * sizeof(double), st[j], a,
                                        G, n_tasks[j], xcd_aware);
-                launch_cols_any(false, G, BS, a, nbs[j], st[j]);
+                launch_cols_any(false, 0, G, BS, a, nbs[j], st[j]);
             }
         }
     }

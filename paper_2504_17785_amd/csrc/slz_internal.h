@@ -63,6 +63,8 @@ struct slz_ctx {
     int bign_lanes;           // 1: one chunk at a time on the caller's stream; 2: two half chunks on two internal streams
     void *bign_lane_stream[2], *bign_lane_done[2], *bign_fork;   // hipStream_t / hipEvent_t of the lanes, created at first use
     int bign_block;           // block size the large-N path uses: 1024 or 2048
+    int bign_latency;         // 1: a handful of ciphertexts take the latency-oriented kernels (four shorter launches per step)
+    double *bign_partial;     // their partial products [few ciphertexts][2][R][2][N], allocated at first use
     double *bign16_rowA;      // [2][G'][64] as bign_rowA for 1024-blocks
     double *bign16_rowB;      // [2][G'][15][64] per-lane twiddles of the last four forward stages of a 1024-block
     // scratch for the generic path, sized for max_batch

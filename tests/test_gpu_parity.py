@@ -647,9 +647,31 @@ def test_large_n_path_matches_oracle_and_generic(slz, orc, shape, block):
     want = orc.pbs_batch(p, case.cts, case.luts, case.lut_idx, case.keys.bsk)
     got = slz.to_host_u64(case.ctx.pbs_batch(case.d_cts, case.d_luts, case.d_idx, case.d_bsk))
     assert np.array_equal(got, want)
+    # five ciphertexts on 1024-blocks took the latency-oriented kernels (four launches per step); the same call on the
+    # throughput kernels, after one more step count on them
+    case.ctx.set_option(slz.SLZ_OPT_LARGE_N_LATENCY, 0)
+    assert np.array_equal(slz.to_host_u64(case.ctx.pbs_batch(case.d_cts, case.d_luts, case.d_idx, case.d_bsk)), want)
+    one = slz.to_host_u64(case.ctx.blind_rotate_batch(case.d_cts, case.d_luts, case.d_idx, case.d_bsk, 1))
+    assert np.array_equal(one, orc.blind_rotate_batch(p, case.cts, case.luts, case.lut_idx, case.keys.bsk, 1))
     case.ctx.set_option(slz.SLZ_OPT_FORCE_GENERIC, 1)
     gen = slz.to_host_u64(case.ctx.pbs_batch(case.d_cts, case.d_luts, case.d_idx, case.d_bsk))
     assert np.array_equal(gen, want)
+
+
+def test_large_n_latency_kernels_at_their_largest_batch_and_one_past_it(slz, orc):
+    # N = 8192 on 1024-blocks: up to 512 / 16 = 32 ciphertexts take the latency-oriented kernels, 33 the throughput ones;
+    # the first 32 results must not depend on which
+    p = tiny(n=2, N=8192, k=1, pbs_base_log=15, pbs_level=2)
+    case = Case(slz, orc, p, 33, raw_inputs=True)
+    assert case.ctx.path == "three_pass_large_n"
+    all33 = slz.to_host_u64(case.ctx.pbs_batch(case.d_cts, case.d_luts, case.d_idx, case.d_bsk))
+    first32 = slz.to_host_u64(case.ctx.pbs_batch(case.d_cts[:32], case.d_luts, case.d_idx[:32], case.d_bsk))
+    one = slz.to_host_u64(case.ctx.pbs_batch(case.d_cts[31:32], case.d_luts, case.d_idx[31:32], case.d_bsk))
+    assert np.array_equal(first32, all33[:32]) and np.array_equal(one[0], all33[31])
+    idx = np.array([0, 15, 31, 32])
+    assert np.array_equal(all33[idx], orc.pbs_batch(p, case.cts[idx], case.luts, case.lut_idx[idx], case.keys.bsk))
+    with pytest.raises(slz.SlzError):
+        case.ctx.set_option(slz.SLZ_OPT_LARGE_N_LATENCY, 2)
 
 
 def test_large_n_path_takes_n2048_with_two_levels(slz, orc):
@@ -681,6 +703,9 @@ def test_large_n_worst_case_magnitudes(slz, orc, block):
     luts[:, 1::2] = np.uint64(1 << 63)
     d_bsk = case.ctx.bsk_prepare(slz.to_device_u64(bsk))
     want = orc.blind_rotate_batch(p, case.cts, luts, case.lut_idx, bsk, p.n)
+    got = slz.to_host_u64(case.ctx.blind_rotate_batch(case.d_cts, slz.to_device_u64(luts), case.d_idx, d_bsk, p.n))
+    assert np.array_equal(got, want)
+    case.ctx.set_option(slz.SLZ_OPT_LARGE_N_LATENCY, 0)           # three ciphertexts: the throughput kernels as well
     got = slz.to_host_u64(case.ctx.blind_rotate_batch(case.d_cts, slz.to_device_u64(luts), case.d_idx, d_bsk, p.n))
     assert np.array_equal(got, want)
 
