@@ -191,6 +191,9 @@ k_big_rows(bign_args A, uint32_t G, uint32_t n_tasks, int xcd_aware) {
 // One wave per (ciphertext, prime, 1024-block), 16 coefficients per lane: the accumulators of both components, the block
 // and the tables fit 256 registers, so two waves share a SIMD and cover each other's memory latency (the 2048-block
 // kernel above needs more than 256 and runs one wave per SIMD, 43 % of it waiting for memory).
+// BOTH = false: one task per output component as well (twice the tasks, each with all R forward transforms but the products
+// and the inverse transform of one component only): for a few ciphertexts, where a pass lasts as long as its longest task.
+template <bool BOTH>
 __global__ void __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(2, 2)))
 k_big_rows16(bign_args A, uint32_t G, uint32_t n_tasks, int xcd_aware) {
     extern __shared__ double lds[];
@@ -203,6 +206,8 @@ k_big_rows16(bign_args A, uint32_t G, uint32_t n_tasks, int xcd_aware) {
         task = (v / cpx) * 2 * G + xcd * cpx + v % cpx;
     }
     if (task >= n_tasks) return;                                 // whole wave leaves; no workgroup barriers below
+    const uint32_t only = BOTH ? 0u : task & 1u;                 // the component of a one-component task
+    if (!BOTH) task >>= 1;
     double *T = lds + wv * (TBUF16 + 1024u);
     double *twA = T + TBUF16, *twB = twA + 64;                  // this block's forward tables, staged in LDS
     const uint32_t row = task % G, q = (task / G) & 1u, b = task / (2 * G);
@@ -235,11 +240,14 @@ k_big_rows16(bign_args A, uint32_t G, uint32_t n_tasks, int xcd_aware) {
         for (int e = 0; e < 16; e++) x[e] = xn[e];
         // the key words of this row and then the next row's block are requested here (vector memory completes in issue
         // order) and arrive while the transform runs
-        const double *k0 = A.bskp_step + (((size_t)q * R + r) * 2 + 0) * N + 32u * row + z;
+        const double *k0 = A.bskp_step + (((size_t)q * R + r) * 2 + only) * N + 32u * row + z;
         const double *k1 = k0 + N;
         double kk0[16], kk1[16];
 #pragma unroll
-        for (int i = 0; i < 16; i++) { kk0[i] = ldl(k0 + (size_t)i * stride, key_lane_off); kk1[i] = ldl(k1 + (size_t)i * stride, key_lane_off); }
+        for (int i = 0; i < 16; i++) {
+            kk0[i] = ldl(k0 + (size_t)i * stride, key_lane_off);
+            if (BOTH) kk1[i] = ldl(k1 + (size_t)i * stride, key_lane_off);
+        }
         {
             const double *nxt = A.X + (((size_t)b * 2 + q) * R + (r + 1 < R ? r + 1 : r)) * N + 1024u * row + z;
 #pragma unroll
@@ -253,13 +261,15 @@ k_big_rows16(bign_args A, uint32_t G, uint32_t n_tasks, int xcd_aware) {
             double r0[4], r1[4];
             const double x4[4] = {x[4 * g], x[4 * g + 1], x[4 * g + 2], x[4 * g + 3]};
             const double ka[4] = {kk0[4 * g], kk0[4 * g + 1], kk0[4 * g + 2], kk0[4 * g + 3]};
-            const double kb[4] = {kk1[4 * g], kk1[4 * g + 1], kk1[4 * g + 2], kk1[4 * g + 3]};
             mulmod_k<4>(r0, x4, ka, m);
-            mulmod_k<4>(r1, x4, kb, m);
+            if (BOTH) {
+                const double kb[4] = {kk1[4 * g], kk1[4 * g + 1], kk1[4 * g + 2], kk1[4 * g + 3]};
+                mulmod_k<4>(r1, x4, kb, m);
+            }
 #pragma unroll
             for (int u = 0; u < 4; u++) {
                 o0[4 * g + u] = (r == 0) ? r0[u] : o0[4 * g + u] + r0[u];
-                o1[4 * g + u] = (r == 0) ? r1[u] : o1[4 * g + u] + r1[u];
+                if (BOTH) o1[4 * g + u] = (r == 0) ? r1[u] : o1[4 * g + u] + r1[u];
             }
         }
         if ((r & 3u) == 3u && r + 1 < R) {                       // more than four rows: keep the running sums below 8 p
@@ -267,17 +277,20 @@ k_big_rows16(bign_args A, uint32_t G, uint32_t n_tasks, int xcd_aware) {
             for (int g = 0; g < 4; g++) {
                 double a4[4], b4[4];
                 const double xa[4] = {o0[4 * g], o0[4 * g + 1], o0[4 * g + 2], o0[4 * g + 3]};
-                const double xb[4] = {o1[4 * g], o1[4 * g + 1], o1[4 * g + 2], o1[4 * g + 3]};
                 reduce_k<4>(a4, xa, m);
-                reduce_k<4>(b4, xb, m);
+                if (BOTH) {
+                    const double xb[4] = {o1[4 * g], o1[4 * g + 1], o1[4 * g + 2], o1[4 * g + 3]};
+                    reduce_k<4>(b4, xb, m);
+                }
 #pragma unroll
-                for (int u = 0; u < 4; u++) { o0[4 * g + u] = a4[u]; o1[4 * g + u] = b4[u]; }
+                for (int u = 0; u < 4; u++) { o0[4 * g + u] = a4[u]; if (BOTH) o1[4 * g + u] = b4[u]; }
             }
         }
         wave_sync();
     }
     // inverse: first 10 stages inside the block, reduce, hand the block to the column pass
-    for (int comp = 0; comp < 2; comp++) {
+    for (int cc = 0; cc < (BOTH ? 2 : 1); cc++) {
+        const uint32_t comp = BOTH ? (uint32_t)cc : only;
         int z;
         asm volatile("s_mov_b32 %0, 0" : "=s"(z));
         double x[16];
@@ -285,7 +298,7 @@ k_big_rows16(bign_args A, uint32_t G, uint32_t n_tasks, int xcd_aware) {
         for (int g = 0; g < 2; g++) {
             double r8[8], x8[8];
 #pragma unroll
-            for (int u = 0; u < 8; u++) x8[u] = comp ? o1[8 * g + u] : o0[8 * g + u];
+            for (int u = 0; u < 8; u++) x8[u] = (BOTH && cc) ? o1[8 * g + u] : o0[8 * g + u];
             reduce_k<8>(r8, x8, m);
 #pragma unroll
             for (int u = 0; u < 8; u++) x[8 * g + u] = r8[u];
@@ -568,7 +581,8 @@ int slz_bign_init(slz_ctx *ctx) {
     if (block_fits(N, 1024) && bounds_ok(N, 1024)) {
         int rc = slz_build_block_tables(ctx, 1024, &ctx->bign16_rowA, &ctx->bign16_rowB);
         if (rc != SLZ_OK) return rc;
-        SLZ_HIP(hipFuncSetAttribute((const void *)k_big_rows16, hipFuncAttributeMaxDynamicSharedMemorySize, 4 * (TBUF16 + 1024) * sizeof(double)));
+        SLZ_HIP(hipFuncSetAttribute((const void *)k_big_rows16<true>, hipFuncAttributeMaxDynamicSharedMemorySize, 4 * (TBUF16 + 1024) * sizeof(double)));
+        SLZ_HIP(hipFuncSetAttribute((const void *)k_big_rows16<false>, hipFuncAttributeMaxDynamicSharedMemorySize, 4 * (TBUF16 + 1024) * sizeof(double)));
         SLZ_HIP(hipFuncSetAttribute((const void *)k_big_rows16_lat_a, hipFuncAttributeMaxDynamicSharedMemorySize, 4 * (TBUF16 + 1024) * sizeof(double)));
         SLZ_HIP(hipFuncSetAttribute((const void *)k_big_rows16_lat_b, hipFuncAttributeMaxDynamicSharedMemorySize, 4 * TBUF16 * sizeof(double)));
         ctx->has_bign16 = 1;
@@ -723,6 +737,14 @@ int slz_bign_cmux_steps(slz_ctx *ctx, const uint64_t *lwe_in, const double *bskp
                 a.step = step;
                 a.bskp_step = bskp + (size_t)step * 2 * R * 2 * N;
                 launch_cols_any(true, lat ? 1 : 0, G, BS, a, nbs[j], st[j]);
+                if (lat && nbs[j] * 2 > latency_max_batch(G)) {
+                    // upper half of the range: one launch of one-component row tasks (all slots get one wave)
+                    const uint32_t tc = n_tasks[j] * 2;
+                    hipLaunchKernelGGL(k_big_rows16<false>, dim3((tc + 3) / 4), dim3(256), 4 * (TBUF16 + 1024) * sizeof(double), st[j], a, G,
+                                       tc, 0);
+                    launch_cols_any(false, 1, G, BS, a, nbs[j], st[j]);
+                    continue;
+                }
                 if (lat) {
                     const uint32_t ta = n_tasks[j] * R, tb = n_tasks[j] * 2;
                     hipLaunchKernelGGL(k_big_rows16_lat_a, dim3((ta + 3) / 4), dim3(256), 4 * (TBUF16 + 1024) * sizeof(double), st[j], a,
@@ -738,7 +760,7 @@ int slz_bign_cmux_steps(slz_ctx *ctx, const uint64_t *lwe_in, const double *bskp
                     hipLaunchKernelGGL(k_big_rows, dim3((n_tasks[j] + 3) / 4), dim3(256), 4 * TBUF * sizeof(double), st[j], a, G,
                                        n_tasks[j], xcd_aware);
                 else
-                    hipLaunchKernelGGL(k_big_rows16, dim3((n_tasks[j] + 3) / 4), dim3(256), 4 * (TBUF16 + 1024) * sizeof(double), st[j], a,
+                    hipLaunchKernelGGL(k_big_rows16<true>, dim3((n_tasks[j] + 3) / 4), dim3(256), 4 * (TBUF16 + 1024) * sizeof(double), st[j], a,
                                        G, n_tasks[j], xcd_aware);
                 launch_cols_any(false, 0, G, BS, a, nbs[j], st[j]);
             }
