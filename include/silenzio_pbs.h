@@ -80,7 +80,7 @@ typedef struct slz_ctx slz_ctx;   /* opaque: parameter copy, twiddle tables, scr
                                      SLZ_E_INVALID_ARG when the context has no large-N path */
 
 #define SLZ_OPT_LARGE_N_LATENCY 5 /* value 1 (default) or 0: on the large-N path with 1024-blocks, calls with so few ciphertexts that
-                                     the chip stays mostly empty (at most 512 / (2 N / 1024): 8 at N = 32768) run every CMux step
+                                     the chip stays mostly empty (at most 1024 / (2 N / 1024): 16 at N = 32768) run every CMux step
                                      as four shorter launches with four times the threads (lower latency, identical results; their
                                      scratch of 2 (k+1) l (k+1) N doubles per such ciphertext is allocated by the first such call);
                                      0 keeps the throughput kernels at every batch size; SLZ_E_INVALID_ARG without a large-N path */

@@ -659,10 +659,13 @@ static int ensure_lanes(slz_ctx *ctx) {
     return SLZ_OK;
 }
 
-// Ciphertexts the latency-oriented kernels are used for: while their row tasks (2 G per ciphertext) fill at most a quarter
-// of the 2048 resident-wave slots of the row pass (measured at N = 32768: 47 against 57 us per step at 8 ciphertexts, 35
-// against 47 at one; from 12 ciphertexts on the throughput kernels are as fast or faster).
-static uint32_t latency_max_batch(uint32_t G) { return 512u / (2 * G) ? 512u / (2 * G) : 1u; }
+// Ciphertexts the latency-oriented kernels are used for: while their row tasks (2 G per ciphertext) fill at most half of
+// the 2048 resident-wave slots of the row pass.  Measured at N = 32768, us per CMux step against the throughput kernels:
+// 34 / 47 at one ciphertext, 40 / 52 at 4, 41 / 57 at 8, 50 / 58 at 12, 53 / 61 at 16; from 20 on they are equal.
+static uint32_t latency_max_batch(uint32_t G) { return 1024u / (2 * G) ? 1024u / (2 * G) : 1u; }
+// Up to this many ciphertexts the row pass is cut into per-GGSW-row and per-component launches, above it into one launch
+// of one-component tasks.
+static uint32_t latency_split_rows_max(uint32_t G) { return 256u / (2 * G) ? 256u / (2 * G) : 1u; }
 
 // Runs steps [0, n_steps) on accumulators that the caller has initialised in `acc` ([batch][2][N]).
 int slz_bign_cmux_steps(slz_ctx *ctx, const uint64_t *lwe_in, const double *bskp, uint32_t n_steps, uint64_t *acc,
@@ -737,8 +740,8 @@ int slz_bign_cmux_steps(slz_ctx *ctx, const uint64_t *lwe_in, const double *bskp
                 a.step = step;
                 a.bskp_step = bskp + (size_t)step * 2 * R * 2 * N;
                 launch_cols_any(true, lat ? 1 : 0, G, BS, a, nbs[j], st[j]);
-                if (lat && nbs[j] * 2 > latency_max_batch(G)) {
-                    // upper half of the range: one launch of one-component row tasks (all slots get one wave)
+                if (lat && nbs[j] > latency_split_rows_max(G)) {
+                    // upper part of the range: one launch of one-component row tasks
                     const uint32_t tc = n_tasks[j] * 2;
                     hipLaunchKernelGGL(k_big_rows16<false>, dim3((tc + 3) / 4), dim3(256), 4 * (TBUF16 + 1024) * sizeof(double), st[j], a, G,
                                        tc, 0);

@@ -659,17 +659,18 @@ def test_large_n_path_matches_oracle_and_generic(slz, orc, shape, block):
 
 
 def test_large_n_latency_kernels_at_their_largest_batch_and_one_past_it(slz, orc):
-    # N = 8192 on 1024-blocks: up to 512 / 16 = 32 ciphertexts take the latency-oriented kernels, 33 the throughput ones;
-    # the first 32 results must not depend on which
+    # N = 8192 on 1024-blocks: up to 1024 / 16 = 64 ciphertexts take the latency-oriented kernels (up to 16 with the row pass
+    # in two launches, above that in one launch of one-component tasks), 65 the throughput ones; a ciphertext's result must
+    # not depend on which
     p = tiny(n=2, N=8192, k=1, pbs_base_log=15, pbs_level=2)
-    case = Case(slz, orc, p, 33, raw_inputs=True)
+    case = Case(slz, orc, p, 65, raw_inputs=True)
     assert case.ctx.path == "three_pass_large_n"
-    all33 = slz.to_host_u64(case.ctx.pbs_batch(case.d_cts, case.d_luts, case.d_idx, case.d_bsk))
-    first32 = slz.to_host_u64(case.ctx.pbs_batch(case.d_cts[:32], case.d_luts, case.d_idx[:32], case.d_bsk))
-    one = slz.to_host_u64(case.ctx.pbs_batch(case.d_cts[31:32], case.d_luts, case.d_idx[31:32], case.d_bsk))
-    assert np.array_equal(first32, all33[:32]) and np.array_equal(one[0], all33[31])
-    idx = np.array([0, 15, 31, 32])
-    assert np.array_equal(all33[idx], orc.pbs_batch(p, case.cts[idx], case.luts, case.lut_idx[idx], case.keys.bsk))
+    all65 = slz.to_host_u64(case.ctx.pbs_batch(case.d_cts, case.d_luts, case.d_idx, case.d_bsk))
+    for count in (64, 17, 16, 1):
+        part = slz.to_host_u64(case.ctx.pbs_batch(case.d_cts[:count], case.d_luts, case.d_idx[:count], case.d_bsk))
+        assert np.array_equal(part, all65[:count]), count
+    idx = np.array([0, 15, 16, 63, 64])
+    assert np.array_equal(all65[idx], orc.pbs_batch(p, case.cts[idx], case.luts, case.lut_idx[idx], case.keys.bsk))
     with pytest.raises(slz.SlzError):
         case.ctx.set_option(slz.SLZ_OPT_LARGE_N_LATENCY, 2)
 
