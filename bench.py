@@ -354,6 +354,8 @@ class Workload:
         self.ctx = ctx = slz.Context(p, batch)
         if args.generic:
             ctx.set_option(slz.SLZ_OPT_FORCE_GENERIC, 1)
+        if args.no_pacing:
+            ctx.set_option(slz.SLZ_OPT_FUSED_PACING, 0)
         if args.large_n_lanes:
             ctx.set_option(slz.SLZ_OPT_LARGE_N_LANES, args.large_n_lanes)
         if args.large_n_block:
@@ -531,6 +533,7 @@ def main():
     ap.add_argument("--no-per-config", action="store_true", help="default run: skip configurations 1 to 4")
     ap.add_argument("--generic", action="store_true", help="force the generic multi-kernel path")
     ap.add_argument("--override", default="", help="comma-separated parameter overrides of the configuration, e.g. N=4096,pbs_base_log=22,n=256")
+    ap.add_argument("--no-pacing", action="store_true", help="fused N = 2048 kernel: let the workgroups run free between ciphertexts")
     ap.add_argument("--large-n-block", type=int, default=0, help="large-N path: block size of the row pass, 1024 or 2048")
     ap.add_argument("--large-n-lanes", type=int, default=0, help="large-N path: 1 = one chunk at a time, 2 = two half chunks on two streams")
     ap.add_argument("--calib-copy", action="store_true",

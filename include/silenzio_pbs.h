@@ -85,6 +85,10 @@ typedef struct slz_ctx slz_ctx;   /* opaque: parameter copy, twiddle tables, scr
                                      scratch of 2 (k+1) l (k+1) N doubles per such ciphertext is allocated by the first such call);
                                      0 keeps the throughput kernels at every batch size; SLZ_E_INVALID_ARG without a large-N path */
 
+#define SLZ_OPT_FUSED_PACING 6    /* value 1 (default) or 0: the N = 2048 fused kernel's workgroups wait for each other between
+                                     ciphertexts (launches of more than 1024 ciphertexts; a wait as long as the waiting workgroup's own ciphertext took ends the pacing for that launch) so that they keep reading the
+                                     same key rows from the L2; 0 lets them run free.  Results are identical.  SLZ_E_INVALID_ARG on other paths */
+
 #define SLZ_OPT_FAIL_ALLOC_AFTER 4 /* for tests of the out-of-memory handling: value v >= 0 makes the (v+1)-th scratch allocation
                                      from now (of any context of the process) return SLZ_E_NOMEM without touching the device,
                                      once; v < 0 disarms */

@@ -20,6 +20,7 @@ SLZ_OPT_LARGE_N_BLOCK = 2
 SLZ_OPT_LARGE_N_LANES = 3
 SLZ_OPT_FAIL_ALLOC_AFTER = 4
 SLZ_OPT_LARGE_N_LATENCY = 5
+SLZ_OPT_FUSED_PACING = 6
 SLZ_OK, SLZ_E_INVALID_ARG, SLZ_E_UNSUPPORTED, SLZ_E_HIP, SLZ_E_NOMEM, SLZ_E_TOO_LARGE = 0, -1, -2, -3, -4, -5
 
 

@@ -60,6 +60,7 @@ extern "C" int slz_ctx_create(const slz_params *params, uint32_t max_batch, slz_
     if (rc == SLZ_OK && slz_fused_supported(params)) {
         rc = slz_fused_init(ctx);
         ctx->has_fused = (rc == SLZ_OK);
+        ctx->fused_pacing = 1;
         if (rc == SLZ_E_UNSUPPORTED) rc = SLZ_OK;
     }
     if (rc == SLZ_OK && slz_fused4096_supported(params)) {
@@ -115,6 +116,11 @@ extern "C" int slz_ctx_set_option(slz_ctx *ctx, int option, int value) {
         if (value == 1024 && ctx->has_bign16) { ctx->bign_block = 1024; return SLZ_OK; }
         if (value == 2048 && ctx->bign_rowA) { ctx->bign_block = 2048; return SLZ_OK; }
         return SLZ_E_INVALID_ARG;
+    }
+    if (option == SLZ_OPT_FUSED_PACING) {
+        if (!ctx->has_fused || (value != 0 && value != 1)) return SLZ_E_INVALID_ARG;
+        ctx->fused_pacing = value;
+        return SLZ_OK;
     }
     if (option == SLZ_OPT_LARGE_N_LATENCY) {
         if (!ctx->has_bign || (value != 0 && value != 1)) return SLZ_E_INVALID_ARG;

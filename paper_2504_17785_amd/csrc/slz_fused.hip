@@ -39,8 +39,17 @@ struct fused_args {
     double tw_inv[2][32];     // inv[t + j], t + j < 32: first five inverse stages
     slz_mod mod[2];
     double p1inv_mod_p2;
+    uint32_t *sync;           // [rounds] arrival counters of the pacing between ciphertexts (zeroed before the launch), or null
 };
 
+#define FUSED_SYNC_SLOTS 4096u        // rounds (ciphertexts per workgroup) one launch can pace
+
+// sync[0 .. rounds) arrival counters, sync[FUSED_SYNC_SLOTS] the "a wait has timed out" flag
+__global__ void k_fused_zero_sync(uint32_t *sync, uint32_t count) {
+    const uint32_t i = blockIdx.x * blockDim.x + threadIdx.x;
+    if (i < count) sync[i] = 0;
+    if (i == 0) sync[FUSED_SYNC_SLOTS] = 0;
+}
 
 #include "slz_wave_ntt.h"
 
@@ -66,6 +75,7 @@ k_fused_blind_rotate_n2048(fused_args A) {
     const uint32_t hh = lane >> 5;
 
     for (uint32_t c = blockIdx.x; c < A.batch; c += gridDim.x) {
+        const long long t_round = A.sync ? wall_clock64() : 0;   // for the pacing at the end of the round
         const uint64_t *lwe = A.lwe_in + (size_t)c * (A.n + 1);
         // ---- accumulator quarter: coefficients 64*(16q + e) + lane of component h ----
         uint64_t acc[16];
@@ -214,6 +224,33 @@ k_fused_blind_rotate_n2048(fused_args A) {
             }
         }
         __syncthreads();                              // the next ciphertext reuses the LDS buffers
+        // Pacing: the workgroups of a launch read the same key rows, and an L2 (4 MiB per XCD) holds the rows of ten to thirty
+        // steps.  Left alone the workgroups drift apart by more than that within a few ciphertexts and most key rows then come from beyond the L2 (measured at 16 384 ciphertexts: 300 times the key's
+        // size per launch; paced: 20 times, which is the eight L2s filling once per round, twice over).  So a workgroup that
+        // has another ciphertext to do waits here until the others have finished this round as well.  A hint, not a
+        // dependency: the first wait that lasts as long as the waiting workgroup's own round did (the two workgroups of a
+        // compute unit do not get equal shares of it, so one may finish well before the other; longer than that means a
+        // workgroup that is not resident, say beside another kernel) switches the pacing off for the rest of the launch.  Run time is the same either way: beyond the L2 the key sits in the
+        // memory-side cache and the loads are issued far enough ahead.
+        if (A.sync) {
+            const bool more = c + gridDim.x < A.batch;
+            if (threadIdx.x == 0) {
+                const uint32_t round = c / gridDim.x;
+                const uint32_t here = min(gridDim.x, A.batch - round * gridDim.x);       // workgroups with a ciphertext in this round
+                __hip_atomic_fetch_add(&A.sync[round], 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+                if (more && !__hip_atomic_load(&A.sync[FUSED_SYNC_SLOTS], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT)) {
+                    const long long t0 = wall_clock64(), limit = t0 - t_round;
+                    while (__hip_atomic_load(&A.sync[round], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) < here) {
+                        if (wall_clock64() - t0 >= limit) {
+                            __hip_atomic_store(&A.sync[FUSED_SYNC_SLOTS], 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+                            break;
+                        }
+                        __builtin_amdgcn_s_sleep(32);
+                    }
+                }
+            }
+            if (more) __syncthreads();
+        }
     }
 }
 
@@ -241,6 +278,7 @@ int slz_fused_init(slz_ctx *ctx) {
         SLZ_HIP(hipMemcpy(ctx->fused_scalars[q][1], ctx->tab[q].inv, 32 * sizeof(double), hipMemcpyDeviceToHost));
     }
     SLZ_HIP(hipMalloc((void **)&ctx->fused_tab, host.size() * sizeof(double)));
+    SLZ_HIP(hipMalloc((void **)&ctx->fused_sync, (FUSED_SYNC_SLOTS + 1) * sizeof(uint32_t)));
     SLZ_HIP(hipMemcpy(ctx->fused_tab, host.data(), host.size() * sizeof(double), hipMemcpyHostToDevice));
     // worst-case bounds of the fixed reduction schedule (units of p); everything must stay below 2^53 = 8 p
     double a = 1e-6;
@@ -265,7 +303,9 @@ int slz_fused_init(slz_ctx *ctx) {
 
 void slz_fused_destroy(slz_ctx *ctx) {
     if (ctx->fused_tab) (void)hipFree(ctx->fused_tab);
+    if (ctx->fused_sync) (void)hipFree(ctx->fused_sync);
     ctx->fused_tab = nullptr;
+    ctx->fused_sync = nullptr;
 }
 
 int slz_fused_blind_rotate(slz_ctx *ctx, const uint64_t *lwe_in, const uint64_t *luts, const uint32_t *lut_idx,
@@ -285,6 +325,12 @@ int slz_fused_blind_rotate(slz_ctx *ctx, const uint64_t *lwe_in, const uint64_t 
     A.p1inv_mod_p2 = ctx->p1inv_mod_p2;
     const uint32_t resident = 2u * 256u;               // two workgroups (68 KiB of LDS each) per compute unit
     const uint32_t grid = batch < resident ? batch : resident;
+    const uint32_t rounds = (batch + grid - 1) / grid;
+    A.sync = nullptr;
+    if (rounds > 2 && rounds <= FUSED_SYNC_SLOTS && ctx->fused_pacing) {   // counters cleared by a kernel (safe under graph capture)
+        hipLaunchKernelGGL(k_fused_zero_sync, dim3((rounds + 255) / 256), dim3(256), 0, s, ctx->fused_sync, rounds);
+        A.sync = ctx->fused_sync;
+    }
     if (A.beta == 23)       // the base of the N = 2048 parameter sets
         hipLaunchKernelGGL(k_fused_blind_rotate_n2048<23>, dim3(grid), dim3(FUSED_THREADS), 4 * TBUF * sizeof(double), s, A);
     else

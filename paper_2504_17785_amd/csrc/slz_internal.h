@@ -55,6 +55,8 @@ struct slz_ctx {
     double p1inv_mod_p2;      // p1^{-1} mod p2 (centred)
     slz_tables tab[2];
     double *fused_tab;        // tables re-laid-out for the fused kernel (or null)
+    uint32_t *fused_sync;     // arrival counters of the fused kernel's pacing between ciphertexts
+    int fused_pacing;         // 1: workgroups of the N = 2048 fused kernel wait for each other between ciphertexts
     double fused_scalars[2][2][32];   // [prime][forward, inverse]: the lane-uniform twiddles of the fused kernel
     int has_bign;             // large-N three-pass path available (N = 2048 G, k = 1)
     double *bign_rowA;        // [2][G][64] block-specific lane-uniform forward twiddles

@@ -389,6 +389,26 @@ def test_fused_more_ciphertexts_than_resident_workgroups(slz, orc):
     assert np.array_equal(fused[idx], want)
 
 
+def test_fused_pacing_between_ciphertexts_changes_nothing(slz, orc):
+    # 1100 ciphertexts on 512 workgroups: three rounds, the last one ragged (76 workgroups).  Between rounds the workgroups wait
+    # for each other (a timing hint with a bounded wait); with it off they run free.  Same bits either way, on repeated
+    # launches (the arrival counters are cleared per launch), and with a batch that needs no pacing in between.
+    p, case = _fused_case(slz, orc, 2, 1100)
+    ctx = case.ctx
+    paced = slz.to_host_u64(ctx.pbs_batch(case.d_cts, case.d_luts, case.d_idx, case.d_bsk))
+    small = slz.to_host_u64(ctx.pbs_batch(case.d_cts[:300], case.d_luts, case.d_idx[:300], case.d_bsk))
+    again = slz.to_host_u64(ctx.pbs_batch(case.d_cts, case.d_luts, case.d_idx, case.d_bsk))
+    ctx.set_option(slz.SLZ_OPT_FUSED_PACING, 0)
+    free = slz.to_host_u64(ctx.pbs_batch(case.d_cts, case.d_luts, case.d_idx, case.d_bsk))
+    assert np.array_equal(paced, free) and np.array_equal(again, free) and np.array_equal(small, free[:300])
+    idx = np.array([0, 511, 512, 1023, 1024, 1099])
+    assert np.array_equal(paced[idx], orc.pbs_batch(p, case.cts[idx], case.luts, case.lut_idx[idx], case.keys.bsk))
+    with pytest.raises(slz.SlzError):
+        ctx.set_option(slz.SLZ_OPT_FUSED_PACING, 2)
+    with pytest.raises(slz.SlzError):
+        slz.Context(tiny(), 4).set_option(slz.SLZ_OPT_FUSED_PACING, 1)      # not the N = 2048 fused path
+
+
 # ---------------------------------------------------------------- fused kernel for N = 512 (k = 1 or 3, l = 1)
 
 @pytest.mark.parametrize("k,beta", [(3, 18), (3, 7), (1, 23), (1, 10)])
