@@ -16,29 +16,19 @@
 // Key rows are read straight from L2 (every workgroup on the chip reads the same 128 KiB per step).
 #include "slz_internal.h"
 #include "slz_modarith.h"
+#include "slz_fused_common.h"
 #include <vector>
 
 #define STAGE_OFF 1088u       // second half of a wave buffer: staging of 1024 accumulator words
 #define FUSED_THREADS 256
 
-struct fused_args {
-    const uint64_t *lwe_in;
-    const uint64_t *luts;
-    const uint32_t *lut_idx;
-    const double *bskp;
-    uint64_t *acc_out;
-    uint64_t *lwe_out;
-    uint32_t n, n_steps, batch, beta;
+struct fused_args : slz_fused_io {
     // per-lane twiddle tables in HBM/L2, one per prime
     const double *fwd6[2];    // [32]      fwd[32 + x]: stage with stride 32 (one value per half-wave and register pair)
     const double *fwdB[2];    // [31][64]  last five forward stages, entry (k, lane)
-    const double *inv[2];     // [N]       inv[t + j]: cyclic inverse twiddles (t >= 32 are per lane)
-    const double *post[2];    // [N]       psi^-j / N
     // lane-uniform twiddles travel in the kernel argument segment and are read with scalar loads
     double tw_fwd[2][32];     // fwd[m + blk], m + blk < 32: first five forward stages
     double tw_inv[2][32];     // inv[t + j], t + j < 32: first five inverse stages
-    slz_mod mod[2];
-    double p1inv_mod_p2;
     uint32_t *sync;           // [rounds] arrival counters of the pacing between ciphertexts (zeroed before the launch), or null
 };
 
@@ -280,20 +270,8 @@ int slz_fused_init(slz_ctx *ctx) {
     SLZ_HIP(hipMalloc((void **)&ctx->fused_tab, host.size() * sizeof(double)));
     SLZ_HIP(hipMalloc((void **)&ctx->fused_sync, (FUSED_SYNC_SLOTS + 1) * sizeof(uint32_t)));
     SLZ_HIP(hipMemcpy(ctx->fused_tab, host.data(), host.size() * sizeof(double), hipMemcpyHostToDevice));
-    // worst-case bounds of the fixed reduction schedule (units of p); everything must stay below 2^53 = 8 p
-    double a = 1e-6;
-    for (int s = 0; s < 6; s++) a += slz_mulmod_bound(a);
-    if (a > 7.5) return SLZ_E_UNSUPPORTED;
-    a = 0.5 + 1e-9;
-    for (int s = 0; s < 5; s++) a += slz_mulmod_bound(a);
-    const double fwd_out = a;
-    if (fwd_out > 7.5 || 2 * slz_mulmod_bound(fwd_out) > 7.5) return SLZ_E_UNSUPPORTED;
-    a = 2.0 * (0.5 + 1e-9) * 2.0;                      // two multiply-free stages double the bound
-    for (int s = 2; s < 5; s++) a += slz_mulmod_bound(a);
-    if (a > 7.5) return SLZ_E_UNSUPPORTED;
-    a = 0.5 + 1e-9;
-    for (int s = 5; s < 11; s++) a += slz_mulmod_bound(a);
-    if (a > 7.5 || slz_mulmod_bound(a) > 1.95) return SLZ_E_UNSUPPORTED;   // slz_d2i needs |r| < 2 p
+    // six forward stages, reduction, five more; two products summed; inverse 2 + 3 stages, reduction, six stages, twist
+    if (!slz_fused_schedule_ok(0, 6, 5, 2, 3, 6, false, 1)) return SLZ_E_UNSUPPORTED;
     SLZ_HIP(hipFuncSetAttribute((const void *)k_fused_blind_rotate_n2048<23>, hipFuncAttributeMaxDynamicSharedMemorySize,
                                 4 * TBUF * sizeof(double)));
     SLZ_HIP(hipFuncSetAttribute((const void *)k_fused_blind_rotate_n2048<0>, hipFuncAttributeMaxDynamicSharedMemorySize,
@@ -312,19 +290,13 @@ int slz_fused_blind_rotate(slz_ctx *ctx, const uint64_t *lwe_in, const uint64_t 
                            const double *bskp, uint32_t n_steps, uint64_t *acc_out, uint64_t *lwe_out, uint32_t batch,
                            hipStream_t s) {
     fused_args A;
-    A.lwe_in = lwe_in; A.luts = luts; A.lut_idx = lut_idx; A.bskp = bskp; A.acc_out = acc_out; A.lwe_out = lwe_out;
-    A.n = ctx->prm.n; A.n_steps = n_steps; A.batch = batch; A.beta = ctx->prm.pbs_base_log;
+    slz_fused_fill_io(A, ctx, lwe_in, luts, lut_idx, bskp, n_steps, acc_out, lwe_out, batch);
     for (int q = 0; q < 2; q++) {
         A.fwd6[q] = ctx->tab[q].fwd + 32;
         A.fwdB[q] = ctx->fused_tab + (size_t)q * 31 * 64;
-        A.inv[q] = ctx->tab[q].inv;
-        A.post[q] = ctx->tab[q].post;
-        A.mod[q] = ctx->mod[q];
         for (int x = 0; x < 32; x++) { A.tw_fwd[q][x] = ctx->fused_scalars[q][0][x]; A.tw_inv[q][x] = ctx->fused_scalars[q][1][x]; }
     }
-    A.p1inv_mod_p2 = ctx->p1inv_mod_p2;
-    const uint32_t resident = 2u * 256u;               // two workgroups (68 KiB of LDS each) per compute unit
-    const uint32_t grid = batch < resident ? batch : resident;
+    const uint32_t grid = slz_fused_grid(batch, 2);    // two workgroups (68 KiB of LDS each) per compute unit
     const uint32_t rounds = (batch + grid - 1) / grid;
     A.sync = nullptr;
     if (rounds > 2 && rounds <= FUSED_SYNC_SLOTS && ctx->fused_pacing) {   // counters cleared by a kernel (safe under graph capture)

@@ -15,6 +15,7 @@
 // The forward twiddle tables of both primes (2 x 1024 doubles) are staged in LDS once per workgroup.
 #include "slz_internal.h"
 #include "slz_modarith.h"
+#include "slz_fused_common.h"
 #include <vector>
 
 #include "slz_wave_ntt.h"
@@ -28,21 +29,10 @@
 #define G_STAGE_OFF 576u       // second half of a wave buffer: staging of 512 accumulator words
 #define G_LDS_DOUBLES(C) (2u * (C) * TBUF16 + 2u * 1024u)
 
-struct fused1024_args {
-    const uint64_t *lwe_in;
-    const uint64_t *luts;
-    const uint32_t *lut_idx;
-    const double *bskp;
-    uint64_t *acc_out;
-    uint64_t *lwe_out;
-    uint32_t n, n_steps, batch, beta;
+struct fused1024_args : slz_fused_io {
     const double *rowA[2];    // [64]      lane-uniform and half-wave / row twiddles of the first six forward stages
     const double *rowB[2];    // [15][64]  per-lane twiddles of the last four forward stages
-    const double *inv[2];     // [N]       inv[t + j]: cyclic inverse twiddles
-    const double *post[2];    // [N]       psi^-j / N
     double tw_inv[2][16];     // inv[t + j], t + j < 16: lane-uniform inverse twiddles (scalar loads)
-    slz_mod mod[2];
-    double p1inv_mod_p2;
 };
 
 template <int BETA, int K>
@@ -267,23 +257,13 @@ int slz_fused1024_supported(const slz_params *p) {
 }
 
 int slz_fused1024_init(slz_ctx *ctx) {
-    // worst-case bounds of the fixed reduction schedule (units of p); everything must stay below 2^53 = 8 p
-    double a = 1e-6;
-    for (int s = 0; s < 6; s++) a += slz_mulmod_bound(a);            // digits through the first six forward stages
-    if (a > 7.5) return SLZ_E_UNSUPPORTED;
-    a = 0.5 + 1e-9;
-    for (int s = 0; s < 4; s++) a += slz_mulmod_bound(a);            // reduced, four more stages
-    if (a > 7.5 || 2 * slz_mulmod_bound(a) > 7.5) return SLZ_E_UNSUPPORTED;   // two products summed
-    a = 2.0 * (0.5 + 1e-9) * 2.0;                                    // inverse: two multiply-free stages double the bound
-    for (int s = 2; s < 4; s++) a += slz_mulmod_bound(a);
-    if (a > 7.5) return SLZ_E_UNSUPPORTED;
-    a = 0.5 + 1e-9;
-    for (int s = 4; s < 10; s++) a += slz_mulmod_bound(a);
-    if (a > 7.5 || slz_mulmod_bound(a) > 1.95) return SLZ_E_UNSUPPORTED;      // the CRT lift needs |r| < 2 p after the twist
+    // six forward stages on the digits, reduction, four more; two products summed; inverse 2 + 2 stages, reduction, six
+    // stages, twist
+    if (!slz_fused_schedule_ok(0, 6, 4, 2, 2, 6, false, 1)) return SLZ_E_UNSUPPORTED;
     int rc = slz_build_block_tables(ctx, GN, &ctx->fused1024_rowA, &ctx->fused1024_rowB);
     if (rc != SLZ_OK) return rc;
-    for (int q = 0; q < 2; q++)
-        SLZ_HIP(hipMemcpy(ctx->fused_scalars[q][1], ctx->tab[q].inv, 32 * sizeof(double), hipMemcpyDeviceToHost));
+    rc = slz_fused_load_inv_scalars(ctx);
+    if (rc != SLZ_OK) return rc;
     SLZ_HIP(hipFuncSetAttribute((const void *)k_fused_blind_rotate_n1024<23, 1>, hipFuncAttributeMaxDynamicSharedMemorySize,
                                 G_LDS_DOUBLES(2) * sizeof(double)));
     SLZ_HIP(hipFuncSetAttribute((const void *)k_fused_blind_rotate_n1024<0, 1>, hipFuncAttributeMaxDynamicSharedMemorySize,
@@ -303,24 +283,17 @@ int slz_fused1024_blind_rotate(slz_ctx *ctx, const uint64_t *lwe_in, const uint6
                                const double *bskp, uint32_t n_steps, uint64_t *acc_out, uint64_t *lwe_out, uint32_t batch,
                                hipStream_t s) {
     fused1024_args A;
-    A.lwe_in = lwe_in; A.luts = luts; A.lut_idx = lut_idx; A.bskp = bskp; A.acc_out = acc_out; A.lwe_out = lwe_out;
-    A.n = ctx->prm.n; A.n_steps = n_steps; A.batch = batch; A.beta = ctx->prm.pbs_base_log;
+    slz_fused_fill_io(A, ctx, lwe_in, luts, lut_idx, bskp, n_steps, acc_out, lwe_out, batch);
     for (int q = 0; q < 2; q++) {
         A.rowA[q] = ctx->fused1024_rowA + (size_t)q * 64;
         A.rowB[q] = ctx->fused1024_rowB + (size_t)q * 15 * 64;
-        A.inv[q] = ctx->tab[q].inv;
-        A.post[q] = ctx->tab[q].post;
-        A.mod[q] = ctx->mod[q];
         for (int x = 0; x < 16; x++) A.tw_inv[q][x] = ctx->fused_scalars[q][1][x];
     }
-    A.p1inv_mod_p2 = ctx->p1inv_mod_p2;
     if (ctx->prm.k == 2) {
-        const uint32_t resident = 2u * 256u;           // six waves and 70 KiB of LDS per workgroup: two per compute unit
-        const uint32_t grid = batch < resident ? batch : resident;
+        const uint32_t grid = slz_fused_grid(batch, 2);    // six waves and 70 KiB of LDS per workgroup: two per compute unit
         hipLaunchKernelGGL((k_fused_blind_rotate_n1024<0, 2>), dim3(grid), dim3(384), G_LDS_DOUBLES(3) * sizeof(double), s, A);
     } else {
-        const uint32_t resident = G_WAVES * 256u;      // workgroups per compute unit x compute units
-        const uint32_t grid = batch < resident ? batch : resident;
+        const uint32_t grid = slz_fused_grid(batch, G_WAVES);
         if (A.beta == 23)
             hipLaunchKernelGGL((k_fused_blind_rotate_n1024<23, 1>), dim3(grid), dim3(G_THREADS), G_LDS_DOUBLES(2) * sizeof(double), s, A);
         else

@@ -15,6 +15,7 @@
 //      its accumulator words.
 #include "slz_internal.h"
 #include "slz_modarith.h"
+#include "slz_fused_common.h"
 #include <vector>
 
 #include "slz_wave_ntt.h"
@@ -24,23 +25,12 @@
 #define H_THREADS 512
 #define H_STAGE_OFF 1088u      // second half of a wave buffer: staging of 1024 accumulator words
 
-struct fused4096_args {
-    const uint64_t *lwe_in;
-    const uint64_t *luts;
-    const uint32_t *lut_idx;
-    const double *bskp;
-    uint64_t *acc_out;
-    uint64_t *lwe_out;
-    uint32_t n, n_steps, batch, beta;
+struct fused4096_args : slz_fused_io {
     const double *rowA[2];    // [2 blocks][64]      block twiddles of the stages with 1..32 sub-blocks
     const double *rowB[2];    // [2 blocks][31][64]  block twiddles of the last five forward stages, entry (k, lane)
-    const double *inv[2];     // [N]                 inv[t + j]: cyclic inverse twiddles
-    const double *post[2];    // [N]                 psi^-j / N
     double tw_fwd[2][2][32];  // [prime][block]: rowA entries below 32 (lane-uniform, read with scalar loads)
     double tw_inv[2][32];     // inv[t + j], t + j < 32
     double w_first[2];        // fwd[1]: the twiddle of the stage across the two blocks
-    slz_mod mod[2];
-    double p1inv_mod_p2;
 };
 
 template <int BETA>
@@ -272,23 +262,9 @@ int slz_fused4096_supported(const slz_params *p) {
 }
 
 int slz_fused4096_init(slz_ctx *ctx) {
-    // worst-case bounds of the fixed reduction schedule (units of p); everything must stay below 2^53 = 8 p
-    double a = 1e-6;
-    a += slz_mulmod_bound(a);                                        // the stage across the blocks, on digits
-    for (int s = 0; s < 6; s++) a += slz_mulmod_bound(a);            // fused_fwd: six stages, reduction
-    if (a > 7.5) return SLZ_E_UNSUPPORTED;
-    a = 0.5 + 1e-9;
-    for (int s = 0; s < 5; s++) a += slz_mulmod_bound(a);
-    if (a > 7.5 || 2 * slz_mulmod_bound(a) > 7.5) return SLZ_E_UNSUPPORTED;
-    a = 2.0 * (0.5 + 1e-9) * 2.0;
-    for (int s = 2; s < 5; s++) a += slz_mulmod_bound(a);
-    if (a > 7.5) return SLZ_E_UNSUPPORTED;
-    a = 0.5 + 1e-9;
-    for (int s = 5; s < 11; s++) a += slz_mulmod_bound(a);
-    if (a > 7.5) return SLZ_E_UNSUPPORTED;
-    a = 0.5 + 1e-9;                                                  // reduced, stage across the blocks, twist
-    a += slz_mulmod_bound(a);
-    if (slz_mulmod_bound(a) > 1.95) return SLZ_E_UNSUPPORTED;        // the CRT lift needs |r| < 2 p
+    // the stage across the blocks and six more on the digits, reduction, five more; two products summed; inverse 2 + 3
+    // stages, reduction, six stages, reduction, the stage across the blocks, twist
+    if (!slz_fused_schedule_ok(1, 6, 5, 2, 3, 6, true, 2)) return SLZ_E_UNSUPPORTED;
     int rc = slz_build_block_tables(ctx, 2048, &ctx->fused4096_rowA, &ctx->fused4096_rowB);
     if (rc != SLZ_OK) return rc;
     for (int q = 0; q < 2; q++) {
@@ -313,22 +289,16 @@ int slz_fused4096_blind_rotate(slz_ctx *ctx, const uint64_t *lwe_in, const uint6
                                const double *bskp, uint32_t n_steps, uint64_t *acc_out, uint64_t *lwe_out, uint32_t batch,
                                hipStream_t s) {
     fused4096_args A;
-    A.lwe_in = lwe_in; A.luts = luts; A.lut_idx = lut_idx; A.bskp = bskp; A.acc_out = acc_out; A.lwe_out = lwe_out;
-    A.n = ctx->prm.n; A.n_steps = n_steps; A.batch = batch; A.beta = ctx->prm.pbs_base_log;
+    slz_fused_fill_io(A, ctx, lwe_in, luts, lut_idx, bskp, n_steps, acc_out, lwe_out, batch);
     for (int q = 0; q < 2; q++) {
         A.rowA[q] = ctx->fused4096_rowA + (size_t)q * 2 * 64;
         A.rowB[q] = ctx->fused4096_rowB + (size_t)q * 2 * 31 * 64;
-        A.inv[q] = ctx->tab[q].inv;
-        A.post[q] = ctx->tab[q].post;
-        A.mod[q] = ctx->mod[q];
         for (int blk = 0; blk < 2; blk++)
             for (int x = 0; x < 32; x++) A.tw_fwd[q][blk][x] = ctx->fused4096_scalars[q][blk * 64 + x];
         for (int x = 0; x < 32; x++) A.tw_inv[q][x] = ctx->fused_scalars[q][1][x];
         A.w_first[q] = ctx->fused4096_w1[q];
     }
-    A.p1inv_mod_p2 = ctx->p1inv_mod_p2;
-    const uint32_t resident = 256u;                    // one workgroup (136 KiB of LDS, eight waves) per compute unit
-    const uint32_t grid = batch < resident ? batch : resident;
+    const uint32_t grid = slz_fused_grid(batch, 1);    // one workgroup (136 KiB of LDS, eight waves) per compute unit
     if (A.beta == 22)
         hipLaunchKernelGGL(k_fused_blind_rotate_n4096<22>, dim3(grid), dim3(H_THREADS), 8 * TBUF * sizeof(double), s, A);
     else

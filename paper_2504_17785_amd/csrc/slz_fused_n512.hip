@@ -17,6 +17,7 @@
 //   5. exchanges half of the residues with the wave of the other prime, CRT-lifts its words and accumulates.
 #include "slz_internal.h"
 #include "slz_modarith.h"
+#include "slz_fused_common.h"
 #include <vector>
 
 #include "slz_wave_ntt.h"
@@ -26,21 +27,10 @@
 #define P_STAGE_OFF 576u       // second half of a wave buffer: staging of 512 accumulator words
 #define P_LDS_DOUBLES(P) (2u * (P) * TBUF16 + 2u * 1024u)
 
-struct fused512_args {
-    const uint64_t *lwe_in;
-    const uint64_t *luts;
-    const uint32_t *lut_idx;
-    const double *bskp;
-    uint64_t *acc_out;
-    uint64_t *lwe_out;
-    uint32_t n, n_steps, batch, beta;
+struct fused512_args : slz_fused_io {
     const double *rowA[2];    // [64]      forward twiddles of the stages before the transposition, both halves
     const double *rowB[2];    // [15][64]  per-lane forward twiddles of the last four stages
-    const double *inv[2];     // [N]       inv[t + j]: cyclic inverse twiddles
-    const double *post[2];    // [N]       psi^-j / N
     double tw_inv[2][16];     // inv[t + j], t + j < 16
-    slz_mod mod[2];
-    double p1inv_mod_p2;
 };
 
 template <int K>
@@ -418,23 +408,13 @@ static int build_pair_tables(slz_ctx *ctx, double **dA, double **dB) {
 }
 
 int slz_fused512_init(slz_ctx *ctx) {
-    // worst-case bounds of the fixed reduction schedule (units of p); everything must stay below 2^53 = 8 p
-    double a = 1e-6;
-    for (int s = 0; s < 5; s++) a += slz_mulmod_bound(a);            // digits through the five stages before the reduction
-    if (a > 7.5) return SLZ_E_UNSUPPORTED;
-    a = 0.5 + 1e-9;
-    for (int s = 0; s < 4; s++) a += slz_mulmod_bound(a);
-    if (a > 7.5 || 4 * slz_mulmod_bound(a) > 7.5) return SLZ_E_UNSUPPORTED;   // four products summed (k = 3)
-    a = 2.0 * (0.5 + 1e-9) * 2.0;                                    // inverse: two multiply-free stages double the bound
-    for (int s = 2; s < 4; s++) a += slz_mulmod_bound(a);
-    if (a > 7.5) return SLZ_E_UNSUPPORTED;
-    a = 0.5 + 1e-9;
-    for (int s = 4; s < 9; s++) a += slz_mulmod_bound(a);
-    if (a > 7.5 || slz_mulmod_bound(a) > 1.95) return SLZ_E_UNSUPPORTED;      // the CRT lift needs |r| < 2 p after the twist
+    // five forward stages on the digits, reduction, four more; four products summed (k = 3); inverse 2 + 2 stages,
+    // reduction, five stages, twist
+    if (!slz_fused_schedule_ok(0, 5, 4, 4, 2, 5, false, 1)) return SLZ_E_UNSUPPORTED;
     int rc = build_pair_tables(ctx, &ctx->fused512_rowA, &ctx->fused512_rowB);
     if (rc != SLZ_OK) return rc;
-    for (int q = 0; q < 2; q++)
-        SLZ_HIP(hipMemcpy(ctx->fused_scalars[q][1], ctx->tab[q].inv, 32 * sizeof(double), hipMemcpyDeviceToHost));
+    rc = slz_fused_load_inv_scalars(ctx);
+    if (rc != SLZ_OK) return rc;
     SLZ_HIP(hipFuncSetAttribute((const void *)k_fused_blind_rotate_n512<1>, hipFuncAttributeMaxDynamicSharedMemorySize,
                                 P_LDS_DOUBLES(1) * sizeof(double)));
     SLZ_HIP(hipFuncSetAttribute((const void *)k_fused_blind_rotate_n512<3>, hipFuncAttributeMaxDynamicSharedMemorySize,
@@ -454,28 +434,20 @@ int slz_fused512_blind_rotate(slz_ctx *ctx, const uint64_t *lwe_in, const uint64
                               const double *bskp, uint32_t n_steps, uint64_t *acc_out, uint64_t *lwe_out, uint32_t batch,
                               hipStream_t s) {
     fused512_args A;
-    A.lwe_in = lwe_in; A.luts = luts; A.lut_idx = lut_idx; A.bskp = bskp; A.acc_out = acc_out; A.lwe_out = lwe_out;
-    A.n = ctx->prm.n; A.n_steps = n_steps; A.batch = batch; A.beta = ctx->prm.pbs_base_log;
+    slz_fused_fill_io(A, ctx, lwe_in, luts, lut_idx, bskp, n_steps, acc_out, lwe_out, batch);
     for (int q = 0; q < 2; q++) {
         A.rowA[q] = ctx->fused512_rowA + (size_t)q * 64;
         A.rowB[q] = ctx->fused512_rowB + (size_t)q * 15 * 64;
-        A.inv[q] = ctx->tab[q].inv;
-        A.post[q] = ctx->tab[q].post;
-        A.mod[q] = ctx->mod[q];
         for (int x = 0; x < 16; x++) A.tw_inv[q][x] = ctx->fused_scalars[q][1][x];
     }
-    A.p1inv_mod_p2 = ctx->p1inv_mod_p2;
     if (ctx->prm.pbs_level == 2) {
-        const uint32_t resident = 2u * 256u;
-        const uint32_t grid = batch < resident ? batch : resident;
+        const uint32_t grid = slz_fused_grid(batch, 2);
         hipLaunchKernelGGL(k_fused_blind_rotate_n512_l2, dim3(grid), dim3(256), P_LDS_DOUBLES(2) * sizeof(double), s, A);
     } else if (ctx->prm.k == 3) {
-        const uint32_t resident = 2u * 256u;           // four waves per workgroup, two waves per SIMD
-        const uint32_t grid = batch < resident ? batch : resident;
+        const uint32_t grid = slz_fused_grid(batch, 2);    // four waves per workgroup, two waves per SIMD
         hipLaunchKernelGGL(k_fused_blind_rotate_n512<3>, dim3(grid), dim3(256), P_LDS_DOUBLES(2) * sizeof(double), s, A);
     } else {
-        const uint32_t resident = 4u * 256u;           // two waves per workgroup
-        const uint32_t grid = batch < resident ? batch : resident;
+        const uint32_t grid = slz_fused_grid(batch, 4);    // two waves per workgroup
         hipLaunchKernelGGL(k_fused_blind_rotate_n512<1>, dim3(grid), dim3(128), P_LDS_DOUBLES(1) * sizeof(double), s, A);
     }
     SLZ_HIP(hipGetLastError());
