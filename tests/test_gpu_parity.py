@@ -829,8 +829,11 @@ def test_keyswitch_first_error_codes(slz, orc):
 @pytest.mark.parametrize("shape,batch", [(dict(n=5, N=2048, k=1, pbs_base_log=23, pbs_level=1, ks_base_log=4, ks_level=8), 40),
                                          (dict(n=3, N=1024, k=1, pbs_base_log=23, pbs_level=1), 9),
                                          (dict(n=6, N=256, k=2, pbs_base_log=8, pbs_level=2), 7),
-                                         (dict(n=2, N=16384, k=1, pbs_base_log=15, pbs_level=1), 70)],
-                         ids=["fused_n2048", "fused_n1024", "generic_k2", "large_n_two_lanes"])
+                                         (dict(n=2, N=16384, k=1, pbs_base_log=15, pbs_level=1), 70),
+                                         (dict(n=2, N=2048, k=1, pbs_base_log=23, pbs_level=1, ks_base_log=4, ks_level=8), 1100),
+                                         (dict(n=2, N=8192, k=1, pbs_base_log=15, pbs_level=2), 3)],
+                         ids=["fused_n2048", "fused_n1024", "generic_k2", "large_n_two_lanes", "fused_n2048_paced_rounds",
+                              "large_n_latency_kernels"])
 def test_lookup_replays_from_a_hip_graph(slz, orc, shape, batch):
     """A serving loop captures one lookup (bootstrapping + keyswitch) once and replays it: after a warm-up call (which makes
     the library's lazy allocations) the calls record nothing but kernels and event edges, and every replay on new inputs
