@@ -130,13 +130,15 @@ k_fused_blind_rotate_n2048(fused_args A) {
                 }
             }
             // 2. forward transform
-            fused_fwd(x, T, tw6, twA, fwdB, m, lane, z);
             // 3. row h of the GGSW times the digits: component h stays, component 1-h goes to the sibling.
-            //    Key words are fetched eight positions (two chunks of 2 x 8 doubles in flight) ahead.
-            {
-                double ks[2][8], ko[2][8];
+            //    Key words are fetched eight positions (two chunks of 2 x 8 doubles in flight) ahead, the first chunk from
+            //    inside the forward transform (before its last three stages).
+            double ks[2][8], ko[2][8];
+            fused_fwd(x, T, tw6, twA, fwdB, m, lane, z, [&]() {
 #pragma unroll
                 for (int i = 0; i < 8; i++) { ks[0][i] = ldl(ksib + 64 * i, lane * 8u); ko[0][i] = ldl(kown + 64 * i, lane * 8u); }
+            });
+            {
                 wave_sync();
 #pragma unroll
                 for (int ch = 0; ch < 4; ch++) {

@@ -111,8 +111,12 @@ __device__ __forceinline__ void bfly_nomul(double &a, double &b) {
 // digits to 4.81 p, one full reduction brings them back to p/2, five more stages end at 4.81 p.
 // tw6 (stage with stride 32) is loaded by the caller; twA = lane-uniform twiddles; the per-lane twiddles of the last
 // five stages are fetched here before the first stage starts.  z is an opaque zero (see the kernel).
+struct fwd_no_hook { __device__ __forceinline__ void operator()() const {} };
+// `hook` runs after the second of the last five stages: a place for the caller to request what it needs right after the
+// transform (three stages of arithmetic then cover the loads' latency).
+template <class Hook = fwd_no_hook>
 __device__ __forceinline__ void fused_fwd(double (&x)[32], double *T, const double (&tw6)[16], const double *twA,
-                                          const double *fwdB, slz_mod m, uint32_t lane, int z) {
+                                          const double *fwdB, slz_mod m, uint32_t lane, int z, Hook hook = Hook()) {
     const uint32_t hh = lane >> 5, l5 = lane & 31u;
     double twB[31];
 #pragma unroll
@@ -163,6 +167,7 @@ __device__ __forceinline__ void fused_fwd(double (&x)[32], double *T, const doub
 #pragma unroll
     for (int s = 0; s < 5; s++) {
         const int t = 16 >> s;
+        if (s == 2) { SCHED_FENCE(); hook(); SCHED_FENCE(); }
 #pragma unroll
         for (int g = 0; g < 4; g++) {
 #define FB_I(b) (((b) / t) * 2 * t + (b) % t)
