@@ -436,6 +436,13 @@ class Workload:
              "roofline": {"bound": "alu", "kernel": "blind rotation (slz_pbs_batch)", "achieved": achieved,
                           "peak": PEAK_ALU_TINSTR, "unit": "Tinstr/s", "frac": achieved / PEAK_ALU_TINSTR,
                           "traffic": stored_traffic(self.ctx.path, "%s_batch%d" % (p.name, batch))}}
+        # the same launch against the memory roofline, from the measured traffic past the L2s (large N: the accumulators and the
+        # intermediates of the three passes move through memory every step, and this bound is as close as the arithmetic one)
+        traffic = r["roofline"]["traffic"]
+        if traffic is not None:
+            gbps = traffic / (t["pbs_ms"] * 1e-3) / 1e9
+            r["memory_roofline"] = {"bound": "hbm", "achieved": gbps, "peak": 8000.0, "unit": "GB/s", "frac": gbps / 8000.0,
+                                    "note": "measured bytes past the L2s (not algorithmic bytes) / launch time"}
         # secondary kernels against their own bounds (whole entry point, helper kernels and launch gaps included)
         kN = p.k * p.N
         if p.ks_base_log <= 8 and kN % 32 == 0 and not generic and batch >= 16:
@@ -574,7 +581,7 @@ def main():
         "config": {"workload": rep["workload"], "path": rep["path"]},
     }
     for key in ("pbs_per_s", "keyswitch_per_s", "pbs_ms", "keyswitch_ms", "lincomb_ms", "bsk_prepared_bytes", "bsk_stream_GBps_min",
-                "roofline", "keyswitch_roofline", "lincomb_roofline"):
+                "roofline", "memory_roofline", "keyswitch_roofline", "lincomb_roofline"):
         if key in rep:
             result[key] = rep[key]
     if not args.no_cpu_baseline:

@@ -119,7 +119,7 @@ def test_config4_gadget_lincomb_pbs_keyswitch(slz, orc):
 def test_config3_first_eight_steps_uniform_key(slz, orc):
     # N = 32768, l = 2 (three-pass path: the accumulator does not fit on chip).  One oracle CMux of this size is 8.6e9
     # multiply-adds, so with a key of uniform words (every u64 pattern, the magnitudes the exactness bound is about) the
-    # first eight steps are compared on 16 sampled ciphertexts of the full batch of 256.
+    # first eight steps are compared on 32 sampled ciphertexts of the full batch of 256.
     p3 = synth.CONFIGS[3]
     p = p3.with_(n=8, name="cfg3_first_steps")
     batch = p3.batch
@@ -134,8 +134,8 @@ def test_config3_first_eight_steps_uniform_key(slz, orc):
     d_bsk = ctx.bsk_prepare(slz.to_device_u64(bsk))
     d_idx = torch.from_numpy(lut_idx.astype(np.int32)).cuda()
     d_cts, d_luts = slz.to_device_u64(cts), slz.to_device_u64(luts)
-    idx = np.unique(np.concatenate([np.linspace(0, batch - 1, 14).astype(np.int64), np.array([31, 32])]))   # both half chunks' edges
-    assert len(idx) == 16
+    idx = np.unique(np.concatenate([np.linspace(0, batch - 1, 30).astype(np.int64), np.array([31, 32])]))   # both half chunks' edges
+    assert len(idx) == 32
     got = slz.to_host_u64(ctx.blind_rotate_batch(d_cts, d_luts, d_idx, d_bsk, 8))
     want = orc.blind_rotate_batch(p, cts[idx], luts, lut_idx[idx], bsk, 8)
     assert np.array_equal(got[idx], want)
