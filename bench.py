@@ -1,4 +1,4 @@
-"""Benchmark of the hot path: one step = slz_pbs_batch + slz_keyswitch_batch over one batch of ciphertexts.
+"""Benchmark of the hot path: one step = slz_pbs_batch + slz_keyswitch_batch(_prepared) over one batch of ciphertexts.
 
 Prints ONE JSON line.  Headline workload: configuration 5 of the baseline, the largest single-GPU batch of the
 128-bit-shaped parameter set (16 384 LWE ciphertexts, 64 lookup tables, n=742, k=1, N=2048, PBS base 2^23 x 1 level,
@@ -371,6 +371,11 @@ class Workload:
         torch.cuda.synchronize()
         del d_bsk_std
         self.d_ksk = slz.to_device_u64(self.ksk)
+        # the keyswitching key in the matrix-core contraction's operand form (one-off, untimed, like the bootstrapping key);
+        # parameter sets or modes without that contraction keep the standard key
+        self.d_kskp = None
+        if p.ks_base_log <= 8 and (p.k * p.N) % 32 == 0 and not args.generic and not args.ksk_standard:
+            self.d_kskp = ctx.ksk_prepare(self.d_ksk)
         self.d_cts = slz.to_device_u64(cts)
         self.d_luts = slz.to_device_u64(self.luts)
         self.d_idx = torch.from_numpy(self.lut_idx.astype(np.int32)).cuda()
@@ -392,10 +397,16 @@ class Workload:
             for r in range(3):
                 self.ctx.lwe_lincomb_batch(self.lin[0][r], self.lin[1][r], out=self.lin[2][r])
 
+    def keyswitch(self):
+        if self.d_kskp is not None:
+            self.ctx.keyswitch_batch_prepared(self.d_big, self.d_kskp, out=self.d_small)
+        else:
+            self.ctx.keyswitch_batch(self.d_big, self.d_ksk, out=self.d_small)
+
     def step(self):
         self.lincomb()
         self.ctx.pbs_batch(self.d_cts, self.d_luts, self.d_idx, self.d_bskp, out=self.d_big)
-        self.ctx.keyswitch_batch(self.d_big, self.d_ksk, out=self.d_small)
+        self.keyswitch()
 
     def run(self, steps, warmup):
         """W untimed steps, then exactly K timed ones; per-call HIP events on the launch stream give the kernel split."""
@@ -411,7 +422,7 @@ class Workload:
             ev[k][1].record()
             self.ctx.pbs_batch(self.d_cts, self.d_luts, self.d_idx, self.d_bskp, out=self.d_big)
             ev[k][2].record()
-            self.ctx.keyswitch_batch(self.d_big, self.d_ksk, out=self.d_small)
+            self.keyswitch()
             ev[k][3].record()
         torch.cuda.synchronize()
         wall = time.perf_counter() - t0
@@ -431,6 +442,7 @@ class Workload:
              "pbs_plus_keyswitch_per_s": batch / (t["ms_per_step"] * 1e-3),
              "pbs_per_s": batch / (t["pbs_ms"] * 1e-3), "keyswitch_per_s": batch / (t["ks_ms"] * 1e-3),
              "ms_per_step": t["ms_per_step"], "pbs_ms": t["pbs_ms"], "keyswitch_ms": t["ks_ms"], "lincomb_ms": t["lin_ms"],
+             "keyswitch_key": "prepared" if self.d_kskp is not None else "standard",
              "bsk_prepared_bytes": prepared_bytes,
              "bsk_stream_GBps_min": prepared_bytes / (t["pbs_ms"] * 1e-3) / 1e9,
              "roofline": {"bound": "alu", "kernel": "blind rotation (slz_pbs_batch)", "achieved": achieved,
@@ -543,6 +555,8 @@ def main():
     ap.add_argument("--no-pacing", action="store_true", help="fused N = 2048 kernel: let the workgroups run free between ciphertexts")
     ap.add_argument("--large-n-block", type=int, default=0, help="large-N path: block size of the row pass, 1024 or 2048")
     ap.add_argument("--large-n-lanes", type=int, default=0, help="large-N path: 1 = one chunk at a time, 2 = two half chunks on two streams")
+    ap.add_argument("--ksk-standard", action="store_true",
+                    help="keyswitch with the standard key (slz_keyswitch_batch) instead of the prepared one")
     ap.add_argument("--calib-copy", action="store_true",
                     help="also run one plain device copy of 256 MiB (a known-size kernel to scale FETCH_SIZE/WRITE_SIZE by)")
     ap.add_argument("--gadget", choices=["matmul_rns", "matmul_highres", "sign_rns", "shift2msbs", "loss_deriv", "weight_update"], default=None,

@@ -147,6 +147,19 @@ int slz_blind_rotate_batch(slz_ctx *ctx, const uint64_t *lwe_in_dev, const uint6
 int slz_keyswitch_batch(slz_ctx *ctx, const uint64_t *lwe_in_dev, const uint64_t *ksk_dev,
                         uint64_t *lwe_out_dev, uint32_t batch, void *hip_stream);
 
+/* The keyswitching key in the form the matrix-core contraction consumes (one-off, untimed, like slz_bsk_prepare): every
+ * 64-bit key word as eight signed bytes b_p with word = sum_p b_p 2^(8p) (mod 2^64), laid out as the contraction's operands.
+ * ksk_dev as for slz_keyswitch_batch; dst_dev: caller-provided device memory, 16-byte aligned; with dst_dev == NULL only
+ * *dst_bytes is set (about 32 ceil((n+1)/32) kN l_ks bytes: the size of the key rounded up to 32 output words).
+ * SLZ_E_UNSUPPORTED when the parameter set does not use the matrix cores (keyswitch base above 2^8, or kN not a multiple
+ * of 32); SLZ_E_INVALID_ARG when *dst_bytes is too small. */
+int slz_ksk_prepare(slz_ctx *ctx, const uint64_t *ksk_dev, void *dst_dev, size_t *dst_bytes, void *hip_stream);
+
+/* slz_keyswitch_batch with the key from slz_ksk_prepare: same ciphertext layouts, same result bit for bit, without the
+ * recoding of the key inside the contraction.  Scratch and chunking as for slz_keyswitch_batch. */
+int slz_keyswitch_batch_prepared(slz_ctx *ctx, const uint64_t *lwe_in_dev, const void *ksk_prepared_dev,
+                                 uint64_t *lwe_out_dev, uint32_t batch, void *hip_stream);
+
 /* For callers that cannot allocate device memory (code under HIP graph capture, tight serving loops, harnesses that
  * forbid hipMalloc): slz_keyswitch_batch on the int8 matrix cores with its digit scratch in a fixed device array of
  * SLZ_KS_STATIC_SCRATCH_BYTES inside the library instead of a buffer of the context.  The call itself allocates and

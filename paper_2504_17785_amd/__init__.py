@@ -38,7 +38,8 @@ class SlzError(RuntimeError):
 _lib = None
 
 EXPORTS = ("slz_ctx_create", "slz_ctx_destroy", "slz_ctx_set_option", "slz_lut_encode", "slz_bsk_prepare",
-           "slz_pbs_batch", "slz_blind_rotate_batch", "slz_keyswitch_batch", "slz_keyswitch_batch_static", "slz_ks_pbs_batch", "slz_lwe_lincomb_batch",
+           "slz_pbs_batch", "slz_blind_rotate_batch", "slz_keyswitch_batch", "slz_keyswitch_batch_static", "slz_ksk_prepare", "slz_keyswitch_batch_prepared",
+           "slz_ks_pbs_batch", "slz_lwe_lincomb_batch",
            "slz_pbs_path", "slz_strerror", "slz_matmul_rns_luts", "slz_matmul_rns_workspace", "slz_matmul_rns",
            "slz_rns_luts", "slz_rns_workspace", "slz_rns2mrns", "slz_sign_rns",
            "slz_shift2msbs_luts", "slz_shift2msbs_workspace", "slz_shift2msbs_plus", "slz_shift2msbs_pm",
@@ -69,6 +70,8 @@ def lib():
         L.slz_blind_rotate_batch.argtypes = [vp, vp, vp, vp, u32, vp, u32, vp, u32, vp]
         L.slz_keyswitch_batch.argtypes = [vp, vp, vp, vp, u32, vp]
         L.slz_keyswitch_batch_static.argtypes = [vp, vp, vp, vp, u32, vp]
+        L.slz_ksk_prepare.argtypes = [vp, vp, vp, ctypes.POINTER(sz), vp]
+        L.slz_keyswitch_batch_prepared.argtypes = [vp, vp, vp, vp, u32, vp]
         L.slz_ks_pbs_batch.argtypes = [vp, vp, vp, vp, vp, u32, vp, vp, u32, vp]
         L.slz_lwe_lincomb_batch.argtypes = [vp, vp, vp, vp, u32, u32, u32, vp]
         L.slz_pbs_path.argtypes = [vp]
@@ -367,6 +370,36 @@ class Context:
         self._check_keys(ksk=ksk)
         _check(lib().slz_keyswitch_batch(self._h, _dev_u64(lwe_in, "lwe_in"), _dev_u64(ksk, "ksk"), _dev_u64(out, "out"),
                                          batch, _stream()), "slz_keyswitch_batch")
+        return out
+
+    def ksk_prepared_bytes(self) -> int:
+        need = ctypes.c_size_t(0)
+        _check(lib().slz_ksk_prepare(self._h, None, None, ctypes.byref(need), None), "slz_ksk_prepare(size)")
+        return need.value
+
+    def ksk_prepare(self, ksk):
+        """Standard keyswitching key (CUDA tensor, u64 bits) -> the key as operands of the matrix-core contraction (CUDA
+        uint8 tensor, library-private layout)."""
+        import torch
+        self._check_keys(ksk=ksk)
+        need = self.ksk_prepared_bytes()
+        dst = torch.empty(need, dtype=torch.uint8, device=ksk.device)
+        nb = ctypes.c_size_t(need)
+        _check(lib().slz_ksk_prepare(self._h, _dev_u64(ksk, "ksk"), dst.data_ptr(), ctypes.byref(nb), _stream()), "slz_ksk_prepare")
+        return dst
+
+    def keyswitch_batch_prepared(self, lwe_in, ksk_prepared, out=None):
+        import torch
+        batch = lwe_in.shape[0]
+        if out is None:
+            out = torch.empty((batch, self.p.n + 1), dtype=torch.int64, device=lwe_in.device)
+        self._big(lwe_in, "lwe_in")
+        self._small(out, "out", batch)
+        if not ksk_prepared.is_cuda or not ksk_prepared.is_contiguous() or \
+                ksk_prepared.numel() * ksk_prepared.element_size() < self.ksk_prepared_bytes():
+            raise ValueError("ksk_prepared: need the contiguous CUDA tensor that ksk_prepare returned")
+        _check(lib().slz_keyswitch_batch_prepared(self._h, _dev_u64(lwe_in, "lwe_in"), ksk_prepared.data_ptr(), _dev_u64(out, "out"),
+                                                  batch, _stream()), "slz_keyswitch_batch_prepared")
         return out
 
     def keyswitch_batch_static(self, lwe_in, ksk, out):

@@ -257,6 +257,25 @@ extern "C" int slz_keyswitch_batch(slz_ctx *ctx, const uint64_t *lwe_in_dev, con
     return slz_keyswitch_launch(ctx, lwe_in_dev, ksk_dev, lwe_out_dev, batch, (hipStream_t)hip_stream);
 }
 
+extern "C" int slz_ksk_prepare(slz_ctx *ctx, const uint64_t *ksk_dev, void *dst_dev, size_t *dst_bytes, void *hip_stream) {
+    if (!ctx || !dst_bytes) return SLZ_E_INVALID_ARG;
+    const size_t need = slz_ksm_prepared_bytes(&ctx->prm);
+    if (need == 0) return SLZ_E_UNSUPPORTED;
+    if (!dst_dev) { *dst_bytes = need; return SLZ_OK; }
+    if (!ksk_dev || *dst_bytes < need || misaligned(ksk_dev) || misaligned(dst_dev)) return SLZ_E_INVALID_ARG;
+    return slz_ksm_prepare(ctx, ksk_dev, dst_dev, (hipStream_t)hip_stream);
+}
+
+extern "C" int slz_keyswitch_batch_prepared(slz_ctx *ctx, const uint64_t *lwe_in_dev, const void *ksk_prepared_dev,
+                                            uint64_t *lwe_out_dev, uint32_t batch, void *hip_stream) {
+    if (!ctx || !lwe_in_dev || !ksk_prepared_dev || !lwe_out_dev || batch == 0) return SLZ_E_INVALID_ARG;
+    if (misaligned8(lwe_in_dev) || misaligned(ksk_prepared_dev) || misaligned8(lwe_out_dev)) return SLZ_E_INVALID_ARG;
+    const slz_params &p = ctx->prm;
+    if (slz_ksm_prepared_bytes(&p) == 0) return SLZ_E_UNSUPPORTED;
+    slz_ks_init_launch(lwe_in_dev, lwe_out_dev, p.k * p.N, p.n, batch, (hipStream_t)hip_stream);
+    return slz_ksm_launch(ctx, lwe_in_dev, nullptr, ksk_prepared_dev, lwe_out_dev, batch, (hipStream_t)hip_stream);
+}
+
 // Keyswitch first, then bootstrapping, on ciphertexts under the big key.  The small ciphertexts between the two live in a
 // scratch buffer of the context (max_batch rows, allocated on first use); everything is ordered on the one stream.
 extern "C" int slz_ks_pbs_batch(slz_ctx *ctx, const uint64_t *lwe_in_dev, const uint64_t *ksk_dev, const uint64_t *luts_dev,

@@ -145,8 +145,10 @@ void slz_ks_init_launch(const uint64_t *lwe_in, uint64_t *lwe_out, uint32_t kN, 
 // matrix-core keyswitch (slz_keyswitch_mfma.hip); lwe_out must already hold (0, .., 0, b')
 int slz_ksm_supported(const slz_params *p);
 void slz_ksm_destroy(slz_ctx *ctx);
-int slz_ksm_launch(slz_ctx *ctx, const uint64_t *lwe_in, const uint64_t *ksk, uint64_t *lwe_out, uint32_t batch,
+int slz_ksm_launch(slz_ctx *ctx, const uint64_t *lwe_in, const uint64_t *ksk, const void *kskp, uint64_t *lwe_out, uint32_t batch,
                    hipStream_t s);
+size_t slz_ksm_prepared_bytes(const slz_params *p);
+int slz_ksm_prepare(slz_ctx *ctx, const uint64_t *ksk, void *dst, hipStream_t s);
 // matrix-core linear combination (slz_lincomb_mfma.hip)
 void slz_lcm_destroy(slz_ctx *ctx);
 int slz_lcm_launch(slz_ctx *ctx, const uint64_t *cts, const int32_t *w, uint64_t *out, uint32_t G, uint32_t J, uint32_t O,

@@ -108,7 +108,7 @@ int slz_keyswitch_launch(slz_ctx *ctx, const uint64_t *lwe_in, const uint64_t *k
     // n = 1024, N = 32768: 0.33 ms against 0.27 ms), where the scalar kernel's plain row streaming wins.
     const size_t key_bytes = (size_t)kN * p.ks_level * (n + 1) * 8;
     if (!ctx->force_generic && (batch >= KS_MFMA_MIN_BATCH || key_bytes < ((size_t)512 << 20)) && slz_ksm_supported(&p)) {
-        int rc = slz_ksm_launch(ctx, lwe_in, ksk, lwe_out, batch, s);
+        int rc = slz_ksm_launch(ctx, lwe_in, ksk, nullptr, lwe_out, batch, s);
         if (rc != SLZ_E_UNSUPPORTED) return rc;
     }
     uint32_t xt = (n + 1 + KS_THREADS - 1) / KS_THREADS, ct = (batch + KS_TB - 1) / KS_TB;

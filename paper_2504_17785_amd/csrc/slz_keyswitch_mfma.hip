@@ -60,9 +60,46 @@ k_ksm_digits(const uint64_t *__restrict__ lwe_in, v4i *__restrict__ dig, uint32_
     }
 }
 
+// ---- key in operand form ----------------------------------------------------------------------------------------------
+// The contraction's B operands, ready to be copied into LDS: P[x tile][block kb][half][plane p][x in tile] (16 bytes):
+// byte t = signed byte p of the key word of row 32 kb + 16 half + t, output word 32 (x tile) + x.  Words past n and
+// blocks past the last row (the block count is padded to a multiple of 2 KM_IT_KB) are zero.  One iteration of a
+// workgroup (KM_IT_KB blocks of one x tile) is KM_BUF_V4 consecutive entries, in the order of its LDS buffer.
+#define KM_KB_PAD (2 * KM_IT_KB)
+static inline uint32_t ksm_padded_blocks(uint32_t n_kb) { return (n_kb + KM_KB_PAD - 1) / KM_KB_PAD * KM_KB_PAD; }
+__device__ __forceinline__ uint32_t ksm_padded_blocks_dev(uint32_t n_kb) { return (n_kb + KM_KB_PAD - 1) / KM_KB_PAD * KM_KB_PAD; }
+
+__global__ void __launch_bounds__(256)
+k_ksk_prepare(const uint64_t *__restrict__ ksk, v4i *__restrict__ out, uint32_t kN, uint32_t n, uint32_t l, uint32_t n_kb,
+              uint32_t n_kb_pad, uint32_t x_tiles) {
+    const uint32_t xl = threadIdx.x % 32, half = (threadIdx.x / 32) % 2;
+    const uint32_t kb = blockIdx.x * 4 + threadIdx.x / 64, xt = blockIdx.y;
+    if (kb >= n_kb_pad) return;
+    const uint32_t x = xt * 32 + xl, width = n + 1;
+    uint64_t w[16];
+#pragma unroll
+    for (int t = 0; t < 16; t++) {
+        const uint32_t rho = 32 * kb + 16 * half + t;             // level-major row: rho = j kN + i
+        const uint32_t j = rho / kN, i = rho % kN;
+        w[t] = (kb < n_kb && x < width) ? slz_signed_bytes(ksk[((size_t)i * l + j) * width + x]) : 0ull;
+    }
+    uint64_t lo[8], hi[8], pl[8], ph[8];
+#pragma unroll
+    for (int t = 0; t < 8; t++) { lo[t] = w[t]; hi[t] = w[8 + t]; }
+    slz_byte_planes(lo, pl);
+    slz_byte_planes(hi, ph);
+    v4i *dst = out + (((size_t)xt * n_kb_pad + kb) * 2 + half) * 8 * 32 + xl;
+#pragma unroll
+    for (int p = 0; p < 8; p++) {
+        v4i o = {(int)(uint32_t)pl[p], (int)(uint32_t)(pl[p] >> 32), (int)(uint32_t)ph[p], (int)(uint32_t)(ph[p] >> 32)};
+        dst[p * 32] = o;
+    }
+}
+
 // ---- contraction ---------------------------------------------------------------------------------------------------
 struct ksm_args {
     const uint64_t *ksk;
+    const v4i *kskp;        // prepared key (k_ksk_prepare) or null
     const v4i *dig;
     uint64_t *out;
     uint32_t kN, n, l, batch;
@@ -73,6 +110,9 @@ struct ksm_args {
     uint32_t per_xcd;
 };
 
+// PREP: the key comes in operand form (A.kskp) and goes from global memory to LDS as it is; otherwise every thread recodes
+// eight words of the standard key per iteration.
+template <bool PREP>
 __global__ void __launch_bounds__(KM_THREADS) __attribute__((amdgpu_waves_per_eu(2, 2)))
 k_ksm_main(ksm_args A) {
     __shared__ v4i lds[2 * KM_BUF_V4];                              // 64 KiB
@@ -80,9 +120,21 @@ k_ksm_main(ksm_args A) {
     // it share a segment of the key and neighbouring output words, which its L2 then serves
     const uint32_t item = (blockIdx.x % 8) * A.per_xcd + blockIdx.x / 8;
     if (blockIdx.x / 8 >= A.per_xcd || item >= A.total) return;
-    const uint32_t cg = item % A.ct_groups;
-    const uint32_t xt = (item / A.ct_groups) % A.x_tiles;
-    const uint32_t seg = item / (A.ct_groups * A.x_tiles);
+    // inside a segment the order is (block of 8 ciphertext groups, x tile, group in the block): the 64 workgroups resident on
+    // an XCD are then about 8 groups x 8 x tiles, and its L2 sees each of their digit and key streams once instead of the
+    // digits of 64 groups against one x tile (the digit operands are the larger stream)
+    const uint32_t per_seg = A.ct_groups * A.x_tiles;
+    const uint32_t seg = item / per_seg, r = item % per_seg;
+    const uint32_t n_full = A.ct_groups / 8, blk = 8 * A.x_tiles;
+    uint32_t cg, xt;
+    if (r < n_full * blk) {
+        cg = (r / blk) * 8 + r % 8;
+        xt = (r % blk) / 8;
+    } else {                                                        // the last, narrower block
+        const uint32_t rr = r - n_full * blk, w = A.ct_groups - n_full * 8;
+        cg = n_full * 8 + rr % w;
+        xt = rr / w;
+    }
     const uint32_t lane = threadIdx.x % 64;
     const uint32_t wave = __builtin_amdgcn_readfirstlane(threadIdx.x / 64);
     const uint32_t tile = cg * KM_WAVES + wave;
@@ -108,7 +160,24 @@ k_ksm_main(ksm_args A) {
     uint64_t kw0[8], kw1[8];
     bool ok0, ok1;
     v4i an0[KM_IT_KB], an1[KM_IT_KB];
+    // operand form: the iteration's KM_BUF_V4 entries are consecutive; a thread moves entries tid + KM_THREADS u (the same
+    // eight registers hold them as four 16-byte values)
+    const uint32_t kb_pad = ksm_padded_blocks_dev(A.n_kb);
+    const v4i *pkey = PREP ? A.kskp + (size_t)xt * kb_pad * (2 * 8 * 32) + threadIdx.x : nullptr;
     auto load_key = [&](uint64_t (&kw)[8], bool &ok, uint32_t it) {
+        if (PREP) {
+            // blocks up to the padded count exist (zero past the last row); past that the read is clamped and unused
+            const uint32_t itc = min(it, kb_pad - KM_IT_KB);
+            const v4i *src = pkey + (size_t)itc * (2 * 8 * 32);
+#pragma unroll
+            for (int u = 0; u < 4; u++) {
+                const v4i v = src[u * KM_THREADS];
+                kw[2 * u] = (uint64_t)(uint32_t)v[0] | ((uint64_t)(uint32_t)v[1] << 32);
+                kw[2 * u + 1] = (uint64_t)(uint32_t)v[2] | ((uint64_t)(uint32_t)v[3] << 32);
+            }
+            ok = true;
+            return;
+        }
         ok = x_ok && (it + oct / 4 < kb_end);
         const uint64_t *src = A.ksk + (ok ? ((size_t)i * A.l + j) * width + x : (size_t)0);
 #pragma unroll
@@ -132,7 +201,14 @@ k_ksm_main(ksm_args A) {
     uint32_t buf = 0;
     auto body = [&](uint64_t (&kw)[8], bool &ok, v4i (&an)[KM_IT_KB], uint32_t it) {
         // recode to signed bytes, transpose 8 rows x 8 planes, park the plane operands in LDS
-        {
+        if (PREP) {
+            uint64_t *dst = reinterpret_cast<uint64_t *>(lds + buf * KM_BUF_V4 + threadIdx.x);
+#pragma unroll
+            for (int u = 0; u < 4; u++) {
+                dst[u * KM_THREADS * 2] = kw[2 * u];
+                dst[u * KM_THREADS * 2 + 1] = kw[2 * u + 1];
+            }
+        } else {
             uint64_t w[8], plane[8];
 #pragma unroll
             for (int t = 0; t < 8; t++) w[t] = ok ? slz_signed_bytes(kw[t]) : 0ull;
@@ -200,12 +276,13 @@ void slz_ksm_destroy(slz_ctx *ctx) {
 
 // The launches of one keyswitch given its digit scratch (`dig`: room for max_tiles 32-ciphertext tiles).  `lwe_out` must
 // already hold (0, .., 0, b').
-static int ksm_run(const slz_params &p, void *dig, uint32_t max_tiles, const uint64_t *lwe_in, const uint64_t *ksk,
+static int ksm_run(const slz_params &p, void *dig, uint32_t max_tiles, const uint64_t *lwe_in, const uint64_t *ksk, const void *kskp,
                    uint64_t *lwe_out, uint32_t batch, hipStream_t s) {
     const uint32_t kN = p.k * p.N;
     const uint32_t n_kb = (uint32_t)((uint64_t)p.ks_level * kN / 32);
     ksm_args A;
     A.ksk = ksk;
+    A.kskp = (const v4i *)kskp;
     A.dig = (const v4i *)dig;
     A.kN = kN; A.n = p.n; A.l = p.ks_level;
     A.n_kb = n_kb;
@@ -232,14 +309,35 @@ static int ksm_run(const slz_params &p, void *dig, uint32_t max_tiles, const uin
         A.per_xcd = (A.total + 7) / 8;
         hipLaunchKernelGGL(k_ksm_digits, dim3((kN / 16 + 7) / 8, A.n_tiles), dim3(256), 0, s,
                            lwe_in + (size_t)c0 * (kN + 1), (v4i *)dig, kN, p.ks_base_log, p.ks_level, nb, n_kb);
-        hipLaunchKernelGGL(k_ksm_main, dim3(A.per_xcd * 8), dim3(KM_THREADS), 0, s, A);
+        if (kskp) hipLaunchKernelGGL(k_ksm_main<true>, dim3(A.per_xcd * 8), dim3(KM_THREADS), 0, s, A);
+        else hipLaunchKernelGGL(k_ksm_main<false>, dim3(A.per_xcd * 8), dim3(KM_THREADS), 0, s, A);
     }
     SLZ_HIP(hipGetLastError());
     return SLZ_OK;
 }
 
-// `lwe_out` must already hold (0, .., 0, b').
-int slz_ksm_launch(slz_ctx *ctx, const uint64_t *lwe_in, const uint64_t *ksk, uint64_t *lwe_out, uint32_t batch, hipStream_t s) {
+// Size of the key in operand form, 0 when the parameter set does not use the matrix cores.
+size_t slz_ksm_prepared_bytes(const slz_params *p) {
+    if (!slz_ksm_supported(p)) return 0;
+    const uint64_t n_kb64 = (uint64_t)p->ks_level * p->k * p->N / 32;
+    if (n_kb64 > (1u << 26)) return 0;
+    const size_t x_tiles = (p->n + 1 + 31) / 32;
+    return x_tiles * ksm_padded_blocks((uint32_t)n_kb64) * (2 * 8 * 32) * sizeof(v4i);
+}
+
+int slz_ksm_prepare(slz_ctx *ctx, const uint64_t *ksk, void *dst, hipStream_t s) {
+    const slz_params &p = ctx->prm;
+    const uint32_t kN = p.k * p.N, n_kb = (uint32_t)((uint64_t)p.ks_level * kN / 32), n_kb_pad = ksm_padded_blocks(n_kb);
+    const uint32_t x_tiles = (p.n + 1 + 31) / 32;
+    hipLaunchKernelGGL(k_ksk_prepare, dim3((n_kb_pad + 3) / 4, x_tiles), dim3(256), 0, s, ksk, (v4i *)dst, kN, p.n, p.ks_level, n_kb,
+                       n_kb_pad, x_tiles);
+    SLZ_HIP(hipGetLastError());
+    return SLZ_OK;
+}
+
+// `lwe_out` must already hold (0, .., 0, b').  Exactly one of ksk (standard form) and kskp (operand form) is given.
+int slz_ksm_launch(slz_ctx *ctx, const uint64_t *lwe_in, const uint64_t *ksk, const void *kskp, uint64_t *lwe_out, uint32_t batch,
+                   hipStream_t s) {
     const slz_params &p = ctx->prm;
     const uint64_t n_kb64 = (uint64_t)p.ks_level * p.k * p.N / 32;
     if (n_kb64 > (1u << 26)) return SLZ_E_UNSUPPORTED;
@@ -247,7 +345,7 @@ int slz_ksm_launch(slz_ctx *ctx, const uint64_t *lwe_in, const uint64_t *ksk, ui
     if (!ctx->ks_dig) {     // digit scratch, sized for max_batch (larger batches go through in chunks)
         if (slz_scratch_alloc(&ctx->ks_dig, (size_t)max_tiles * n_kb64 * 1024) != SLZ_OK) return SLZ_E_NOMEM;
     }
-    return ksm_run(p, ctx->ks_dig, max_tiles, lwe_in, ksk, lwe_out, batch, s);
+    return ksm_run(p, ctx->ks_dig, max_tiles, lwe_in, ksk, kskp, lwe_out, batch, s);
 }
 
 // ---- the variant that allocates nothing ------------------------------------------------------------------------------
@@ -281,5 +379,5 @@ extern "C" int slz_keyswitch_batch_static(slz_ctx *ctx, const uint64_t *lwe_in_d
     slz_ks_init_launch(lwe_in_dev, lwe_out_dev, p.k * p.N, p.n, batch, s);
     // every digit slot of the tiles in use is rewritten by k_ksm_digits (ciphertexts past the batch get zeros), so the
     // contents the previous call left behind are never read
-    return ksm_run(p, scratch_ptr[dev], (uint32_t)tiles, lwe_in_dev, ksk_dev, lwe_out_dev, batch, s);
+    return ksm_run(p, scratch_ptr[dev], (uint32_t)tiles, lwe_in_dev, ksk_dev, nullptr, lwe_out_dev, batch, s);
 }

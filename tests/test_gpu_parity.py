@@ -151,6 +151,58 @@ def test_matrix_core_keyswitch_extreme_bytes_and_digits(slz, orc):
     assert np.array_equal(got, orc.keyswitch_batch(p, cts, ksk))
 
 
+@pytest.mark.parametrize("batch,k,N,n,beta,l", [(16, 1, 32, 5, 8, 8), (300, 3, 32, 100, 1, 7), (65, 1, 512, 31, 7, 9),
+                                                 (257, 1, 256, 32, 4, 16), (1024, 1, 1024, 63, 2, 3), (33, 2, 64, 64, 6, 1),
+                                                 (1, 1, 64, 10, 4, 3), (37, 1, 2048, 742, 3, 5), (70, 3, 32, 40, 3, 5)])
+def test_keyswitch_with_prepared_key_matches_oracle(slz, orc, batch, k, N, n, beta, l):
+    # the key recoded once into the contraction's operands: row-block counts that are and are not multiples of eight
+    # (the prepared key is zero-padded), ragged word and ciphertext tiles, one ciphertext, chunks of a smaller context
+    p = tiny(n=n, N=N, k=k, ks_base_log=beta, ks_level=l)
+    kN = k * N
+    ksk = synth.raw_words(p, "raw_ksk", kN * l * (n + 1)).reshape(kN, l, n + 1)
+    cts = synth.raw_words(p, "raw_ct", batch * (kN + 1)).reshape(batch, kN + 1)
+    want = orc.keyswitch_batch(p, cts, ksk)
+    d_cts, d_ksk = slz.to_device_u64(cts), slz.to_device_u64(ksk)
+    ctx = slz.Context(p, batch)
+    kskp = ctx.ksk_prepare(d_ksk)
+    assert kskp.numel() == ctx.ksk_prepared_bytes() and ctx.ksk_prepared_bytes() % 8192 == 0
+    got = ctx.keyswitch_batch_prepared(d_cts, kskp)
+    assert np.array_equal(slz.to_host_u64(got), want)
+    assert torch.equal(got, ctx.keyswitch_batch(d_cts, d_ksk))
+    ctx_small = slz.Context(p, 40)
+    assert np.array_equal(slz.to_host_u64(ctx_small.keyswitch_batch_prepared(d_cts, kskp)), want)
+
+
+def test_keyswitch_with_prepared_key_extreme_bytes_and_errors(slz, orc):
+    p = tiny(n=70, N=256, k=1, ks_base_log=8, ks_level=8)
+    kN, l, n, batch = 256, 8, 70, 48
+    pats = np.array([0x8080808080808080, 0x7f7f7f7f7f7f7f7f, 0xffffffffffffffff, 0x0000000000000000, 0x807f807f807f807f,
+                     0x7f807f807f807f80, 0xff7fff80007f0080, 0x0100000000000080], dtype=np.uint64)
+    ksk = pats[(np.arange(kN * l * (n + 1)) * 5 // 3) % len(pats)].reshape(kN, l, n + 1)
+    cts = pats[(np.arange(batch * (kN + 1)) // 7) % len(pats)].reshape(batch, kN + 1)
+    ksk[:, :, 0] = np.uint64(0x8080808080808080)
+    ksk[:, :, 1] = np.uint64(0x7f7f7f7f7f7f7f7f)
+    ctx = slz.Context(p, batch)
+    d_cts, d_ksk = slz.to_device_u64(cts), slz.to_device_u64(ksk)
+    kskp = ctx.ksk_prepare(d_ksk)
+    assert np.array_equal(slz.to_host_u64(ctx.keyswitch_batch_prepared(d_cts, kskp)), orc.keyswitch_batch(p, cts, ksk))
+    L = slz.lib()
+    out = torch.zeros((batch, n + 1), dtype=torch.int64, device="cuda")
+    import ctypes
+    small = ctypes.c_size_t(ctx.ksk_prepared_bytes() - 1)
+    assert L.slz_ksk_prepare(ctx._h, d_ksk.data_ptr(), kskp.data_ptr(), ctypes.byref(small), None) == slz.SLZ_E_INVALID_ARG
+    assert L.slz_ksk_prepare(ctx._h, d_ksk.data_ptr(), kskp.data_ptr(), None, None) == slz.SLZ_E_INVALID_ARG
+    assert L.slz_keyswitch_batch_prepared(ctx._h, d_cts.data_ptr(), None, out.data_ptr(), batch, None) == slz.SLZ_E_INVALID_ARG
+    assert L.slz_keyswitch_batch_prepared(ctx._h, d_cts.data_ptr(), kskp.data_ptr() + 8, out.data_ptr(), batch, None) == slz.SLZ_E_INVALID_ARG
+    assert L.slz_keyswitch_batch_prepared(ctx._h, d_cts.data_ptr(), kskp.data_ptr(), out.data_ptr(), 0, None) == slz.SLZ_E_INVALID_ARG
+    # a keyswitch base above 2^8 has no matrix-core form
+    wide = slz.Context(tiny(n=20, N=64, k=1, ks_base_log=12, ks_level=5), 4)
+    need = ctypes.c_size_t(0)
+    assert L.slz_ksk_prepare(wide._h, None, None, ctypes.byref(need), None) == slz.SLZ_E_UNSUPPORTED
+    assert L.slz_keyswitch_batch_prepared(wide._h, d_cts.data_ptr(), kskp.data_ptr(), out.data_ptr(), 4, None) == slz.SLZ_E_UNSUPPORTED
+    torch.cuda.synchronize()
+
+
 def _lincomb_weights(p, J, O, kind):
     raw = synth.words(p.seed, "weights", J * O).view(np.int64)
     if kind == "small":          # residue-sized, as in the matmul gadget: one byte plane
