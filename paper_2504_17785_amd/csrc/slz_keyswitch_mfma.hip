@@ -23,40 +23,56 @@
 // dig[tile][kb][lane] (16 bytes): the A operand of lane `lane` for 32-row block kb of 32-ciphertext tile `tile`:
 // ciphertext 32 tile + lane % 32, rows 32 kb + 16 (lane / 32) + t for byte t.  Ciphertexts past the batch get zero digits.
 // Signed digits without a carry chain: with H = sum_j (B/2) B^(l-j), digit j of v is ((v + H) >> beta (l-j)) mod B - B/2.
+// A workgroup takes 32 ciphertexts x 128 mask words: every wave reads whole 512-byte runs of a ciphertext, the digit bytes
+// are turned through LDS (rows of 128 + 16 bytes: the 16-byte reads of 8 neighbouring lanes then cover all banks), and
+// every store instruction writes one 1 KiB operand block.
+#define KD_WORDS 128
+#define KD_PITCH (KD_WORDS + 16)
+#define KD_LEVELS 8                     // levels turned through LDS at a time
 __global__ void __launch_bounds__(256)
 k_ksm_digits(const uint64_t *__restrict__ lwe_in, v4i *__restrict__ dig, uint32_t kN, uint32_t beta, uint32_t l, uint32_t batch,
              uint32_t n_kb) {
-    const uint32_t cin = threadIdx.x % 32;
-    const uint32_t g16 = blockIdx.x * 8 + threadIdx.x / 32;     // group of 16 mask words
-    const uint32_t tile = blockIdx.y;
-    if (g16 >= kN / 16) return;
-    const uint32_t c = tile * 32 + cin;
+    __shared__ __attribute__((aligned(16))) unsigned char L[KD_LEVELS * 32 * KD_PITCH];
+    const uint32_t lane = threadIdx.x % 64, wave = threadIdx.x / 64;
+    const uint32_t w0 = blockIdx.x * KD_WORDS, tile = blockIdx.y;
+    const uint32_t n_blk = min((kN - w0) / 32u, (uint32_t)KD_WORDS / 32u);    // 32-word blocks of this workgroup (kN % 32 == 0)
     const uint32_t bits = beta * l;
     const uint32_t half_b = 1u << (beta - 1);
     uint64_t H = 0;
     for (uint32_t j = 0; j < l; j++) H |= (uint64_t)half_b << (beta * j);
-    uint64_t v[16];
+    // wave `wave` reads ciphertexts 8 wave .. 8 wave + 7 of the tile, lane words w0 + lane and w0 + 64 + lane
+    uint64_t v[8][2];
 #pragma unroll
-    for (int t = 0; t < 16; t++) {
-        uint64_t a = c < batch ? lwe_in[(size_t)c * (kN + 1) + 16 * g16 + t] : 0ull;
-        v[t] = slz_round_top_bits(a, bits) + H;
-    }
-    for (uint32_t jj = 0; jj < l; jj++) {                       // level jj + 1, most significant first
-        const uint32_t sh = beta * (l - 1 - jj);
-        uint32_t wds[4];
+    for (int q = 0; q < 8; q++) {
+        const uint32_t c = tile * 32 + 8 * wave + q;
 #pragma unroll
-        for (int q = 0; q < 4; q++) {
-            uint32_t wd = 0;
-#pragma unroll
-            for (int t = 0; t < 4; t++) {
-                uint32_t u = (uint32_t)(v[4 * q + t] >> sh) & (2 * half_b - 1);
-                wd |= ((u - half_b) & 0xffu) << (8 * t);
-            }
-            wds[q] = wd;
+        for (int h = 0; h < 2; h++) {
+            const uint32_t w = w0 + 64 * h + lane;
+            const uint64_t a = (c < batch && w < kN) ? lwe_in[(size_t)c * (kN + 1) + w] : 0ull;
+            v[q][h] = slz_round_top_bits(a, bits) + H;
         }
-        v4i o = {(int)wds[0], (int)wds[1], (int)wds[2], (int)wds[3]};
-        const uint32_t kb = (jj * kN + 16 * g16) / 32;
-        dig[((size_t)tile * n_kb + kb) * 64 + cin + 32 * (g16 & 1)] = o;
+    }
+    for (uint32_t j0 = 0; j0 < l; j0 += KD_LEVELS) {
+        const uint32_t nj = min(l - j0, (uint32_t)KD_LEVELS);
+        if (j0) __syncthreads();                                    // the previous group has been read
+        for (uint32_t jj = 0; jj < nj; jj++) {                     // level j0 + jj + 1, most significant first
+            const uint32_t sh = beta * (l - 1 - (j0 + jj));
+#pragma unroll
+            for (int q = 0; q < 8; q++)
+#pragma unroll
+                for (int h = 0; h < 2; h++) {
+                    const uint32_t u = (uint32_t)(v[q][h] >> sh) & (2 * half_b - 1);
+                    L[(jj * 32 + 8 * wave + q) * KD_PITCH + 64 * h + lane] = (unsigned char)(u - half_b);
+                }
+        }
+        __syncthreads();
+        // operand blocks (level, 32-word block) of this group, dealt to the waves; lane = ciphertext + 32 half
+        for (uint32_t ob = wave; ob < nj * n_blk; ob += 4) {
+            const uint32_t jj = ob / n_blk, kbl = ob % n_blk;
+            const v4i o = *reinterpret_cast<const v4i *>(&L[(jj * 32 + lane % 32) * KD_PITCH + 32 * kbl + 16 * (lane / 32)]);
+            const uint32_t kb = ((j0 + jj) * kN + w0) / 32 + kbl;
+            dig[((size_t)tile * n_kb + kb) * 64 + lane] = o;
+        }
     }
 }
 
@@ -307,7 +323,7 @@ static int ksm_run(const slz_params &p, void *dig, uint32_t max_tiles, const uin
         if (total > (1u << 30)) return SLZ_E_UNSUPPORTED;
         A.total = (uint32_t)total;
         A.per_xcd = (A.total + 7) / 8;
-        hipLaunchKernelGGL(k_ksm_digits, dim3((kN / 16 + 7) / 8, A.n_tiles), dim3(256), 0, s,
+        hipLaunchKernelGGL(k_ksm_digits, dim3((kN + KD_WORDS - 1) / KD_WORDS, A.n_tiles), dim3(256), 0, s,
                            lwe_in + (size_t)c0 * (kN + 1), (v4i *)dig, kN, p.ks_base_log, p.ks_level, nb, n_kb);
         if (kskp) hipLaunchKernelGGL(k_ksm_main<true>, dim3(A.per_xcd * 8), dim3(KM_THREADS), 0, s, A);
         else hipLaunchKernelGGL(k_ksm_main<false>, dim3(A.per_xcd * 8), dim3(KM_THREADS), 0, s, A);
