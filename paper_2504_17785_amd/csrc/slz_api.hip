@@ -272,7 +272,6 @@ extern "C" int slz_keyswitch_batch_prepared(slz_ctx *ctx, const uint64_t *lwe_in
     if (misaligned8(lwe_in_dev) || misaligned(ksk_prepared_dev) || misaligned8(lwe_out_dev)) return SLZ_E_INVALID_ARG;
     const slz_params &p = ctx->prm;
     if (slz_ksm_prepared_bytes(&p) == 0) return SLZ_E_UNSUPPORTED;
-    slz_ks_init_launch(lwe_in_dev, lwe_out_dev, p.k * p.N, p.n, batch, (hipStream_t)hip_stream);
     return slz_ksm_launch(ctx, lwe_in_dev, nullptr, ksk_prepared_dev, lwe_out_dev, batch, (hipStream_t)hip_stream);
 }
 

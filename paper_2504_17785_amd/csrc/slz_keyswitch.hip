@@ -102,7 +102,6 @@ int slz_keyswitch_launch(slz_ctx *ctx, const uint64_t *lwe_in, const uint64_t *k
     const uint32_t kN = p.k * p.N, n = p.n;
     if (p.ks_level > KS_MAX_L || p.ks_base_log > 31) return SLZ_E_UNSUPPORTED;
     static_assert(KS_THREADS == KS_TB * KS_IC, "one mask word per thread in the decomposition step");
-    slz_ks_init_launch(lwe_in, lwe_out, kN, n, batch, s);
     // digits of at most a byte: int8 MFMA contraction.  Measured faster than the scalar kernel below at every batch size,
     // one ciphertext included, except for a handful of ciphertexts against a key of HBM-streaming size (1.3 GB at
     // n = 1024, N = 32768: 0.33 ms against 0.27 ms), where the scalar kernel's plain row streaming wins.
@@ -111,6 +110,7 @@ int slz_keyswitch_launch(slz_ctx *ctx, const uint64_t *lwe_in, const uint64_t *k
         int rc = slz_ksm_launch(ctx, lwe_in, ksk, nullptr, lwe_out, batch, s);
         if (rc != SLZ_E_UNSUPPORTED) return rc;
     }
+    slz_ks_init_launch(lwe_in, lwe_out, kN, n, batch, s);
     uint32_t xt = (n + 1 + KS_THREADS - 1) / KS_THREADS, ct = (batch + KS_TB - 1) / KS_TB;
     // enough segments of the mask index to give the 256 CUs several workgroups each
     uint32_t segs = 1;

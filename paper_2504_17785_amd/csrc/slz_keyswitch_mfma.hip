@@ -117,7 +117,10 @@ struct ksm_args {
     const uint64_t *ksk;
     const v4i *kskp;        // prepared key (k_ksk_prepare) or null
     const v4i *dig;
+    const uint64_t *lwe_in; // this chunk's input ciphertexts (for the bodies when direct)
     uint64_t *out;
+    uint32_t direct;        // one segment: a workgroup owns its output words and stores (0, b') - sum itself; otherwise
+                            // `out` already holds (0, b') and the segments are combined with atomics
     uint32_t kN, n, l, batch;
     uint32_t n_tiles;       // 32-ciphertext tiles in dig
     uint32_t n_kb;          // 32-row blocks in total (l kN / 32)
@@ -276,7 +279,12 @@ k_ksm_main(ksm_args A) {
             uint64_t val = 0;
 #pragma unroll
             for (int p = 0; p < 8; p++) val += (uint64_t)(int64_t)acc[p][r] << (8 * p);
-            atomicAdd((unsigned long long *)&A.out[(size_t)c * width + x], (unsigned long long)(0 - val));
+            if (A.direct) {
+                const uint64_t base = x == A.n ? A.lwe_in[(size_t)c * (A.kN + 1) + A.kN] : 0ull;
+                A.out[(size_t)c * width + x] = base - val;
+            } else {
+                atomicAdd((unsigned long long *)&A.out[(size_t)c * width + x], (unsigned long long)(0 - val));
+            }
         }
     }
 }
@@ -290,8 +298,7 @@ void slz_ksm_destroy(slz_ctx *ctx) {
     ctx->ks_dig = nullptr;
 }
 
-// The launches of one keyswitch given its digit scratch (`dig`: room for max_tiles 32-ciphertext tiles).  `lwe_out` must
-// already hold (0, .., 0, b').
+// The launches of one keyswitch given its digit scratch (`dig`: room for max_tiles 32-ciphertext tiles).
 static int ksm_run(const slz_params &p, void *dig, uint32_t max_tiles, const uint64_t *lwe_in, const uint64_t *ksk, const void *kskp,
                    uint64_t *lwe_out, uint32_t batch, hipStream_t s) {
     const uint32_t kN = p.k * p.N;
@@ -323,6 +330,9 @@ static int ksm_run(const slz_params &p, void *dig, uint32_t max_tiles, const uin
         if (total > (1u << 30)) return SLZ_E_UNSUPPORTED;
         A.total = (uint32_t)total;
         A.per_xcd = (A.total + 7) / 8;
+        A.lwe_in = lwe_in + (size_t)c0 * (kN + 1);
+        A.direct = segs == 1;
+        if (!A.direct) slz_ks_init_launch(A.lwe_in, A.out, kN, p.n, nb, s);
         hipLaunchKernelGGL(k_ksm_digits, dim3((kN + KD_WORDS - 1) / KD_WORDS, A.n_tiles), dim3(256), 0, s,
                            lwe_in + (size_t)c0 * (kN + 1), (v4i *)dig, kN, p.ks_base_log, p.ks_level, nb, n_kb);
         if (kskp) hipLaunchKernelGGL(k_ksm_main<true>, dim3(A.per_xcd * 8), dim3(KM_THREADS), 0, s, A);
@@ -351,7 +361,7 @@ int slz_ksm_prepare(slz_ctx *ctx, const uint64_t *ksk, void *dst, hipStream_t s)
     return SLZ_OK;
 }
 
-// `lwe_out` must already hold (0, .., 0, b').  Exactly one of ksk (standard form) and kskp (operand form) is given.
+// Exactly one of ksk (standard form) and kskp (operand form) is given.  Writes every word of lwe_out.
 int slz_ksm_launch(slz_ctx *ctx, const uint64_t *lwe_in, const uint64_t *ksk, const void *kskp, uint64_t *lwe_out, uint32_t batch,
                    hipStream_t s) {
     const slz_params &p = ctx->prm;
@@ -392,7 +402,6 @@ extern "C" int slz_keyswitch_batch_static(slz_ctx *ctx, const uint64_t *lwe_in_d
         scratch_ptr[dev] = ptr;
     }
     hipStream_t s = (hipStream_t)hip_stream;
-    slz_ks_init_launch(lwe_in_dev, lwe_out_dev, p.k * p.N, p.n, batch, s);
     // every digit slot of the tiles in use is rewritten by k_ksm_digits (ciphertexts past the batch get zeros), so the
     // contents the previous call left behind are never read
     return ksm_run(p, scratch_ptr[dev], (uint32_t)tiles, lwe_in_dev, ksk_dev, nullptr, lwe_out_dev, batch, s);
