@@ -67,8 +67,22 @@ def test_null_context_calls_are_errors_not_crashes():
     assert L.slz_lwe_lincomb_batch(None, None, None, None, 0, 0, 0, None) == -1
     need = ctypes.c_size_t(0)
     assert L.slz_bsk_prepare(None, None, None, ctypes.byref(need), None) == -1
+    assert L.slz_ksk_prepare(None, None, None, ctypes.byref(need), None) == -1
+    assert L.slz_keyswitch_batch_prepared(None, None, None, None, 0, None) == -1
+    assert L.slz_keyswitch_batch_static(None, None, None, None, 0, None) == -1
     out = ctypes.c_void_p()
     assert L.slz_ctx_create(None, 1, ctypes.byref(out)) == -1
+
+
+def test_bench_refuses_more_than_one_gpu():
+    # one GPU per box: the bench says so instead of launching anything (no GPU is touched before the check)
+    import os
+    import subprocess
+    import sys
+    root = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+    r = subprocess.run([sys.executable, os.path.join(root, "bench.py"), "--gpus", "2"], capture_output=True, text=True, timeout=300)
+    assert r.returncode != 0
+    assert "one GPU" in r.stderr and r.stdout.strip() == ""
 
 
 def test_matmul_rns_luts_match_oracle_tables(orc):
