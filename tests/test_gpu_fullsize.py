@@ -219,3 +219,41 @@ def test_config3_full_depth_decrypts_and_late_steps_match_oracle(slz, orc):
         assert np.array_equal(acc, after[i][q]), (i, int(sample[q]))
     # the accumulator after the last step is what the bootstrapping extracted from
     assert np.array_equal(big_h[sample], np.stack([orc.sample_extract(p, a) for a in after[1023]]))
+
+
+def test_config3_whole_rotation_matches_the_stored_oracle_result(slz):
+    # All 1024 CMux steps at N = 32768 and the sample extraction, bit for bit, on six ciphertexts of the full batch of 256
+    # (default two-stream mode; uniform key and ciphertext words).  The oracle needs about two core-hours per ciphertext for
+    # this, so its result is stored: tests/golden/config3_full_depth.txt, written by tests/golden/make_config3_full_depth.py,
+    # which calls only the oracle and the input generators.
+    import hashlib
+    import os
+    p = synth.CONFIGS[3]
+    batch = p.batch
+    rows = []
+    stored = os.path.join(os.path.dirname(os.path.abspath(__file__)), "golden", "config3_full_depth.txt")
+    if not os.path.exists(stored):
+        pytest.skip("tests/golden/config3_full_depth.txt has not been generated (tests/golden/make_config3_full_depth.py)")
+    with open(stored) as fh:
+        for line in fh:
+            if not line.startswith("#") and line.strip():
+                f = line.split()
+                rows.append((int(f[0]), f[1], [int(x, 16) for x in f[2:6]]))
+    assert len(rows) == 6
+    R, C = (p.k + 1) * p.pbs_level, p.k + 1
+    bsk = synth.raw_words(p, "raw_bsk", p.n * R * C * p.N).reshape(p.n, p.k + 1, p.pbs_level, C, p.N)
+    cts = synth.raw_words(p, "raw_ct", batch * (p.n + 1)).reshape(batch, p.n + 1)
+    luts = slz.lut_encode(p, synth.config_tables(3))
+    ctx = slz.Context(p, batch)
+    assert ctx.path == "three_pass_large_n"
+    d_std = slz.to_device_u64(bsk)
+    del bsk
+    d_bsk = ctx.bsk_prepare(d_std)
+    torch.cuda.synchronize()
+    del d_std
+    d_idx = torch.from_numpy(synth.config_lut_idx(3).astype(np.int32)).cuda()
+    big = slz.to_host_u64(ctx.pbs_batch(slz.to_device_u64(cts), slz.to_device_u64(luts), d_idx, d_bsk))
+    for c, sha, words in rows:
+        o = np.ascontiguousarray(big[c]).astype("<u8")
+        assert [int(o[0]), int(o[1]), int(o[-2]), int(o[-1])] == words, "ciphertext %d" % c
+        assert hashlib.sha256(o.tobytes()).hexdigest() == sha, "ciphertext %d" % c
