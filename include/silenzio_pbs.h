@@ -86,8 +86,11 @@ typedef struct slz_ctx slz_ctx;   /* opaque: parameter copy, twiddle tables, scr
                                      0 keeps the throughput kernels at every batch size; SLZ_E_INVALID_ARG without a large-N path */
 
 #define SLZ_OPT_FUSED_PACING 6    /* value 1 (default) or 0: the N = 2048 fused kernel's workgroups wait for each other between
-                                     ciphertexts (launches of more than 1024 ciphertexts; a wait as long as the waiting workgroup's own ciphertext took ends the pacing for that launch) so that they keep reading the
-                                     same key rows from the L2; 0 lets them run free.  Results are identical.  SLZ_E_INVALID_ARG on other paths */
+                                     ciphertexts (launches of more than 1024 ciphertexts) so that they keep reading the same key
+                                     rows from the L2; a wait as long as the waiting workgroup's own ciphertext took ends the
+                                     pacing for that launch; 0 lets them run free.  Value 2 (for tests of that give-up path):
+                                     paced, but a wait that is not satisfied at once gives up.  Results are identical in
+                                     every mode.  SLZ_E_INVALID_ARG on other paths */
 
 #define SLZ_OPT_FAIL_ALLOC_AFTER 4 /* for tests of the out-of-memory handling: value v >= 0 makes the (v+1)-th scratch allocation
                                      from now (of any context of the process) return SLZ_E_NOMEM without touching the device,

@@ -118,7 +118,7 @@ extern "C" int slz_ctx_set_option(slz_ctx *ctx, int option, int value) {
         return SLZ_E_INVALID_ARG;
     }
     if (option == SLZ_OPT_FUSED_PACING) {
-        if (!ctx->has_fused || (value != 0 && value != 1)) return SLZ_E_INVALID_ARG;
+        if (!ctx->has_fused || value < 0 || value > 2) return SLZ_E_INVALID_ARG;
         ctx->fused_pacing = value;
         return SLZ_OK;
     }

@@ -30,6 +30,7 @@ struct fused_args : slz_fused_io {
     double tw_fwd[2][32];     // fwd[m + blk], m + blk < 32: first five forward stages
     double tw_inv[2][32];     // inv[t + j], t + j < 32: first five inverse stages
     uint32_t *sync;           // [rounds] arrival counters of the pacing between ciphertexts (zeroed before the launch), or null
+    uint32_t patience;        // 0: a pacing wait gives up at once (tests); otherwise it lasts up to the waiter's own round time
 };
 
 #define FUSED_SYNC_SLOTS 4096u        // rounds (ciphertexts per workgroup) one launch can pace
@@ -217,13 +218,15 @@ k_fused_blind_rotate_n2048(fused_args A) {
         }
         __syncthreads();                              // the next ciphertext reuses the LDS buffers
         // Pacing: the workgroups of a launch read the same key rows, and an L2 (4 MiB per XCD) holds the rows of ten to thirty
-        // steps.  Left alone the workgroups drift apart by more than that within a few ciphertexts and most key rows then come from beyond the L2 (measured at 16 384 ciphertexts: 300 times the key's
-        // size per launch; paced: 20 times, which is the eight L2s filling once per round, twice over).  So a workgroup that
-        // has another ciphertext to do waits here until the others have finished this round as well.  A hint, not a
-        // dependency: the first wait that lasts as long as the waiting workgroup's own round did (the two workgroups of a
-        // compute unit do not get equal shares of it, so one may finish well before the other; longer than that means a
-        // workgroup that is not resident, say beside another kernel) switches the pacing off for the rest of the launch.  Run time is the same either way: beyond the L2 the key sits in the
-        // memory-side cache and the loads are issued far enough ahead.
+        // steps.  Left alone the workgroups drift apart by more than that within a few ciphertexts and most key rows then
+        // come from beyond the L2 (measured at 16 384 ciphertexts: 300 times the key's size per launch; paced: 20 times,
+        // which is the eight L2s filling once per round, twice over).  So a workgroup that has another ciphertext to do
+        // waits here until the others have finished this round as well.  A hint, not a dependency: the first wait that
+        // lasts as long as the waiting workgroup's own round did (the two workgroups of a compute unit do not get equal
+        // shares of it, so one may finish well before the other; longer than that means a workgroup that is not resident,
+        // say beside another kernel) switches the pacing off for the rest of the launch.  Run time is the same either way:
+        // beyond the L2 the key sits in the memory-side cache and the loads are issued far enough ahead.
+        // A.patience == 0 (tests of the give-up path): the first wait that is not satisfied at once gives up.
         if (A.sync) {
             const bool more = c + gridDim.x < A.batch;
             if (threadIdx.x == 0) {
@@ -231,7 +234,7 @@ k_fused_blind_rotate_n2048(fused_args A) {
                 const uint32_t here = min(gridDim.x, A.batch - round * gridDim.x);       // workgroups with a ciphertext in this round
                 __hip_atomic_fetch_add(&A.sync[round], 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
                 if (more && !__hip_atomic_load(&A.sync[FUSED_SYNC_SLOTS], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT)) {
-                    const long long t0 = wall_clock64(), limit = t0 - t_round;
+                    const long long t0 = wall_clock64(), limit = A.patience ? t0 - t_round : 0;
                     while (__hip_atomic_load(&A.sync[round], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) < here) {
                         if (wall_clock64() - t0 >= limit) {
                             __hip_atomic_store(&A.sync[FUSED_SYNC_SLOTS], 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
@@ -301,6 +304,7 @@ int slz_fused_blind_rotate(slz_ctx *ctx, const uint64_t *lwe_in, const uint64_t 
     const uint32_t grid = slz_fused_grid(batch, 2);    // two workgroups (68 KiB of LDS each) per compute unit
     const uint32_t rounds = (batch + grid - 1) / grid;
     A.sync = nullptr;
+    A.patience = ctx->fused_pacing == 2 ? 0u : 1u;
     if (rounds > 2 && rounds <= FUSED_SYNC_SLOTS && ctx->fused_pacing) {   // counters cleared by a kernel (safe under graph capture)
         hipLaunchKernelGGL(k_fused_zero_sync, dim3((rounds + 255) / 256), dim3(256), 0, s, ctx->fused_sync, rounds);
         A.sync = ctx->fused_sync;

@@ -455,8 +455,14 @@ def test_fused_pacing_between_ciphertexts_changes_nothing(slz, orc):
     assert np.array_equal(paced, free) and np.array_equal(again, free) and np.array_equal(small, free[:300])
     idx = np.array([0, 511, 512, 1023, 1024, 1099])
     assert np.array_equal(paced[idx], orc.pbs_batch(p, case.cts[idx], case.luts, case.lut_idx[idx], case.keys.bsk))
+    # the give-up path: paced, but the first wait that is not satisfied at once switches the pacing off for the launch
+    ctx.set_option(slz.SLZ_OPT_FUSED_PACING, 2)
+    gave_up = slz.to_host_u64(ctx.pbs_batch(case.d_cts, case.d_luts, case.d_idx, case.d_bsk))
+    ctx.set_option(slz.SLZ_OPT_FUSED_PACING, 1)
+    after = slz.to_host_u64(ctx.pbs_batch(case.d_cts, case.d_luts, case.d_idx, case.d_bsk))
+    assert np.array_equal(gave_up, free) and np.array_equal(after, free)
     with pytest.raises(slz.SlzError):
-        ctx.set_option(slz.SLZ_OPT_FUSED_PACING, 2)
+        ctx.set_option(slz.SLZ_OPT_FUSED_PACING, 3)
     with pytest.raises(slz.SlzError):
         slz.Context(tiny(), 4).set_option(slz.SLZ_OPT_FUSED_PACING, 1)      # not the N = 2048 fused path
 
