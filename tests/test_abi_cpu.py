@@ -173,3 +173,18 @@ def test_headers_are_plain_c():
         r = subprocess.run([gcc, "-std=c99", "-Wall", "-Wextra", "-pedantic", "-Werror", "-fsyntax-only", "-x", "c", os.path.join(inc, h)],
                            capture_output=True, text=True)
         assert r.returncode == 0, r.stderr
+
+
+def test_stored_traffic_figures_belong_to_the_current_kernel_sources():
+    # bench.py reports a stored FETCH_SIZE / WRITE_SIZE figure only when the kernel's sources still hash to the value recorded
+    # with it; a line that has gone stale is dropped silently there, so it is caught here
+    import os
+    import sys
+    root = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+    sys.path.insert(0, root)
+    import bench
+    rows = [l.split() for l in open(os.path.join(root, "profiles", "hbm_traffic.txt")) if l.strip() and not l.startswith("#")]
+    assert len(rows) >= 3
+    for path, workload, fetch, write, commit, digest in rows:
+        assert bench.kernel_source_hash(path) == digest, "%s %s: re-measure and update profiles/hbm_traffic.txt" % (path, workload)
+        assert bench.stored_traffic(path, workload) == float(fetch) + float(write)
