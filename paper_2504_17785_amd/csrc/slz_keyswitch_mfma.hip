@@ -82,8 +82,7 @@ k_ksm_digits(const uint64_t *__restrict__ lwe_in, v4i *__restrict__ dig, uint32_
 // blocks past the last row (the block count is padded to a multiple of 2 KM_IT_KB) are zero.  One iteration of a
 // workgroup (KM_IT_KB blocks of one x tile) is KM_BUF_V4 consecutive entries, in the order of its LDS buffer.
 #define KM_KB_PAD (2 * KM_IT_KB)
-static inline uint32_t ksm_padded_blocks(uint32_t n_kb) { return (n_kb + KM_KB_PAD - 1) / KM_KB_PAD * KM_KB_PAD; }
-__device__ __forceinline__ uint32_t ksm_padded_blocks_dev(uint32_t n_kb) { return (n_kb + KM_KB_PAD - 1) / KM_KB_PAD * KM_KB_PAD; }
+__host__ __device__ static inline uint32_t ksm_padded_blocks(uint32_t n_kb) { return (n_kb + KM_KB_PAD - 1) / KM_KB_PAD * KM_KB_PAD; }
 
 __global__ void __launch_bounds__(256)
 k_ksk_prepare(const uint64_t *__restrict__ ksk, v4i *__restrict__ out, uint32_t kN, uint32_t n, uint32_t l, uint32_t n_kb,
@@ -181,7 +180,7 @@ k_ksm_main(ksm_args A) {
     v4i an0[KM_IT_KB], an1[KM_IT_KB];
     // operand form: the iteration's KM_BUF_V4 entries are consecutive; a thread moves entries tid + KM_THREADS u (the same
     // eight registers hold them as four 16-byte values)
-    const uint32_t kb_pad = ksm_padded_blocks_dev(A.n_kb);
+    const uint32_t kb_pad = ksm_padded_blocks(A.n_kb);
     const v4i *pkey = PREP ? A.kskp + (size_t)xt * kb_pad * (2 * 8 * 32) + threadIdx.x : nullptr;
     auto load_key = [&](uint64_t (&kw)[8], bool &ok, uint32_t it) {
         if (PREP) {
