@@ -789,6 +789,30 @@ def test_large_n_worst_case_magnitudes(slz, orc, block):
     assert np.array_equal(got, want)
 
 
+def test_largest_polynomial_size_matches_oracle(slz, orc):
+    # N = 65536 = 32 blocks of 2048: the largest polynomial the library takes (the 11-bit lookups of the loss gadgets run at
+    # it).  One oracle CMux of this size is 3.4e10 multiply-adds, so: two steps (the second one on dense accumulators),
+    # three ciphertexts, uniform key words.
+    p = tiny(n=2, N=65536, k=1, pbs_base_log=15, pbs_level=2, msg_bits=11)
+    batch = 3
+    R, C = (p.k + 1) * p.pbs_level, p.k + 1
+    bsk = synth.raw_words(p, "raw_bsk", p.n * R * C * p.N).reshape(p.n, p.k + 1, p.pbs_level, C, p.N)
+    cts = synth.raw_words(p, "raw_ct", batch * (p.n + 1)).reshape(batch, p.n + 1)
+    luts = orc.lut_encode(p, synth.random_tables(p, 2))
+    lut_idx = np.array([0, 1, 0], dtype=np.uint32)
+    ctx = slz.Context(p, batch)
+    assert ctx.path == "three_pass_large_n"
+    d_bsk = ctx.bsk_prepare(slz.to_device_u64(bsk))
+    d_cts, d_luts = slz.to_device_u64(cts), slz.to_device_u64(luts)
+    d_idx = torch.from_numpy(lut_idx.astype(np.int32)).cuda()
+    want = orc.blind_rotate_batch(p, cts, luts, lut_idx, bsk, 2)
+    got = slz.to_host_u64(ctx.blind_rotate_batch(d_cts, d_luts, d_idx, d_bsk, 2))
+    assert np.array_equal(got, want)
+    big = slz.to_host_u64(ctx.pbs_batch(d_cts, d_luts, d_idx, d_bsk))
+    assert np.array_equal(big, np.stack([orc.sample_extract(p, a) for a in want]))
+    assert slz.Context(tiny(n=2, N=131072, k=1, pbs_base_log=15, pbs_level=2), 1).path == "generic"     # one size up
+
+
 def test_large_n_two_lanes_match_one_lane_and_oracle(slz, orc):
     # 70 ciphertexts at N = 16384: chunks of 64 + 6 on two internal streams (the default) against one chunk at a time
     p = tiny(n=2, N=16384, k=1, pbs_base_log=15, pbs_level=1)
